@@ -1,0 +1,8 @@
+"""CPU oracle (test infrastructure only).  See prom_oracle.c for what it computes.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package; the HIP product path never does.
+"""
+from .prom_oracle import (  # noqa: F401
+    build, requant, pw_accum, pw_conv, dw_conv, block, max_threads, set_threads,
+)
