@@ -1,0 +1,159 @@
+/*
+ * prom.h -- C ABI of the MI355X (gfx950) ternary pointwise-convolution library.
+ *
+ * The operations are the inference hot path of PROM (arXiv 2505.03254):
+ *   - a pointwise 1x1 convolution whose weights are ternary {-1,0,+1}, so that every
+ *     output is a signed sum of int8 input channels (paper Section 2, last paragraph;
+ *     Section 3.1 "Pointwise Convolutions"; Figure 12, inference branch), followed by a
+ *     per-output-channel rescale (Section 3.1: "scaled by alpha afterwards"; Figure 12:
+ *     dequantise after the convolution), here in integer form;
+ *   - the int8 depthwise 3x3 convolution that sits between two pointwise convolutions
+ *     (Section 2, first paragraph; Section 3.1 "Depthwise Convolutions", Eq. 4-5);
+ *   - the block expand -> depthwise -> project with optional skip (Section 2; Figure 4).
+ *
+ * Conventions shared by every entry point
+ *   Layout      activations are int8 NHWC, dense (no strides); a pointwise layer sees them
+ *               as a row-major [M = n*h*w][C] matrix.
+ *   Memory      "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *               addresses.  The caller owns every buffer.  The library allocates nothing,
+ *               frees nothing and never synchronises: kernels are enqueued on `stream`
+ *               (a hipStream_t passed as void*, NULL = the default stream) and the call
+ *               returns immediately.
+ *   Requant     with acc the int32 accumulator of output channel c,
+ *                   s = acc + bias[c]
+ *                   q = floor( s * mult[c] / 2^(31 + shift[c]) + 1/2 )   (one rounding,
+ *                                                                  ties toward +infinity)
+ *                   y = min(max(q, act_min), act_max)
+ *                   if a residual is given:  y = min(max(y + residual, -128), 127)
+ *               The paper rescales in floating point (Figure 12); this integer form with
+ *               bias (folded BatchNorm shift), Q31 multiplier and shift is the contract of
+ *               this library.  Preconditions (not checked, the arrays live on the device):
+ *               0 < mult[c] < 2^31, 0 <= shift[c] <= 31, and |acc + bias[c]| < 2^31.
+ *   Errors      every int-returning function returns PROM_OK (0) or a negative code; on
+ *               error nothing has been enqueued.
+ */
+#ifndef PROM_H
+#define PROM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PROM_OK = 0,
+    PROM_EINVAL = -1,        /* null pointer, non-positive dimension, bad window or stride    */
+    PROM_EUNSUPPORTED = -2,  /* shape beyond a compiled limit (see each function)             */
+    PROM_EALIAS = -3,        /* output overlaps an input it must not overlap                  */
+    PROM_EWORKSPACE = -4,    /* workspace missing or too small                                */
+    PROM_EHIP = -5,          /* the HIP runtime reported an error at launch                   */
+    PROM_EVALUE = -6         /* prom_pack_ternary: a weight outside {-1,0,+1}                 */
+};
+
+/* Per-output-channel requantisation and activation window.  The struct itself is read on
+ * the host at call time; its three arrays are device memory of C int32 values each. */
+typedef struct {
+    const int32_t *bias;     /* dev [C]                                                       */
+    const int32_t *mult;     /* dev [C]  Q31 multiplier, 2^30 <= mult < 2^31 for a normalised
+                                          scale (any 0 < mult < 2^31 is computed exactly)     */
+    const int32_t *shift;    /* dev [C]  extra right shift, 0..31                             */
+    int32_t act_min;         /* -128 <= act_min <= act_max <= 127; [0,127] is ReLU6 when the  */
+    int32_t act_max;         /*  output scale maps 6.0 to 127                                 */
+} prom_requant_t;
+
+/* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default". */
+typedef struct {
+    int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..12)       */
+    int32_t pixel_tiles;     /* PT: 16-pixel tiles a wavefront processes per iteration (1,2,4)*/
+    int32_t workgroups;      /* workgroups launched per output-channel chunk                  */
+    int32_t reserved;
+} prom_pw_plan_t;
+
+/* ---- ternary weight packing (host side, once per layer: the paper notes that weights are
+ * quantised and fixed in advance, Figure 12) ------------------------------------------- */
+
+/* Bytes of the packed form of a [cout][cin] ternary matrix: 2 bits per weight, each row
+ * padded to a multiple of 16 weights (one 32-bit word per 16 weights). 0 if a dimension is
+ * not positive. */
+size_t prom_packed_size(int cout, int cin);
+
+/* Pack w_host[cout][cin] (row-major int8, every value in {-1,0,+1}) into packed_host.
+ * Codes: 0 -> 00, +1 -> 01, -1 -> 11 (two-bit two's complement); 10 never occurs and padding
+ * weights are 00.  Word j of row c holds weights k = 16j..16j+15 of that row; weight
+ * k = 16j + 4d + b (d, b in 0..3) sits at bits [8b+2d, 8b+2d+1] of the word, so that
+ * (word >> 2d) & 0x03030303 yields the four codes of 32-bit lane d of the decoded 16-byte
+ * group.  Returns PROM_EVALUE for a weight outside {-1,0,+1} (nothing useful is written),
+ * PROM_EWORKSPACE if packed_bytes < prom_packed_size(cout, cin).  Host to host; the caller
+ * copies the result to the device. */
+int prom_pack_ternary(const int8_t *w_host, int cout, int cin, void *packed_host,
+                      size_t packed_bytes);
+
+/* Inverse of prom_pack_ternary (host to host), for round-trip checks and tooling. */
+int prom_unpack_ternary(const void *packed_host, size_t packed_bytes, int cout, int cin,
+                        int8_t *w_host);
+
+/* ---- pointwise 1x1 convolution with ternary weights ------------------------------------
+ * y[m][co] = requant_co( sum_k x[m][k] * W[co][k] ),  m over n*h*w pixels.
+ *   x         dev int8 [n][h][w][cin]
+ *   w_packed  dev, prom_pack_ternary output for [cout][cin], 4-byte aligned
+ *   rq        host struct; arrays dev [cout]
+ *   residual  dev int8 [n][h][w][cout] or NULL; may be the same buffer as y (each element
+ *             is read before it is written)
+ *   y         dev int8 [n][h][w][cout]; must not overlap x or w_packed
+ * Limits: cin <= 4096 (PROM_EUNSUPPORTED above).  n*h*w*max(cin,cout) must be < 2^40.
+ * Fast path needs cin % 8 == 0, cout % 4 == 0 and 4-byte aligned x, y, residual; other
+ * shapes run a slower kernel with identical results. */
+int prom_pw_conv(const int8_t *x, int n, int h, int w, int cin,
+                 const void *w_packed, int cout, const prom_requant_t *rq,
+                 const int8_t *residual, int8_t *y, void *stream);
+
+/* Same operation with an explicit launch plan (testing and tuning); plan == NULL is
+ * prom_pw_conv.  PROM_EINVAL if the plan is not realisable for this shape. */
+int prom_pw_conv_ex(const int8_t *x, int n, int h, int w, int cin,
+                    const void *w_packed, int cout, const prom_requant_t *rq,
+                    const int8_t *residual, int8_t *y, const prom_pw_plan_t *plan,
+                    void *stream);
+
+/* Raw int32 accumulators acc[m][co] = sum_k x[m][k] * W[co][k] (no bias, no requant), for
+ * staged checking of the accumulation alone.  acc: dev int32 [n*h*w][cout]. */
+int prom_pw_accum_i32(const int8_t *x, int n, int h, int w, int cin,
+                      const void *w_packed, int cout, int32_t *acc, void *stream);
+
+/* ---- depthwise 3x3 convolution, pad 1, stride 1 or 2 -----------------------------------
+ * acc[n][oy][ox][c] = sum_{i,j in 0..2} x[n][oy*stride+i-1][ox*stride+j-1][c] * w_dw[i][j][c]
+ * with x = 0 outside the image (the paper's quantisers are symmetric: no zero-point), then
+ * the requantisation above.  ho = (h-1)/stride + 1, wo = (w-1)/stride + 1.
+ *   x dev int8 [n][h][w][c];  w_dw dev int8 [3][3][c];  y dev int8 [n][ho][wo][c];
+ *   y must not overlap x. */
+int prom_dw_conv(const int8_t *x, int n, int h, int w, int c,
+                 const int8_t *w_dw, int stride, const prom_requant_t *rq,
+                 int8_t *y, void *stream);
+
+/* ---- inverted-residual block ------------------------------------------------------------
+ * pointwise expand (cin -> chid, rq_expand) -> depthwise 3x3 (stride, rq_dw) ->
+ * pointwise project (chid -> cout, rq_project); if add_residual (requires stride == 1 and
+ * cin == cout) the block input x is added with saturation after the projection's clamp.
+ *   workspace  dev, at least prom_block_workspace_size(...) bytes, 256-byte aligned; holds
+ *              intermediates, contents undefined afterwards
+ *   y          dev int8 [n][ho][wo][cout]; must not overlap x or the workspace */
+int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
+               const void *w_expand_packed, const prom_requant_t *rq_expand,
+               const int8_t *w_dw, const prom_requant_t *rq_dw,
+               const void *w_project_packed, const prom_requant_t *rq_project,
+               int add_residual, void *workspace, size_t workspace_bytes,
+               int8_t *y, void *stream);
+
+size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* Static, human-readable text for a return code. */
+const char *prom_strerror(int code);
+
+/* Text of the HIP runtime error behind the most recent PROM_EHIP on the calling thread. */
+const char *prom_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROM_H */

@@ -1,0 +1,13 @@
+"""MI355X-native ternary pointwise-convolution path of PROM (arXiv 2505.03254).
+
+The product is libprom.so (HIP kernels for gfx950 behind the C ABI of include/prom.h).
+This package is the thin Python binding: it marshals torch tensors (used only as device
+memory and for the current stream) into the C calls.  Nothing is computed in Python and
+there is no fallback: if the library has not been built, every call raises.
+"""
+from .binding import (  # noqa: F401
+    PromError, Requant, PwPlan, library_path, load_library,
+    prom_packed_size, prom_pack_ternary, prom_unpack_ternary,
+    prom_pw_conv, prom_pw_conv_ex, prom_pw_accum_i32, prom_dw_conv,
+    prom_block, prom_block_workspace_size, prom_strerror,
+)

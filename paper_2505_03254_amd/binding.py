@@ -1,0 +1,249 @@
+"""ctypes binding of include/prom.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libprom.so")
+_lib = None
+
+PROM_OK = 0
+
+
+class PromError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = ""
+        if code == -5:
+            detail = " [" + load_library().prom_last_hip_error().decode() + "]"
+        super().__init__(f"{where}: {prom_strerror(code)} (code {code}){detail}")
+
+
+class _RequantC(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("mult", ctypes.c_void_p), ("shift", ctypes.c_void_p),
+                ("act_min", ctypes.c_int32), ("act_max", ctypes.c_int32)]
+
+
+class _PlanC(ctypes.Structure):
+    _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
+                ("workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libprom.so; raises if it has not been built (there is no CPU fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                           f"`python -m paper_2505_03254_amd.build` (needs hipcc)")
+    # The process must hold ONE HIP runtime.  PyTorch ships its own libamdhip64 (same
+    # soname as the system one); importing torch first makes the dynamic loader bind
+    # libprom.so to that copy, so kernels launch on the runtime that owns torch's device
+    # memory and streams.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.prom_packed_size.restype = sz
+    lib.prom_packed_size.argtypes = [ci, ci]
+    lib.prom_pack_ternary.restype = ci
+    lib.prom_pack_ternary.argtypes = [vp, ci, ci, vp, sz]
+    lib.prom_unpack_ternary.restype = ci
+    lib.prom_unpack_ternary.argtypes = [vp, sz, ci, ci, vp]
+    lib.prom_pw_conv.restype = ci
+    lib.prom_pw_conv.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp, vp]
+    lib.prom_pw_conv_ex.restype = ci
+    lib.prom_pw_conv_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp,
+                                    ctypes.POINTER(_PlanC), vp]
+    lib.prom_pw_accum_i32.restype = ci
+    lib.prom_pw_accum_i32.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp]
+    lib.prom_dw_conv.restype = ci
+    lib.prom_dw_conv.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp]
+    lib.prom_block.restype = ci
+    lib.prom_block.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
+                               vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
+                               vp, ctypes.POINTER(_RequantC), ci, vp, sz, vp, vp]
+    lib.prom_block_workspace_size.restype = sz
+    lib.prom_block_workspace_size.argtypes = [ci] * 7
+    lib.prom_strerror.restype = ctypes.c_char_p
+    lib.prom_strerror.argtypes = [ci]
+    lib.prom_last_hip_error.restype = ctypes.c_char_p
+    lib.prom_last_hip_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def prom_strerror(code: int) -> str:
+    return load_library().prom_strerror(int(code)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != PROM_OK:
+        raise PromError(rc, where)
+
+
+@dataclass
+class Requant:
+    """Device int32 tensors bias/mult/shift of one layer plus its activation window."""
+    bias: "torch.Tensor"
+    mult: "torch.Tensor"
+    shift: "torch.Tensor"
+    act_min: int
+    act_max: int
+
+    def _c(self) -> _RequantC:
+        import torch
+        for t in (self.bias, self.mult, self.shift):
+            assert t.dtype == torch.int32 and t.is_contiguous() and t.is_cuda
+        return _RequantC(self.bias.data_ptr(), self.mult.data_ptr(), self.shift.data_ptr(),
+                         int(self.act_min), int(self.act_max))
+
+
+@dataclass
+class PwPlan:
+    tiles_per_wave: int = 0
+    pixel_tiles: int = 0
+    workgroups: int = 0
+
+    def _c(self) -> _PlanC:
+        return _PlanC(self.tiles_per_wave, self.pixel_tiles, self.workgroups, 0)
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_i8(t, name):
+    import torch
+    if not (t.is_cuda and t.dtype == torch.int8 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous int8 device tensor")
+    return t
+
+
+# ---- host-side packing --------------------------------------------------------------------
+def prom_packed_size(cout: int, cin: int) -> int:
+    return int(load_library().prom_packed_size(int(cout), int(cin)))
+
+
+def prom_pack_ternary(w: np.ndarray) -> np.ndarray:
+    """w: int8 [cout][cin] host array with values in {-1,0,1} -> packed bytes (uint8 host array)."""
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    cout, cin = w.shape
+    out = np.zeros(prom_packed_size(cout, cin), dtype=np.uint8)
+    rc = load_library().prom_pack_ternary(w.ctypes.data, cout, cin, out.ctypes.data, out.size)
+    _check(rc, "prom_pack_ternary")
+    return out
+
+
+def prom_unpack_ternary(packed: np.ndarray, cout: int, cin: int) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    w = np.empty((cout, cin), dtype=np.int8)
+    rc = load_library().prom_unpack_ternary(packed.ctypes.data, packed.size, cout, cin, w.ctypes.data)
+    _check(rc, "prom_unpack_ternary")
+    return w
+
+
+# ---- device entry points --------------------------------------------------------------------
+def prom_pw_conv_ex(x, w_packed, cout: int, rq: Requant, residual=None, y=None,
+                    plan: Optional[PwPlan] = None, stream=None):
+    """x: int8 [n,h,w,cin] device; w_packed: uint8 device tensor from prom_pack_ternary."""
+    import torch
+    _dev_i8(x, "x")
+    n, h, w, cin = x.shape
+    if y is None:
+        y = torch.empty((n, h, w, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    if residual is not None:
+        _dev_i8(residual, "residual")
+    rqc = rq._c()
+    planc = plan._c() if plan is not None else None
+    rc = load_library().prom_pw_conv_ex(
+        x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout), ctypes.byref(rqc),
+        residual.data_ptr() if residual is not None else None, y.data_ptr(),
+        ctypes.byref(planc) if planc is not None else None, _stream_ptr(stream))
+    _check(rc, "prom_pw_conv_ex")
+    return y
+
+
+def prom_pw_conv(x, w_packed, cout: int, rq: Requant, residual=None, y=None, stream=None):
+    import torch
+    _dev_i8(x, "x")
+    n, h, w, cin = x.shape
+    if y is None:
+        y = torch.empty((n, h, w, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    if residual is not None:
+        _dev_i8(residual, "residual")
+    rqc = rq._c()
+    rc = load_library().prom_pw_conv(
+        x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout), ctypes.byref(rqc),
+        residual.data_ptr() if residual is not None else None, y.data_ptr(), _stream_ptr(stream))
+    _check(rc, "prom_pw_conv")
+    return y
+
+
+def prom_pw_accum_i32(x, w_packed, cout: int, acc=None, stream=None):
+    import torch
+    _dev_i8(x, "x")
+    n, h, w, cin = x.shape
+    if acc is None:
+        acc = torch.empty((n, h, w, cout), dtype=torch.int32, device=x.device)
+    rc = load_library().prom_pw_accum_i32(x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout),
+                                          acc.data_ptr(), _stream_ptr(stream))
+    _check(rc, "prom_pw_accum_i32")
+    return acc
+
+
+def prom_dw_conv(x, w_dw, stride: int, rq: Requant, y=None, stream=None):
+    """x: int8 [n,h,w,c] device; w_dw: int8 [3,3,c] device."""
+    import torch
+    _dev_i8(x, "x")
+    _dev_i8(w_dw, "w_dw")
+    n, h, w, c = x.shape
+    ho, wo = (h - 1) // stride + 1, (w - 1) // stride + 1
+    if y is None:
+        y = torch.empty((n, ho, wo, c), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    rqc = rq._c()
+    rc = load_library().prom_dw_conv(x.data_ptr(), n, h, w, c, w_dw.data_ptr(), int(stride),
+                                     ctypes.byref(rqc), y.data_ptr(), _stream_ptr(stream))
+    _check(rc, "prom_dw_conv")
+    return y
+
+
+def prom_block_workspace_size(n, h, w, cin, chid, cout, stride) -> int:
+    return int(load_library().prom_block_workspace_size(n, h, w, cin, chid, cout, stride))
+
+
+def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand: Requant,
+               w_dw, rq_dw: Requant, w_project_packed, rq_project: Requant, add_residual: bool,
+               workspace, y=None, stream=None):
+    import torch
+    _dev_i8(x, "x")
+    _dev_i8(w_dw, "w_dw")
+    n, h, w, cin = x.shape
+    ho, wo = (h - 1) // stride + 1, (w - 1) // stride + 1
+    if y is None:
+        y = torch.empty((n, ho, wo, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    e, d, p = rq_expand._c(), rq_dw._c(), rq_project._c()
+    rc = load_library().prom_block(
+        x.data_ptr(), n, h, w, cin, int(chid), int(cout), int(stride),
+        w_expand_packed.data_ptr(), ctypes.byref(e), w_dw.data_ptr(), ctypes.byref(d),
+        w_project_packed.data_ptr(), ctypes.byref(p), int(bool(add_residual)),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), y.data_ptr(),
+        _stream_ptr(stream))
+    _check(rc, "prom_block")
+    return y

@@ -1,0 +1,61 @@
+// Device helpers shared by the HIP kernels: exact requantisation and byte packing.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace prom {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+// 4-byte-aligned views for global accesses whose address is only dword aligned
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
+
+// Bias applied to the rounded quotient before the float->int truncation so that the
+// truncation acts as floor over the whole clamp window (see requant_to_biased).
+constexpr int kQBias = 256;
+
+// Put the wave's double-precision rounding mode to round-toward-minus-infinity (MODE
+// register FP_ROUND bits [3:2]).  Every kernel that calls requant_to_biased executes this
+// first; the kernels use no other f64/f16 arithmetic whose rounding matters.
+__device__ __forceinline__ void set_f64_round_down()
+{
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 2");
+}
+
+// scale = mult * 2^-(31+shift), exact in double (mult has at most 31 significant bits).
+__device__ __forceinline__ double make_scale(int mult, int shift)
+{
+    return __builtin_ldexp((double)mult, -(31 + shift));
+}
+
+// Returns clamp(q, lo, hi) + kQBias where q = floor(s*scale + 1/2) is the exact rounded
+// quotient; lo_b = lo + kQBias, hi_b = hi + kQBias.
+// Why it is exact: (double)s and scale are exact, and 256.5 is exact, so the FMA computes
+// RD(s*scale + 256.5) with a single round-down.  Round-down never crosses an integer
+// (integers of this magnitude are representable), hence floor(RD(v)) == floor(v).  The
+// conversion truncates toward zero, which equals floor for v >= 0; for v < 0 it yields a
+// value <= 0 < lo_b, and the true floor is also below lo_b, so both clamp to lo_b.  Values
+// beyond int32 saturate in the conversion and clamp to hi_b or lo_b likewise.
+__device__ __forceinline__ int requant_to_biased(int s, double scale, int lo_b, int hi_b)
+{
+    const double v = __builtin_fma((double)s, scale, 256.5);
+    const int qe = (int)v;
+    return min(max(qe, lo_b), hi_b);
+}
+
+// Low bytes of four ints -> one dword (a in bits 0..7).
+__device__ __forceinline__ uint32_t pack4_low_bytes(int a, int b, int c, int d)
+{
+    const uint32_t ab = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
+    const uint32_t cd = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+}
+
+// Sign-extended byte i (0..3) of a dword.
+__device__ __forceinline__ int sbyte(uint32_t v, int i)
+{
+    return (int)(v << (24 - 8 * i)) >> 24;
+}
+
+}  // namespace prom

@@ -1,0 +1,89 @@
+// Host-side parts of the C ABI: ternary weight packing and error strings.
+// The packed format is documented at prom_pack_ternary in prom.h.
+#include "prom.h"
+#include "prom_launch.h"
+
+#include <cstring>
+
+namespace {
+inline int words_per_row(int cin) { return (cin + 15) / 16; }
+}  // namespace
+
+extern "C" size_t prom_packed_size(int cout, int cin)
+{
+    if (cout <= 0 || cin <= 0) return 0;
+    return (size_t)cout * (size_t)words_per_row(cin) * sizeof(uint32_t);
+}
+
+extern "C" int prom_pack_ternary(const int8_t *w_host, int cout, int cin, void *packed_host,
+                                 size_t packed_bytes)
+{
+    if (!w_host || !packed_host || cout <= 0 || cin <= 0) return PROM_EINVAL;
+    const size_t need = prom_packed_size(cout, cin);
+    if (packed_bytes < need) return PROM_EWORKSPACE;
+    const size_t total = (size_t)cout * (size_t)cin;
+    for (size_t i = 0; i < total; ++i)
+        if (w_host[i] < -1 || w_host[i] > 1) return PROM_EVALUE;
+    const int kw = words_per_row(cin);
+    unsigned char *out = static_cast<unsigned char *>(packed_host);
+    for (int c = 0; c < cout; ++c) {
+        const int8_t *row = w_host + (size_t)c * cin;
+        for (int j = 0; j < kw; ++j) {
+            uint32_t word = 0;
+            for (int e = 0; e < 16; ++e) {
+                const int k = 16 * j + e;
+                if (k >= cin) break;
+                const uint32_t code = (uint32_t)(row[k]) & 3u;  // 0->00, 1->01, -1->11
+                const int d = e >> 2, b = e & 3;
+                word |= code << (8 * b + 2 * d);
+            }
+            std::memcpy(out + ((size_t)c * kw + j) * 4, &word, 4);
+        }
+    }
+    return PROM_OK;
+}
+
+extern "C" int prom_unpack_ternary(const void *packed_host, size_t packed_bytes, int cout, int cin,
+                                   int8_t *w_host)
+{
+    if (!w_host || !packed_host || cout <= 0 || cin <= 0) return PROM_EINVAL;
+    if (packed_bytes < prom_packed_size(cout, cin)) return PROM_EWORKSPACE;
+    const int kw = words_per_row(cin);
+    const unsigned char *in = static_cast<const unsigned char *>(packed_host);
+    for (int c = 0; c < cout; ++c) {
+        for (int k = 0; k < cin; ++k) {
+            uint32_t word;
+            std::memcpy(&word, in + ((size_t)c * kw + k / 16) * 4, 4);
+            const int e = k & 15, d = e >> 2, b = e & 3;
+            const uint32_t code = (word >> (8 * b + 2 * d)) & 3u;
+            if (code == 2u) return PROM_EVALUE;
+            w_host[(size_t)c * cin + k] = (int8_t)(code == 3u ? -1 : (int)code);
+        }
+    }
+    return PROM_OK;
+}
+
+hipError_t &prom::last_hip_error()
+{
+    static thread_local hipError_t e = hipSuccess;
+    return e;
+}
+
+extern "C" const char *prom_last_hip_error(void)
+{
+    return hipGetErrorString(prom::last_hip_error());
+}
+
+extern "C" const char *prom_strerror(int code)
+{
+    switch (code) {
+    case PROM_OK: return "success";
+    case PROM_EINVAL: return "invalid argument (null pointer, non-positive dimension, bad activation window or stride)";
+    case PROM_EUNSUPPORTED: return "shape beyond a compiled limit";
+    case PROM_EALIAS: return "output buffer overlaps an input";
+    case PROM_EWORKSPACE: return "workspace or output buffer missing or too small";
+    case PROM_EHIP: return "HIP runtime error at kernel launch";
+    case PROM_EVALUE: return "weight value outside {-1,0,+1}";
+    default: return "unknown error code";
+    }
+}

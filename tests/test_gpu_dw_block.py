@@ -1,0 +1,84 @@
+"""Parity of prom_dw_conv and prom_block against the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_dw_layer, make_block, BASELINE_CONFIGS, CONFIG_SEED_BASE
+from gpu_util import assert_same, dev, requant_dev, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2505_03254_amd as P
+    P.load_library()
+    return P
+
+
+DW_SHAPES = [
+    # n, h, w, c, stride
+    (1, 1, 1, 4, 1), (1, 3, 3, 8, 1), (2, 4, 5, 12, 1), (2, 4, 5, 12, 2), (1, 7, 7, 960, 1),
+    (3, 14, 14, 384, 1), (2, 28, 28, 192, 2), (1, 9, 11, 20, 2), (1, 112, 112, 32, 1),
+    (1, 56, 56, 144, 2), (2, 5, 4, 5, 1), (2, 5, 4, 7, 2), (1, 2, 7, 1, 2), (1, 15, 1, 16, 2),
+]
+
+
+@pytest.mark.parametrize("shape", DW_SHAPES)
+def test_dw_shapes(P, shape):
+    torch = torch_cuda()
+    n, h, w, c, stride = shape
+    D = make_dw_layer(5000 + h * 31 + c + stride, n, h, w, c, stride, signed_x=True,
+                      act_window=(-128, 127), shift_range=(4, 10))
+    D.x.reshape(-1)[::29] = -128
+    y = P.prom_dw_conv(dev(D.x), dev(D.weight), stride, requant_dev(P, D))
+    torch.cuda.synchronize()
+    want = oracle.dw_conv(D.x, D.weight, stride, D.bias, D.mult, D.shift, -128, 127)
+    assert_same(y.cpu().numpy(), want, f"dw {shape}")
+
+
+def test_dw_relu6_window(P):
+    torch = torch_cuda()
+    D = make_dw_layer(5100, 4, 28, 28, 192, 1)
+    y = P.prom_dw_conv(dev(D.x), dev(D.weight), 1, requant_dev(P, D))
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), oracle.dw_conv(D.x, D.weight, 1, D.bias, D.mult, D.shift, 0, 127), "dw relu6")
+
+
+def _run_block(P, B):
+    torch = torch_cuda()
+    e, d, p = B.expand, B.dw, B.project
+    ws = torch.empty(P.prom_block_workspace_size(B.n, B.h, B.w, B.cin, B.chid, B.cout, B.stride),
+                     dtype=torch.int8, device="cuda")
+    y = P.prom_block(dev(B.x), B.chid, B.cout, B.stride,
+                     dev(P.prom_pack_ternary(e.weight)), requant_dev(P, e),
+                     dev(d.weight), requant_dev(P, d),
+                     dev(P.prom_pack_ternary(p.weight)), requant_dev(P, p),
+                     B.add_residual, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def _oracle_block(B):
+    e, d, p = B.expand, B.dw, B.project
+    y, _, _ = oracle.block(B.x, (e.weight, e.bias, e.mult, e.shift, e.act_min, e.act_max),
+                           (d.weight, d.bias, d.mult, d.shift, d.act_min, d.act_max),
+                           (p.weight, p.bias, p.mult, p.shift, p.act_min, p.act_max),
+                           B.stride, B.add_residual)
+    return y
+
+
+def test_block_config4_full_output(P):
+    c = BASELINE_CONFIGS[4]
+    B = make_block(CONFIG_SEED_BASE + 4, c["n"], c["h"], c["w"], c["cin"], c["t"], stride=c["stride"])
+    assert B.add_residual
+    assert_same(_run_block(P, B), _oracle_block(B), "config 4")
+
+
+@pytest.mark.parametrize("shape", [(2, 9, 9, 16, 6, 16, 1), (1, 14, 14, 24, 6, 32, 2),
+                                   (2, 7, 7, 160, 6, 320, 1), (1, 5, 6, 8, 1, 8, 1),
+                                   (1, 112, 112, 16, 6, 24, 2)])
+def test_block_shapes(P, shape):
+    n, h, w, cin, t, cout, stride = shape
+    B = make_block(6000 + cin + cout, n, h, w, cin, t, cout, stride, signed_x=True)
+    assert_same(_run_block(P, B), _oracle_block(B), f"block {shape}")

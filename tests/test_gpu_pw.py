@@ -1,0 +1,164 @@
+"""Parity of prom_pw_conv (HIP, through the C ABI) against the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_pw_layer, BASELINE_CONFIGS, CONFIG_SEED_BASE
+from gpu_util import run_pw, oracle_pw, assert_same, dev, requant_dev, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2505_03254_amd as P
+    P.load_library()
+    return P
+
+
+def _cfg_layer(i):
+    c = BASELINE_CONFIGS[i]
+    return make_pw_layer(CONFIG_SEED_BASE + i, c["n"], c["h"], c["w"], c["cin"], c["cout"],
+                         act_window=c["act_window"], with_residual=c["residual"])
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_baseline_configs_full_output(P, cfg):
+    L = _cfg_layer(cfg)
+    assert_same(run_pw(P, L), oracle_pw(oracle, L), f"config {cfg}")
+
+
+EDGE_SHAPES = [
+    # n, h, w, cin, cout  -- ragged pixel counts, channel counts off every tile size
+    (1, 1, 1, 8, 4), (1, 3, 5, 16, 16), (1, 5, 13, 24, 20), (2, 7, 7, 40, 36),
+    (1, 9, 9, 64, 144), (3, 5, 7, 72, 200), (1, 17, 3, 144, 24), (1, 11, 11, 200, 52),
+    (1, 4, 4, 960, 160), (2, 6, 5, 328, 1280), (1, 31, 33, 32, 192), (1, 2, 2, 1024, 8),
+    (1, 13, 7, 4096, 12),
+]
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES)
+@pytest.mark.parametrize("res", [False, True])
+def test_edge_shapes_signed_inputs(P, shape, res):
+    n, h, w, cin, cout = shape
+    L = make_pw_layer(1000 + cin * 7 + cout, n, h, w, cin, cout, signed_x=True,
+                      act_window=(-128, 127) if res else (-20, 90), with_residual=res,
+                      shift_range=(3, 9))
+    L.x.reshape(-1)[::37] = -128
+    assert_same(run_pw(P, L), oracle_pw(oracle, L), f"shape {shape} res={res}")
+
+
+GENERIC_SHAPES = [(1, 3, 3, 3, 5), (1, 5, 7, 17, 7), (2, 4, 4, 1, 1), (1, 6, 6, 24, 5),
+                  (1, 6, 6, 13, 16), (1, 3, 11, 100, 33), (1, 2, 3, 4095, 6)]
+
+
+@pytest.mark.parametrize("shape", GENERIC_SHAPES)
+def test_generic_path_odd_channels(P, shape):
+    n, h, w, cin, cout = shape
+    L = make_pw_layer(2000 + cin * 3 + cout, n, h, w, cin, cout, signed_x=True,
+                      act_window=(-128, 127), with_residual=True, shift_range=(0, 6))
+    assert_same(run_pw(P, L), oracle_pw(oracle, L), f"generic shape {shape}")
+
+
+def test_misaligned_pointers_take_the_generic_path(P):
+    torch = torch_cuda()
+    L = make_pw_layer(2100, 1, 7, 9, 32, 24, signed_x=True, act_window=(-128, 127), with_residual=True)
+    want = oracle_pw(oracle, L)
+    m = 63
+    xbuf = torch.zeros(m * 32 + 8, dtype=torch.int8, device="cuda")
+    ybuf = torch.zeros(m * 24 + 8, dtype=torch.int8, device="cuda")
+    rbuf = torch.zeros(m * 24 + 8, dtype=torch.int8, device="cuda")
+    for off in (1, 2, 3):
+        xv = xbuf[off:off + m * 32].view(1, 7, 9, 32)
+        xv.copy_(dev(L.x))
+        yv = ybuf[off:off + m * 24].view(1, 7, 9, 24)
+        rv = rbuf[off:off + m * 24].view(1, 7, 9, 24)
+        rv.copy_(dev(L.residual))
+        ybuf.fill_(77)
+        P.prom_pw_conv(xv, dev(P.prom_pack_ternary(L.weight)), 24, requant_dev(P, L), rv, yv)
+        torch.cuda.synchronize()
+        assert_same(yv.cpu().numpy(), want, f"offset {off}")
+        assert int(ybuf[off - 1]) == 77 and int(ybuf[off + m * 24]) == 77  # no write outside y
+
+
+@pytest.mark.parametrize("nt", list(range(1, 13)))
+def test_every_tile_plan(P, nt):
+    """Every compiled (tiles per wave, pixel tiles) variant, on shapes whose channel count is
+    not a multiple of the chunk, with both load widths (cin % 16 == 0 and cin % 16 == 8)."""
+    for cin, cout in ((64, 192), (24, 144), (200, 100)):
+        L = make_pw_layer(3000 + nt + cin, 2, 9, 13, cin, cout, signed_x=True,
+                          act_window=(-100, 100), with_residual=(cin == 64))
+        want = oracle_pw(oracle, L)
+        for pt in (1, 2, 4):
+            if pt > (4 if nt <= 2 else 2 if nt <= 6 else 1):
+                continue
+            for wgs in (0, 1, 3):
+                plan = P.PwPlan(nt, pt, wgs)
+                assert_same(run_pw(P, L, plan=plan), want, f"nt={nt} pt={pt} wgs={wgs} cin={cin}")
+
+
+def test_raw_accumulators(P):
+    torch = torch_cuda()
+    for cin, cout in ((64, 384), (24, 144), (17, 5), (960, 160)):
+        L = make_pw_layer(4000 + cin, 1, 7, 9, cin, cout, signed_x=True)
+        acc = P.prom_pw_accum_i32(dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout)
+        torch.cuda.synchronize()
+        assert_same(acc.cpu().numpy(), oracle.pw_accum(L.x, L.weight), f"accum {cin}x{cout}")
+
+
+def test_closed_forms_on_gpu(P):
+    """All-zero weights give the requantised bias; all +1 give row sums."""
+    L = make_pw_layer(4100, 1, 8, 8, 48, 32, signed_x=True, act_window=(-128, 127))
+    L.weight[:] = 0
+    y = run_pw(P, L)
+    assert_same(y, oracle_pw(oracle, L), "zero weights")
+    assert (y == y[0, 0, 0]).all()
+    L.weight[:] = 1
+    assert_same(run_pw(P, L), oracle_pw(oracle, L), "all +1 weights")
+    L.weight[:] = -1
+    assert_same(run_pw(P, L), oracle_pw(oracle, L), "all -1 weights")
+
+
+CRAFTED = [(1 << 30, 8), (1 << 30, 0), ((1 << 31) - 1, 14), ((1 << 30) + 1, 9),
+           (0x5A5A5A5B, 11), (0x7FFFFFFF, 0), (0x40000000, 31), (0x6DB6DB6E, 13), (1, 0), (3, 31)]
+
+
+def test_epilogue_sweep_every_s_and_ties(P):
+    """Identity-like weights turn the layer into a pure epilogue test: s = x + bias[c] sweeps
+    every integer in [-4224, 4223] (and a wide range scaled by 2^k) for crafted (mult, shift),
+    including exact .5 ties."""
+    x = np.tile(np.arange(-128, 128, dtype=np.int16).astype(np.int8).reshape(256, 1), (1, 8))
+    x = np.ascontiguousarray(x).reshape(1, 16, 16, 8)
+    cout = 33 * len(CRAFTED)
+    w = np.zeros((cout, 8), dtype=np.int8)
+    w[:, 0] = 1
+    bias = np.zeros(cout, np.int32); mult = np.zeros(cout, np.int32); shift = np.zeros(cout, np.int32)
+    for i, (m, s) in enumerate(CRAFTED):
+        for b in range(33):
+            c = i * 33 + b
+            bias[c] = -4096 + 256 * b
+            mult[c], shift[c] = m, s
+    L = make_pw_layer(1, 1, 16, 16, 8, cout)
+    L.x, L.weight, L.bias, L.mult, L.shift = x, w, bias, mult, shift
+    for window in ((-128, 127), (0, 127), (-7, 7)):
+        assert_same(run_pw(P, L, window=window), oracle_pw(oracle, L, window=window), f"sweep {window}")
+    # large |s|: biases up to 2^30 in magnitude
+    L.bias = (bias.astype(np.int64) * (1 << 17)).clip(-(1 << 30), 1 << 30).astype(np.int32)
+    assert_same(run_pw(P, L, window=(-128, 127)), oracle_pw(oracle, L, window=(-128, 127)), "large s")
+
+
+def test_residual_may_alias_output(P):
+    torch = torch_cuda()
+    L = make_pw_layer(4200, 2, 7, 7, 96, 40, act_window=(-128, 127), with_residual=True)
+    want = oracle_pw(oracle, L)
+    y = dev(L.residual).clone()
+    P.prom_pw_conv(dev(L.x), dev(P.prom_pack_ternary(L.weight)), 40, requant_dev(P, L), y, y)
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), want, "in-place residual")
+
+
+def test_zero_fraction_variants(P):
+    """Weight zero fractions from the paper's initialisation (31 %) to its trained maximum (55 %)."""
+    for pz in (0.0, 0.31, 0.55, 1.0):
+        L = make_pw_layer(4300, 1, 14, 14, 64, 384, p_zero=pz)
+        assert_same(run_pw(P, L), oracle_pw(oracle, L), f"p_zero={pz}")
