@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the ternary pointwise-convolution path on one MI355X.
+
+A step is one pass over all 34 pointwise layers of MobileNetV2 (width 1.0, 224x224) at batch
+128 -- decode, int8 MFMA accumulation and integer requantisation of every layer -- on
+seeded synthetic int8 NHWC inputs already resident in HBM.  Every layer has its own input and
+output buffers, so between two uses of a buffer the sweep touches ~880 MB (more than the
+256 MB Infinity Cache): the numbers are cache-cold.
+
+Prints ONE JSON line on stdout.  Human-readable per-layer tables go to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+MFMA_I8_PEAK_TOPS = 5000.0  # MI355X dense int8 MFMA, published
+BATCH = 128
+SEED = 0x50524F4D + 300
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_bytes(m, k, nc, residual=False):
+    """Algorithmic HBM bytes of one layer: activations in + out (+ residual), 2-bit weights,
+    12 bytes of requantisation parameters per output channel."""
+    return m * (k + nc) + (m * nc if residual else 0) + ((k + 3) // 4) * nc + 12 * nc
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=BATCH, help="images per layer (metric is quoted at 128)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
+    ap.add_argument("--cpu-sample-images", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU; multi-GPU runs are not part of it "
+              "(the path shards by batch with no communication). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_03254_amd as P
+    from workloads import (make_pw_layer, make_dw_layer, make_block, mobilenetv2_pointwise_layers,
+                           mobilenetv2_depthwise_layers)
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t_setup = time.time()
+
+    # ---- build the workload ----------------------------------------------------------------
+    shapes = mobilenetv2_pointwise_layers()
+    layers = []
+    for i, s in enumerate(shapes):
+        L = make_pw_layer(SEED + i, args.batch, s.hw, s.hw, s.cin, s.cout)
+        x = torch.from_numpy(L.x).to(dev)
+        wp = torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev)
+        rq = P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
+                       torch.from_numpy(L.shift).to(dev), 0, 127)
+        y = torch.empty((args.batch, s.hw, s.hw, s.cout), dtype=torch.int8, device=dev)
+        plan = P.prom_pw_plan_query(args.batch, s.hw, s.hw, s.cin, s.cout)
+        variant = (plan["tiles_per_wave"], plan["pixel_tiles"], plan["load_bytes"])
+        m = args.batch * s.hw * s.hw
+        layers.append(dict(shape=s, L=L, x=x, wp=wp, rq=rq, y=y, plan=plan, variant=variant, m=m,
+                           bytes=layer_bytes(m, s.cin, s.cout), ops=2 * m * s.cin * s.cout))
+    total_ops = sum(l["ops"] for l in layers)
+    total_bytes = sum(l["bytes"] for l in layers)
+    log(f"[bench] workload built in {time.time() - t_setup:.1f}s: {len(layers)} layers, "
+        f"{total_bytes / 1e6:.1f} MB algorithmic, {total_ops / 1e9:.2f} Gop per step")
+
+    # dominant kernel variant = the template instantiation moving the most bytes
+    by_variant = {}
+    for l in layers:
+        by_variant.setdefault(l["variant"], []).append(l)
+    dom_variant = max(by_variant, key=lambda v: sum(l["bytes"] for l in by_variant[v]))
+    dom_name = (f"prom::pw_kernel<{dom_variant[0]}, {dom_variant[1]}, {dom_variant[2]}, false, false>")
+
+    # segments: maximal runs of non-dominant layers, and each dominant layer alone with events
+    segments = []
+    run = []
+    for l in layers:
+        tup = (l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"])
+        if l["variant"] == dom_variant:
+            if run:
+                segments.append((False, P.PwSequence(run), None))
+                run = []
+            segments.append((True, P.PwSequence([tup]), l))
+        else:
+            run.append(tup)
+    if run:
+        segments.append((False, P.PwSequence(run), None))
+    n_dom = sum(1 for s in segments if s[0])
+
+    def one_step(events=None):
+        for is_dom, seq, _ in segments:
+            if is_dom and events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                seq.run()
+                e1.record()
+                events.append((e0, e1))
+            else:
+                seq.run()
+
+    # ---- warmup, then the timed region --------------------------------------------------------
+    for _ in range(max(args.warmup, 1)):
+        one_step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = total_ops / (ms_per_step * 1e-3) / 1e9  # Gop/s
+    dom_ms = [e0.elapsed_time(e1) for e0, e1 in events]
+    dom_avg_us = 1e3 * sum(dom_ms) / len(dom_ms)
+    dom_bytes_per_launch = sum(l["bytes"] for l in by_variant[dom_variant]) / n_dom
+    dom_achieved = dom_bytes_per_launch / (dom_avg_us * 1e-6) / 1e9
+
+    # ---- per-layer table: a separate, instrumented pass (events around every launch) -------
+    per_layer = []
+    seqs = [P.PwSequence([(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"])]) for l in layers]
+    reps = 10
+    acc_ms = [0.0] * len(layers)
+    for _ in range(reps):
+        evs = []
+        for s in seqs:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            s.run()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        for i, (e0, e1) in enumerate(evs):
+            acc_ms[i] += e0.elapsed_time(e1)
+    log(f"{'layer':<13}{'HW':>4}{'Cin':>5}{'Cout':>6} {'plan(NT,PT,ld)':>15} {'us':>8} {'GB/s':>8} "
+        f"{'%HBM':>6} {'Gop/s':>9} {'%MFMA':>6}")
+    for i, l in enumerate(layers):
+        us = acc_ms[i] / reps * 1e3
+        gbs = l["bytes"] / (us * 1e-6) / 1e9
+        gops = l["ops"] / (us * 1e-6) / 1e9
+        s = l["shape"]
+        per_layer.append(dict(layer=s.name, us=round(us, 2), gbs=round(gbs, 1), gops=round(gops, 1)))
+        log(f"{s.name:<13}{s.hw:>4}{s.cin:>5}{s.cout:>6} {str(l['variant']):>15} {us:8.2f} {gbs:8.1f} "
+            f"{100 * gbs / HBM_PEAK_GBS:6.1f} {gops:9.1f} {100 * gops / (MFMA_I8_PEAK_TOPS * 1e3):6.1f}")
+    sum_us = sum(p["us"] for p in per_layer)
+    log(f"sum of per-layer event times: {sum_us:.1f} us  (timed region: {ms_per_step * 1e3:.1f} us/step)")
+
+    # ---- HBM yardstick: the library's plain copy kernel on 512 MB --------------------------
+    nb = 512 << 20
+    src = torch.empty(nb, dtype=torch.uint8, device=dev)
+    dst = torch.empty(nb, dtype=torch.uint8, device=dev)
+    src.random_(0, 255)
+    for _ in range(2):
+        P.prom_copy_bytes(src, dst)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        P.prom_copy_bytes(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    log(f"[bench] copy kernel (512 MB, read+write): {copy_gbs:.0f} GB/s")
+
+    result = {
+        "metric": "ternary pointwise conv Gop/s and % of roofline, MobileNetV2 layers, batch 128",
+        "value": round(value, 1),
+        "unit": "Gop/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "configs[3]: the 34 ternary pointwise layers of MobileNetV2 1.0 (224x224), "
+                               f"batch {args.batch}, int8 NHWC, one launch per layer",
+                   "batch": args.batch, "layers": len(layers)},
+        "sweep": {"algorithmic_bytes": total_bytes, "dense_equiv_ops": total_ops,
+                  "gbs": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                  "frac_hbm_roofline": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "gadd_per_s": round(value / 2, 1),
+                  "sum_layer_event_us": round(sum_us, 1),
+                  "copy_kernel_gbs": round(copy_gbs, 0)},
+        "roofline": {"bound": "hbm", "kernel": dom_name,
+                     "layers": [l["shape"].name for l in by_variant[dom_variant]],
+                     "achieved": round(dom_achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom_achieved / HBM_PEAK_GBS, 4),
+                     "avg_launch_us": round(dom_avg_us, 2),
+                     "bytes_per_launch": int(dom_bytes_per_launch),
+                     "traffic": None},
+        "per_layer": per_layer,
+    }
+
+    # ---- extra legs: depthwise sweep and the fused block of config 4 ---------------------------
+    if not args.no_extra:
+        result["extra"] = extra_legs(P, torch, dev, args.batch, log)
+
+    # ---- CPU baseline: the oracle on a bounded sample, plus a parity check of that sample ------
+    if not args.no_cpu_baseline:
+        import oracle
+        ns = min(args.cpu_sample_images, args.batch)
+        torch.cuda.synchronize()
+        ops = 0
+        t_cpu = 0.0
+        mismatches = 0
+        for l in layers:
+            L, s = l["L"], l["shape"]
+            xs = np.ascontiguousarray(L.x[:ns])
+            tc = time.perf_counter()
+            want = oracle.pw_conv(xs, L.weight, L.bias, L.mult, L.shift, 0, 127)
+            t_cpu += time.perf_counter() - tc
+            ops += 2 * ns * s.hw * s.hw * s.cin * s.cout
+            got = l["y"][:ns].cpu().numpy()
+            mismatches += int((got != want).sum())
+        result["cpu_baseline"] = {"value": round(ops / t_cpu / 1e9, 2), "unit": "Gop/s",
+                                  "cores": oracle.max_threads(), "kind": "oracle",
+                                  "sample": f"first {ns} of {args.batch} images of every layer "
+                                            f"({ops / 1e9:.1f} Gop, {t_cpu:.1f} s)",
+                                  "parity_mismatches_vs_gpu": mismatches}
+        log(f"[bench] oracle: {ops / t_cpu / 1e9:.2f} Gop/s on {oracle.max_threads()} threads; "
+            f"GPU outputs of the sample differ in {mismatches} elements")
+
+    print(json.dumps(result), flush=True)
+
+
+def extra_legs(P, torch, dev, batch, log):
+    """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
+    import numpy as np
+    from workloads import make_dw_layer, make_block, mobilenetv2_depthwise_layers
+    out = {}
+    dws = []
+    for i, d in enumerate(mobilenetv2_depthwise_layers()):
+        D = make_dw_layer(SEED + 1000 + i, 1, d.hw_in, d.hw_in, d.c, d.stride)
+        x = torch.randint(0, 128, (batch, d.hw_in, d.hw_in, d.c), dtype=torch.int8, device=dev)
+        w = torch.from_numpy(D.weight).to(dev)
+        rq = P.Requant(torch.from_numpy(D.bias).to(dev), torch.from_numpy(D.mult).to(dev),
+                       torch.from_numpy(D.shift).to(dev), 0, 127)
+        ho = (d.hw_in - 1) // d.stride + 1
+        y = torch.empty((batch, ho, ho, d.c), dtype=torch.int8, device=dev)
+        dws.append((d, x, w, rq, y, batch * d.c * (d.hw_in ** 2 + ho ** 2)))
+    for _ in range(2):
+        for d, x, w, rq, y, _b in dws:
+            P.prom_dw_conv(x, w, d.stride, rq, y)
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for d, x, w, rq, y, _b in dws:
+            P.prom_dw_conv(x, w, d.stride, rq, y)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    nbytes = sum(b for *_, b in dws)
+    out["depthwise_sweep"] = {"layers": len(dws), "us": round(dt * 1e6, 1),
+                              "gbs": round(nbytes / dt / 1e9, 1),
+                              "frac_hbm_roofline": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    log(f"[bench] depthwise sweep: {dt * 1e6:.1f} us, {nbytes / dt / 1e9:.0f} GB/s")
+    del dws
+
+    B = make_block(SEED + 2000, 64, 28, 28, 32, 6)
+    e, d, p = B.expand, B.dw, B.project
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rqs = [P.Requant(t(l.bias), t(l.mult), t(l.shift), l.act_min, l.act_max) for l in (e, d, p)]
+    ws = torch.empty(P.prom_block_workspace_size(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
+                     dtype=torch.int8, device=dev)
+    # rotate over enough input/output sets that the footprint between reuses exceeds the cache
+    xs = [t(B.x) for _ in range(8)]
+    ys = [torch.empty_like(xs[0]) for _ in range(8)]
+    we, wd, wp = t(P.prom_pack_ternary(e.weight)), t(d.weight), t(P.prom_pack_ternary(p.weight))
+
+    def run(i):
+        P.prom_block(xs[i % 8], B.chid, B.cout, 1, we, rqs[0], wd, rqs[1], wp, rqs[2], True, ws, ys[i % 8])
+    for i in range(8):
+        run(i)
+    torch.cuda.synchronize()
+    reps = 40
+    t0 = time.perf_counter()
+    for i in range(reps):
+        run(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    m = B.n * B.h * B.w
+    compulsory = m * (B.cin + B.cout)
+    out["block_config4"] = {"us": round(dt * 1e6, 1),
+                            "compulsory_gbs": round(compulsory / dt / 1e9, 1),
+                            "pw_gops": round(2 * m * B.cin * B.chid * 2 / dt / 1e9, 1)}
+    log(f"[bench] block (config 4): {dt * 1e6:.1f} us per call")
+    return out
+
+
+if __name__ == "__main__":
+    main()

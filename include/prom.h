@@ -116,6 +116,27 @@ int prom_pw_conv_ex(const int8_t *x, int n, int h, int w, int cin,
                     const int8_t *residual, int8_t *y, const prom_pw_plan_t *plan,
                     void *stream);
 
+/* The launch plan prom_pw_conv would use for this shape (all pointers assumed 4-byte aligned):
+ * fills tiles_per_wave, pixel_tiles, workgroups (per chunk) and, in `reserved`, the activation
+ * load width in bytes (16, 8, or 1 for the slow generic kernel).  Host only, launches nothing. */
+int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out);
+
+/* One layer of a sequence for prom_pw_conv_sequence: the arguments of prom_pw_conv. */
+typedef struct {
+    const int8_t *x;
+    int32_t n, h, w, cin;
+    const void *w_packed;
+    int32_t cout;
+    prom_requant_t rq;
+    const int8_t *residual;
+    int8_t *y;
+} prom_pw_layer_t;
+
+/* Enqueue `count` pointwise layers back to back on `stream` (one host call instead of
+ * `count`).  All layers are validated first; on any error nothing is enqueued and the index
+ * of the offending layer is stored in *bad_layer when bad_layer is not NULL. */
+int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream);
+
 /* Raw int32 accumulators acc[m][co] = sum_k x[m][k] * W[co][k] (no bias, no requant), for
  * staged checking of the accumulation alone.  acc: dev int32 [n*h*w][cout]. */
 int prom_pw_accum_i32(const int8_t *x, int n, int h, int w, int cin,
@@ -146,6 +167,12 @@ int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout
                int8_t *y, void *stream);
 
 size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* ---- measurement utility ------------------------------------------------------------------
+ * Plain streaming copy of nbytes (multiple of 16, both pointers 16-byte aligned) from src to
+ * dst, dev to dev, as a kernel of this library: the HBM-bandwidth yardstick the pointwise
+ * kernel is compared with, and the known-size reference for scaling hardware byte counters. */
+int prom_copy_bytes(const void *src, void *dst, size_t nbytes, void *stream);
 
 /* Static, human-readable text for a return code. */
 const char *prom_strerror(int code);

@@ -29,6 +29,13 @@ class _RequantC(ctypes.Structure):
                 ("act_min", ctypes.c_int32), ("act_max", ctypes.c_int32)]
 
 
+class _PwLayerC(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("n", ctypes.c_int32), ("h", ctypes.c_int32),
+                ("w", ctypes.c_int32), ("cin", ctypes.c_int32), ("w_packed", ctypes.c_void_p),
+                ("cout", ctypes.c_int32), ("rq", _RequantC), ("residual", ctypes.c_void_p),
+                ("y", ctypes.c_void_p)]
+
+
 class _PlanC(ctypes.Structure):
     _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
                 ("workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
@@ -74,6 +81,12 @@ def load_library():
                                vp, ctypes.POINTER(_RequantC), ci, vp, sz, vp, vp]
     lib.prom_block_workspace_size.restype = sz
     lib.prom_block_workspace_size.argtypes = [ci] * 7
+    lib.prom_pw_plan_query.restype = ci
+    lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC)]
+    lib.prom_pw_conv_sequence.restype = ci
+    lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_copy_bytes.restype = ci
+    lib.prom_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.prom_strerror.restype = ctypes.c_char_p
     lib.prom_strerror.argtypes = [ci]
     lib.prom_last_hip_error.restype = ctypes.c_char_p
@@ -247,3 +260,52 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
         _stream_ptr(stream))
     _check(rc, "prom_block")
     return y
+
+
+def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:
+    """Launch plan the library picks for a shape: tiles per wave, pixel tiles, workgroups per
+    chunk and activation load width."""
+    p = _PlanC()
+    _check(load_library().prom_pw_plan_query(n, h, w, cin, cout, ctypes.byref(p)), "prom_pw_plan_query")
+    return {"tiles_per_wave": p.tiles_per_wave, "pixel_tiles": p.pixel_tiles,
+            "workgroups": p.workgroups, "load_bytes": p.reserved}
+
+
+class PwSequence:
+    """A prebuilt array of prom_pw_layer_t; run() enqueues all layers with one C call.
+    Keeps references to every tensor it points at."""
+
+    def __init__(self, layers):
+        """layers: iterable of (x, w_packed, cout, Requant, residual_or_None, y) device tensors."""
+        layers = list(layers)
+        self._keep = layers
+        self._arr = (_PwLayerC * len(layers))()
+        for i, (x, wp, cout, rq, res, y) in enumerate(layers):
+            _dev_i8(x, "x")
+            _dev_i8(y, "y")
+            n, h, w, cin = x.shape
+            c = self._arr[i]
+            c.x, c.n, c.h, c.w, c.cin = x.data_ptr(), n, h, w, cin
+            c.w_packed, c.cout, c.rq = wp.data_ptr(), int(cout), rq._c()
+            c.residual = res.data_ptr() if res is not None else None
+            c.y = y.data_ptr()
+        self.count = len(layers)
+
+    def run(self, stream=None):
+        bad = ctypes.c_int(-1)
+        rc = load_library().prom_pw_conv_sequence(self._arr, self.count, ctypes.byref(bad),
+                                                  _stream_ptr(stream))
+        if rc != PROM_OK:
+            raise PromError(rc, f"prom_pw_conv_sequence (layer {bad.value})")
+
+
+def prom_pw_conv_sequence(layers, stream=None):
+    PwSequence(layers).run(stream)
+
+
+def prom_copy_bytes(src, dst, nbytes: Optional[int] = None, stream=None):
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    _check(load_library().prom_copy_bytes(src.data_ptr(), dst.data_ptr(), int(nbytes),
+                                          _stream_ptr(stream)), "prom_copy_bytes")
+    return dst

@@ -362,33 +362,47 @@ static bool overlaps(const void *p, size_t pn, const void *q, size_t qn)
 
 static int max_pt_for(int nt) { return nt <= 2 ? 4 : (nt <= 6 ? 2 : 1); }
 
-// mode: 0 = requantised int8 output, 1 = raw int32 accumulators
-static int pw_dispatch(const int8_t *x, int n, int h, int w, int cin, const void *w_packed, int cout,
-                       const prom_requant_t *rq, const int8_t *residual, int8_t *y, int32_t *acc_out,
-                       const prom_pw_plan_t *plan, void *stream, int mode)
+struct PwLaunch {
+    PwArgs a;
+    int nt, pt, xmode, grid;
+    size_t lds;
+    bool fast;
+    int mode;
+};
+
+// Validate the arguments and fill the launch description.  mode: 0 = requantised int8
+// output, 1 = raw int32 accumulators.  Launches nothing.
+static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void *w_packed, int cout,
+                      const prom_requant_t *rq, const int8_t *residual, int8_t *y, int32_t *acc_out,
+                      const prom_pw_plan_t *plan, int mode, bool shape_only, PwLaunch &L)
 {
-    if (!x || !w_packed || n <= 0 || h <= 0 || w <= 0 || cin <= 0 || cout <= 0) return PROM_EINVAL;
-    if (((uintptr_t)w_packed & 3) != 0) return PROM_EINVAL;
+    if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || cout <= 0) return PROM_EINVAL;
     const long long M = (long long)n * h * w;
-    if (mode == 0) {
-        if (!rq || !rq->bias || !rq->mult || !rq->shift || !y) return PROM_EINVAL;
-        if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
-    } else {
-        if (!acc_out || ((uintptr_t)acc_out & 3) != 0) return PROM_EINVAL;
+    if (!shape_only) {
+        if (!x || !w_packed) return PROM_EINVAL;
+        if (((uintptr_t)w_packed & 3) != 0) return PROM_EINVAL;
+        if (mode == 0) {
+            if (!rq || !rq->bias || !rq->mult || !rq->shift || !y) return PROM_EINVAL;
+            if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
+        } else {
+            if (!acc_out || ((uintptr_t)acc_out & 3) != 0) return PROM_EINVAL;
+        }
     }
     if (cin > kMaxCin) return PROM_EUNSUPPORTED;
     if (M * (long long)(cin > cout ? cin : cout) >= (1LL << 40)) return PROM_EUNSUPPORTED;
-    const size_t xbytes = (size_t)M * cin, ybytes = (size_t)M * cout;
-    const size_t wbytes = prom_packed_size(cout, cin);
-    if (mode == 0) {
-        if (overlaps(y, ybytes, x, xbytes) || overlaps(y, ybytes, w_packed, wbytes)) return PROM_EALIAS;
-        if (residual && residual != y && overlaps(y, ybytes, residual, ybytes)) return PROM_EALIAS;
-    } else {
-        if (overlaps(acc_out, ybytes * 4, x, xbytes) || overlaps(acc_out, ybytes * 4, w_packed, wbytes))
-            return PROM_EALIAS;
+    if (!shape_only) {
+        const size_t xbytes = (size_t)M * cin, ybytes = (size_t)M * cout;
+        const size_t wbytes = prom_packed_size(cout, cin);
+        if (mode == 0) {
+            if (overlaps(y, ybytes, x, xbytes) || overlaps(y, ybytes, w_packed, wbytes)) return PROM_EALIAS;
+            if (residual && residual != y && overlaps(y, ybytes, residual, ybytes)) return PROM_EALIAS;
+        } else {
+            if (overlaps(acc_out, ybytes * 4, x, xbytes) || overlaps(acc_out, ybytes * 4, w_packed, wbytes))
+                return PROM_EALIAS;
+        }
     }
 
-    PwArgs a;
+    PwArgs &a = L.a;
     a.x = x;
     a.wq = static_cast<const uint32_t *>(w_packed);
     a.bias = rq ? rq->bias : nullptr;
@@ -408,7 +422,6 @@ static int pw_dispatch(const int8_t *x, int n, int h, int w, int cin, const void
     const int n_tiles = (cout + 15) / 16;
     const bool aligned = (((uintptr_t)x | (uintptr_t)y | (uintptr_t)residual) & 3) == 0;
     const bool fast = mode == 0 && aligned && (cin % 8 == 0) && (cout % 4 == 0);
-    hipStream_t st = static_cast<hipStream_t>(stream);
 
     int nt, pt;
     if (!fast) {
@@ -448,27 +461,55 @@ static int pw_dispatch(const int8_t *x, int n, int h, int w, int cin, const void
     a.wg_per_chunk = (int)wgs;
     const long long total = wgs * a.n_chunks;
     if (total > (1LL << 30)) return PROM_EUNSUPPORTED;
-    const int grid = (int)((total + 7) / 8 * 8);
-    const size_t lds = (size_t)nt * a.KS * 1024;
+    L.grid = (int)((total + 7) / 8 * 8);
+    L.lds = (size_t)nt * a.KS * 1024;
+    L.nt = nt;
+    L.pt = pt;
+    L.fast = fast;
+    L.mode = mode;
+    L.xmode = !fast ? 1 : (cin % 16 == 0 ? 16 : 8);
+    return PROM_OK;
+}
 
-    if (mode == 1) {
-        switch (nt) {
-        case 1: return launch_one<1, 1, 1, true, true>(a, grid, lds, st);
-        case 2: return launch_one<2, 1, 1, true, true>(a, grid, lds, st);
-        case 3: return launch_one<3, 1, 1, true, true>(a, grid, lds, st);
-        default: return launch_one<4, 1, 1, true, true>(a, grid, lds, st);
+static int pw_launch(const PwLaunch &L, hipStream_t st)
+{
+    const PwArgs &a = L.a;
+    if (L.mode == 1) {
+        switch (L.nt) {
+        case 1: return launch_one<1, 1, 1, true, true>(a, L.grid, L.lds, st);
+        case 2: return launch_one<2, 1, 1, true, true>(a, L.grid, L.lds, st);
+        case 3: return launch_one<3, 1, 1, true, true>(a, L.grid, L.lds, st);
+        default: return launch_one<4, 1, 1, true, true>(a, L.grid, L.lds, st);
         }
     }
-    if (!fast) {
-        switch (nt) {
-        case 1: return launch_one<1, 1, 1, true, false>(a, grid, lds, st);
-        case 2: return launch_one<2, 1, 1, true, false>(a, grid, lds, st);
-        case 3: return launch_one<3, 1, 1, true, false>(a, grid, lds, st);
-        default: return launch_one<4, 1, 1, true, false>(a, grid, lds, st);
+    if (!L.fast) {
+        switch (L.nt) {
+        case 1: return launch_one<1, 1, 1, true, false>(a, L.grid, L.lds, st);
+        case 2: return launch_one<2, 1, 1, true, false>(a, L.grid, L.lds, st);
+        case 3: return launch_one<3, 1, 1, true, false>(a, L.grid, L.lds, st);
+        default: return launch_one<4, 1, 1, true, false>(a, L.grid, L.lds, st);
         }
     }
-    if (cin % 16 == 0) return launch_nt<16>(a, nt, pt, grid, lds, st);
-    return launch_nt<8>(a, nt, pt, grid, lds, st);
+    if (L.xmode == 16) return launch_nt<16>(a, L.nt, L.pt, L.grid, L.lds, st);
+    return launch_nt<8>(a, L.nt, L.pt, L.grid, L.lds, st);
+}
+
+static int pw_dispatch(const int8_t *x, int n, int h, int w, int cin, const void *w_packed, int cout,
+                       const prom_requant_t *rq, const int8_t *residual, int8_t *y, int32_t *acc_out,
+                       const prom_pw_plan_t *plan, void *stream, int mode)
+{
+    PwLaunch L;
+    const int rc = pw_prepare(x, n, h, w, cin, w_packed, cout, rq, residual, y, acc_out, plan, mode,
+                              false, L);
+    if (rc != PROM_OK) return rc;
+    return pw_launch(L, static_cast<hipStream_t>(stream));
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst,
+                                                   long long n16)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace prom
@@ -492,4 +533,57 @@ extern "C" int prom_pw_accum_i32(const int8_t *x, int n, int h, int w, int cin, 
 {
     return prom::pw_dispatch(x, n, h, w, cin, w_packed, cout, nullptr, nullptr, nullptr, acc, nullptr,
                              stream, 1);
+}
+
+extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out)
+{
+    if (!plan_out) return PROM_EINVAL;
+    prom::PwLaunch L;
+    const int rc = prom::pw_prepare(nullptr, n, h, w, cin, nullptr, cout, nullptr, nullptr, nullptr,
+                                    nullptr, nullptr, 0, true, L);
+    if (rc != PROM_OK) return rc;
+    plan_out->tiles_per_wave = L.nt;
+    plan_out->pixel_tiles = L.pt;
+    plan_out->workgroups = L.a.wg_per_chunk;
+    plan_out->reserved = L.xmode;
+    return PROM_OK;
+}
+
+extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream)
+{
+    if (!layers || count <= 0) return PROM_EINVAL;
+    constexpr int kMaxSeq = 256;
+    if (count > kMaxSeq) return PROM_EUNSUPPORTED;
+    static thread_local prom::PwLaunch plans[kMaxSeq];
+    for (int i = 0; i < count; ++i) {
+        const prom_pw_layer_t &l = layers[i];
+        const int rc = prom::pw_prepare(l.x, l.n, l.h, l.w, l.cin, l.w_packed, l.cout, &l.rq, l.residual,
+                                        l.y, nullptr, nullptr, 0, false, plans[i]);
+        if (rc != PROM_OK) {
+            if (bad_layer) *bad_layer = i;
+            return rc;
+        }
+    }
+    for (int i = 0; i < count; ++i) {
+        const int rc = prom::pw_launch(plans[i], static_cast<hipStream_t>(stream));
+        if (rc != PROM_OK) {
+            if (bad_layer) *bad_layer = i;
+            return rc;
+        }
+    }
+    return PROM_OK;
+}
+
+extern "C" int prom_copy_bytes(const void *src, void *dst, size_t nbytes, void *stream)
+{
+    if (!src || !dst || nbytes == 0 || (nbytes & 15) != 0) return PROM_EINVAL;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15) != 0) return PROM_EINVAL;
+    const long long n16 = (long long)(nbytes / 16);
+    long long blocks = (n16 + 255) / 256;
+    if (blocks > prom::kNumCU * 16) blocks = prom::kNumCU * 16;
+    prom::clear_hip_error();
+    hipLaunchKernelGGL(prom::copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const prom::v4i *>(src),
+                       static_cast<prom::v4i *>(dst), n16);
+    return prom::check_launch();
 }
