@@ -28,7 +28,7 @@
  *               The paper rescales in floating point (Figure 12); this integer form with
  *               bias (folded BatchNorm shift), Q31 multiplier and shift is the contract of
  *               this library.  Preconditions (not checked, the arrays live on the device):
- *               0 < mult[c] < 2^31, 0 <= shift[c] <= 31, and |acc + bias[c]| < 2^31.
+ *               0 < mult[c] < 2^31, 0 <= shift[c] <= 31, |bias[c]| < 2^29 and |acc + bias[c]| < 2^30.
  *   Errors      every int-returning function returns PROM_OK (0) or a negative code; on
  *               error nothing has been enqueued.
  */
@@ -65,7 +65,7 @@ typedef struct {
 
 /* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default". */
 typedef struct {
-    int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..12)       */
+    int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..10)       */
     int32_t pixel_tiles;     /* PT: 16-pixel tiles a wavefront processes per iteration (1,2,4)*/
     int32_t workgroups;      /* workgroups launched per output-channel chunk                  */
     int32_t reserved;

@@ -23,6 +23,27 @@ __device__ __forceinline__ void set_f64_round_down()
     asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 2");
 }
 
+// min(max(v, lo), hi); becomes one v_med3_i32 when lo and hi sit in vector registers or are
+// inline constants (the instruction can read at most one scalar register).
+__device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max(v, lo), hi); }
+
+// Median of three = clamp of v to [lo, hi] when lo <= hi.  Written as the instruction because
+// the compiler cannot prove lo <= hi and would emit a max and a min.
+__device__ __forceinline__ int med3_i32(int v, int lo, int hi)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
+// Moves a wave-uniform value into a vector register and hides its origin from the optimiser,
+// so that two such bounds can feed one v_med3_i32.
+__device__ __forceinline__ int in_vgpr(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 // scale = mult * 2^-(31+shift), exact in double (mult has at most 31 significant bits).
 __device__ __forceinline__ double make_scale(int mult, int shift)
 {
@@ -41,7 +62,7 @@ __device__ __forceinline__ int requant_to_biased(int s, double scale, int lo_b, 
 {
     const double v = __builtin_fma((double)s, scale, 256.5);
     const int qe = (int)v;
-    return min(max(qe, lo_b), hi_b);
+    return clamp_i32(qe, lo_b, hi_b);
 }
 
 // Low bytes of four ints -> one dword (a in bits 0..7).

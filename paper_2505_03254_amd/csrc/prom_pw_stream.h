@@ -1,0 +1,411 @@
+// Ternary pointwise 1x1 convolution on gfx950: int8 MFMA over weights decoded from 2-bit
+// codes into LDS, activations streamed from HBM straight into the MFMA operand registers,
+// exact integer requantisation in the epilogue, outputs staged through LDS so that every
+// global store instruction writes one contiguous run.
+//
+// Formulation.  The layer is Y[m][co] = sum_k X[m][k] * W[co][k]  (paper Section 2: a sum of
+// input channels; Section 3.1: convolve with the ternary weights, rescale afterwards).  The
+// kernel computes the transpose, D = W_tile (16 channels x 64 k) * X_tile^T (64 k x 16 pixels)
+// with v_mfma_i32_16x16x64_i8, because then
+//   - the B operand of lane l is 16 consecutive k-bytes of pixel (l & 15): one 16-byte
+//     load from the NHWC row, no LDS staging of activations;
+//   - the D registers of lane l are 4 consecutive output channels of pixel (l & 15): one
+//     packed dword of int8 outputs, and per-lane requantisation parameters.
+// A wavefront owns NT 16-channel tiles (a "chunk" of 16*NT output channels) and walks over
+// groups of 16*PT pixels; the 4 wavefronts of a workgroup share the decoded weights.
+//
+// Requantisation.  With acc the raw accumulator, the epilogue needs
+//     q = floor(((acc + bias) * mult + 2^(30+shift)) / 2^(31+shift)).
+// Per channel the prologue forms the 64-bit constant C = bias*mult + 2^(30+shift); then
+//     t = acc*mult + C            one v_mad_i64_i32 (full rate on gfx950)
+//     q = hi32(t) >> (shift-1)    when shift >= 1 (arithmetic shifts are floor divisions)
+//     q = (t >> 31) >> shift      in general (taken by a workgroup whose chunk has a shift of 0)
+// which is exact integer arithmetic for |acc + bias| < 2^30.
+//
+// Memory pipeline.  The streaming kernel addresses x, y and the residual through buffer
+// resources: an access whose byte offset is beyond the tensor reads zero or is dropped by the
+// hardware, so ragged pixel counts need no branches, the loop body is straight-line code, and
+// the activation loads of a ring of D future steps stay in flight across the epilogue.
+#pragma once
+#include "prom.h"
+#include "prom_device.h"
+
+#include <type_traits>
+
+namespace prom {
+
+struct PwArgs {
+    const int8_t *x;
+    const uint32_t *wq;
+    const int32_t *bias;
+    const int32_t *mult;
+    const int32_t *shift;
+    const int8_t *residual;
+    int8_t *y;
+    int32_t *acc_out;
+    int M;       // pixels
+    int units;   // pixel groups of 16*PT pixels, one per wavefront iteration
+    int K, Nc;
+    int KW;      // packed 32-bit words per weight row = ceil(K/16)
+    int KS;      // 64-wide k steps = ceil(K/64)
+    int n_chunks;      // output-channel chunks of 16*NT channels
+    int wg_per_chunk;  // workgroups per chunk; 4*wg_per_chunk wavefronts share the units
+    int lo, hi;        // activation window
+};
+
+// Tiles of a chunk are stored in groups of 4, then 2, then 1 so that a lane's outputs of a
+// group are 16, 8 or 4 contiguous bytes.
+template <int NT> __host__ __device__ constexpr int grp_size(int t)
+{
+    return t < 4 * (NT / 4) ? 4 : (((NT % 4) >= 2 && t < 4 * (NT / 4) + 2) ? 2 : 1);
+}
+template <int NT> __host__ __device__ constexpr int grp_first(int t)
+{
+    return t < 4 * (NT / 4) ? (t & ~3)
+           : (((NT % 4) >= 2 && t < 4 * (NT / 4) + 2) ? 4 * (NT / 4)
+                                                       : 4 * (NT / 4) + ((NT % 4) >= 2 ? 2 : 0));
+}
+// Channel (relative to the chunk base) held in D row 4*gr + r of tile slot t.
+template <int NT> __host__ __device__ constexpr int chan_of(int t, int gr, int r)
+{
+    return 16 * grp_first<NT>(t) + 4 * grp_size<NT>(t) * gr + 4 * (t - grp_first<NT>(t)) + r;
+}
+
+// 16 two-bit codes (layout of prom_pack_ternary) -> 16 int8 weights in MFMA operand order.
+__device__ __forceinline__ v4i decode_word(uint32_t word)
+{
+    v4i f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        // code c in {0,1,3} -> byte selector 2c in {0,2,6} of the 8-byte table below
+        const uint32_t sel = ((word >> (2 * d)) & 0x03030303u) << 1;
+        // table bytes: [0]=0x00 (zero), [2]=0x01 (+1), [6]=0xFF (-1)
+        f[d] = (int)__builtin_amdgcn_perm(0x00FF0000u, 0x00010000u, sel);
+    }
+    return f;
+}
+
+// Decode the chunk's weights into LDS fragments frag[NT][KS][64 lanes] and the chunk's
+// requantisation parameters into lpar[NT][4 g][4 r] = (C lo, C hi, mult, shift).  Returns
+// (to every thread) whether any channel of the chunk has shift == 0.  Contains the barrier.
+template <int NT, bool WITH_PARAMS>
+__device__ __forceinline__ bool stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar)
+{
+    const int tid = threadIdx.x;
+    const int KS = a.KS, Nc = a.Nc;
+    const int nfrag = NT * KS * 64;
+    bool sh0 = false;
+    int pb = 0, pm = 0, ps = 1;
+    const bool ptid = WITH_PARAMS && tid < NT * 16;
+    if (ptid) {
+        const int c = cbase + chan_of<NT>(tid >> 4, (tid >> 2) & 3, tid & 3);
+        if (c < Nc) {
+            pb = a.bias[c];
+            pm = a.mult[c];
+            ps = a.shift[c];
+        }
+    }
+    constexpr int U = 8;  // words in flight per thread
+    for (int base = 0; base < nfrag; base += 256 * U) {
+        uint32_t word[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            const int tk = idx >> 6;
+            const int ks = tk % KS;
+            const int t = tk / KS;
+            const int i = idx & 15;
+            const int c = cbase + chan_of<NT>(t, i >> 2, i & 3);
+            const int kw = 4 * ks + ((idx & 63) >> 4);
+            // clamp instead of branching so that the loads of a batch are issued back to back
+            const bool ok = idx < nfrag && c < Nc && kw < a.KW;
+            const uint32_t v = a.wq[ok ? (long long)c * a.KW + kw : 0];
+            word[q] = ok ? v : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            if (idx < nfrag) frag[idx] = decode_word(word[q]);
+        }
+    }
+    if (ptid) {
+        const long long C = (long long)pb * pm + (1LL << (30 + ps));
+        lpar[tid] = v4i{(int)(uint32_t)C, (int)(C >> 32), pm, ps};
+        sh0 = ps == 0;
+    }
+    return __syncthreads_or(sh0) != 0;
+}
+
+// t = acc*mult + C; q = t >> (31 + shift); clamp to [lo, hi].  pr = (C lo, C hi, mult, s) with
+// s = shift-1 when !GENERAL (the caller guarantees shift >= 1) and s = shift when GENERAL.
+template <bool GENERAL>
+__device__ __forceinline__ int requant_i64(int accv, const v4i &pr, int lo, int hi)
+{
+    const long long C = (long long)(((unsigned long long)(uint32_t)pr[1] << 32) | (uint32_t)pr[0]);
+    const long long t = (long long)accv * (long long)pr[2] + C;
+    int q;
+    if constexpr (GENERAL)
+        q = (int)(t >> 31) >> pr[3];
+    else
+        q = (int)(t >> 32) >> pr[3];
+    return med3_i32(q, lo, hi);
+}
+
+// XCD-aware logical workgroup id: consecutive hardware ids go round-robin over the 8 XCDs;
+// make logical neighbours (the chunks of one pixel range) land on the same XCD and L2.
+__device__ __forceinline__ int logical_block_id()
+{
+    const int nblk = gridDim.x;  // multiple of 8
+    return (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+}
+
+// Depth of the activation prefetch ring (load groups in flight per wavefront).
+template <int PT> __host__ __device__ constexpr int ring_depth() { return PT == 1 ? 4 : 3; }
+
+// LDS bytes of the streaming kernel: decoded weight fragments, one int4 of parameters per
+// channel, one output staging tile (16 pixels x 16*NT bytes) per wavefront.
+__host__ __device__ constexpr size_t lds_bytes_fast(int nt, int ks)
+{
+    return (size_t)nt * ks * 1024 + (size_t)nt * 16 * 16 + (size_t)4 * 256 * nt;
+}
+__host__ __device__ constexpr size_t lds_bytes_generic(int nt, int ks)
+{
+    return (size_t)nt * ks * 1024 + (size_t)nt * 16 * 16;
+}
+
+constexpr int kBufFlags = 0x00020000;   // raw buffer of dwords, gfx9 family
+constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled here
+
+// ============================================================================================
+// Streaming kernel: cin % 8 == 0, cout % 4 == 0, 4-byte aligned tensors below 2^30 bytes, and
+// either one chunk (its tile is one contiguous run) or cout % 16 == 0.
+//   XMODE 16: cin % 16 == 0, one 16-byte load per fragment; XMODE 8: two 8-byte loads.
+//   KS1: cin <= 64 (one k step per group, no branch around the epilogue).
+//   FULLW: cout % (16*NT) == 0, every chunk is 16*NT valid channels wide (no per-lane channel
+//          conditions, compile-time staging geometry).
+// ============================================================================================
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW>
+__global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
+{
+    constexpr int D = ring_depth<PT>();
+    constexpr int NI = (NT + 3) / 4;  // 16-byte store instructions per staged tile
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int KS = KS1 ? 1 : a.KS;
+    v4i *frag = reinterpret_cast<v4i *>(lds_raw);  // [NT][KS][64 lanes] decoded A operands
+    v4i *lpar = frag + NT * KS * 64;               // [NT][4 g][4 r] requantisation parameters
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
+    const int j = lane & 15;  // pixel within a 16-pixel tile
+    const int g = lane >> 4;  // k group on the input side, channel group on the output side
+
+    const int lid = logical_block_id();
+    const int chunk = lid % a.n_chunks;
+    const int wg = lid / a.n_chunks;
+    if (wg >= a.wg_per_chunk) return;
+    const int cbase = chunk * NT * 16;
+    const int Wv = a.wg_per_chunk * 4;  // wavefronts sharing the pixel groups of this chunk
+    const int w0 = wg * 4 + wave;       // this wavefront's first group
+    const int K = a.K, Nc = a.Nc;
+    unsigned char *stage = reinterpret_cast<unsigned char *>(lpar + NT * 16) + wave * (256 * NT);
+
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.M * K, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.M * Nc, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.residual ? a.residual : a.y), 0, a.M * Nc, kBufFlags);
+
+    // ---- load cursor: next (group, k step) to fetch.  Offsets beyond the tensor read zero. ----
+    // Offsets are unsigned 32-bit and saturate at kOobOffset, so running past the end of this
+    // wavefront's work can never wrap around into the tensor.
+    int lk = 0;
+    unsigned xoff = min((unsigned)kOobOffset,
+                        (unsigned)(w0 * (16 * PT) + j) * (unsigned)K + 16u * g);  // pixel tile 0, k step 0
+    const unsigned xstep = (unsigned)Wv * (16 * PT) * (unsigned)K;
+    auto load_group = [&](v4i(&b)[PT]) {
+#pragma unroll
+        for (int p = 0; p < PT; ++p) {
+            const int so = (16 * p) * K + 64 * lk;
+            if constexpr (XMODE == 16) {
+                b[p] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xoff, so, 0);
+            } else {
+                const v2i lo2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)xoff, so, 0);
+                const v2i hi2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(xoff + 8), so, 0);
+                b[p] = v4i{lo2[0], lo2[1], hi2[0], hi2[1]};
+            }
+        }
+        if (KS1 || ++lk == KS) {
+            lk = 0;
+            xoff = min(xoff + xstep, (unsigned)kOobOffset);
+        }
+    };
+
+    // ---- start the activation prefetch ring before anything else ----------------------------
+    v4i ring[D][PT];
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_group(ring[d]);
+
+    const bool general_shift = stage_weights<NT, true>(a, cbase, frag, lpar);
+
+    // per-lane parameters: 4 channels per tile slot; .w holds shift-1 on the fast path
+    v4i par[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            par[t][r] = lpar[(t * 4 + g) * 4 + r];
+            if (!general_shift) par[t][r][3] -= 1;
+        }
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int m128 = in_vgpr(-128), p127 = in_vgpr(127);
+
+    // ---- output staging geometry (uniform per workgroup) -----------------------------------------
+    // RW: valid bytes per pixel row of this chunk.  The staged tile is 16 rows of RW bytes,
+    // written to y in 16-byte pieces; piece q = 64*i + lane sits at staged offset 16*q.  When the
+    // chunk is the whole row (RW == Nc) the tile is one contiguous run of 16*Nc bytes; otherwise
+    // RW % 16 == 0 and a piece never crosses a row.
+    const int RW = FULLW ? 16 * NT : min(16 * NT, Nc - cbase);
+    const bool rw16 = (RW & 15) == 0, rw8 = (RW & 7) == 0;
+    const bool contig = RW == Nc;
+    int goff[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int q = i * 64 + lane;
+        int o;
+        if (contig) {
+            o = 16 * q;
+        } else {
+            const int per_row = RW >> 4;
+            const int row = q / per_row;
+            o = row * Nc + 16 * (q - row * per_row);
+        }
+        goff[i] = q < RW ? o : kOobOffset;
+    }
+
+    // byte offset of (first pixel of the group, chunk base); uniform per wavefront
+    unsigned ytile = min((unsigned)kOobOffset, (unsigned)(w0 * (16 * PT)) * (unsigned)Nc + (unsigned)cbase);
+    const unsigned ystep = (unsigned)Wv * (16 * PT) * (unsigned)Nc;
+
+    const int my_groups = w0 < a.units ? (a.units - w0 + Wv - 1) / Wv : 0;
+    const int outer = (my_groups * KS + D - 1) / D;
+    const v4i *fl = frag + lane;
+
+    // ---- main loop: D ring slots per iteration, straight-line; steps past the end of this
+    // wavefront's work load zeros and store nothing (their offsets are beyond the tensor).
+    // The loop is instantiated per (residual, general shift) so that its body has no branch
+    // on either. ------------------------------------------------------------------------------
+    auto run = [&](auto has_res_tag, auto general_tag) {
+        constexpr bool HAS_RES = decltype(has_res_tag)::value;
+        constexpr bool GENERAL = decltype(general_tag)::value;
+        v4i acc[PT][NT];
+        const v4i zero4 = {0, 0, 0, 0};
+        int ck = 0;
+        for (int it = 0; it < outer; ++it) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const v4i *fk = fl + ck * 64;
+                if (KS1 || ck == 0) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const v4i wfrag = fk[t * KS * 64];
+#pragma unroll
+                        for (int p = 0; p < PT; ++p)
+                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, ring[d][p], zero4, 0, 0, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const v4i wfrag = fk[t * KS * 64];
+#pragma unroll
+                        for (int p = 0; p < PT; ++p)
+                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, ring[d][p], acc[p][t], 0, 0, 0);
+                    }
+                }
+                load_group(ring[d]);  // refill this slot with the group D steps ahead
+                if (KS1 || ++ck == KS) {
+                    ck = 0;
+#pragma unroll
+                    for (int p = 0; p < PT; ++p) {
+                        const int tile_off = (int)(ytile + (unsigned)((16 * p) * Nc));
+#pragma unroll
+                        for (int t0 = 0; t0 < NT; t0 += grp_size<NT>(t0)) {
+                            const int S = grp_size<NT>(t0);
+                            const int cl = chan_of<NT>(t0, g, 0);  // lane's first channel of the group
+                            uint32_t res[4] = {0, 0, 0, 0};
+                            if constexpr (HAS_RES) {
+                                const int ro = j * Nc + cl;
+                                if (S == 4) {
+                                    const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, tile_off, 0);
+                                    res[0] = v[0]; res[1] = v[1]; res[2] = v[2]; res[3] = v[3];
+                                } else if (S == 2) {
+                                    const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, tile_off, 0);
+                                    res[0] = v[0]; res[1] = v[1];
+                                } else {
+                                    res[0] = __builtin_amdgcn_raw_buffer_load_b32(rr, ro, tile_off, 0);
+                                }
+                            }
+                            uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+                            for (int tt = 0; tt < 4; ++tt) {
+                                if (tt < S) {
+                                    int v[4];
+#pragma unroll
+                                    for (int r = 0; r < 4; ++r)
+                                        v[r] = requant_i64<GENERAL>(acc[p][t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                    if constexpr (HAS_RES) {
+#pragma unroll
+                                        for (int r = 0; r < 4; ++r)
+                                            v[r] = med3_i32(v[r] + sbyte(res[tt], r), m128, p127);
+                                    }
+                                    out[tt] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                                }
+                            }
+                            // stage the lane's dwords at [pixel j][channel cl..] of the wavefront's tile
+                            unsigned char *sp = stage + j * RW + cl;
+                            const bool full = FULLW || cl + 4 * S <= RW;
+                            if (full && S == 4 && (FULLW || rw16)) {
+                                *reinterpret_cast<v4i *>(sp) = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+                            } else if (full && S == 2 && (FULLW || rw8)) {
+                                *reinterpret_cast<v2i *>(sp) = v2i{(int)out[0], (int)out[1]};
+                            } else {
+#pragma unroll
+                                for (int tt = 0; tt < 4; ++tt)
+                                    if (tt < S && (FULLW || cl + 4 * tt + 4 <= RW))
+                                        *reinterpret_cast<uint32_t *>(sp + 4 * tt) = out[tt];
+                            }
+                        }
+                        // write the staged tile; pieces outside the tile or the tensor are dropped
+#pragma unroll
+                        for (int i = 0; i < NI; ++i) {
+                            const v4i v = *reinterpret_cast<const v4i *>(stage + (i * 64 + lane) * 16);
+                            __builtin_amdgcn_raw_buffer_store_b128(v, ry, goff[i], tile_off, 0);
+                        }
+                    }
+                    ytile = min(ytile + ystep, (unsigned)kOobOffset);
+                }
+            }
+        }
+    };
+
+    if (a.residual) {
+        if (general_shift)
+            run(std::true_type{}, std::true_type{});
+        else
+            run(std::true_type{}, std::false_type{});
+    } else {
+        if (general_shift)
+            run(std::false_type{}, std::true_type{});
+        else
+            run(std::false_type{}, std::false_type{});
+    }
+}
+
+using PwKernelFn = void (*)(const PwArgs);
+
+// One translation unit per NT instantiates the streaming kernel (prom_pw_inst.hip) and exports
+// its selector; returns nullptr for a combination that is not compiled.
+template <int NT> PwKernelFn pw_stream_select(int pt, int xmode, bool ks1, bool fullw);
+
+constexpr int kMaxNT = 10;
+
+}  // namespace prom
