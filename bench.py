@@ -31,6 +31,25 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def kernel_name(variant):
+    nt, pt, ld, ks1, fullw = variant
+    return (f"void prom::pw_stream_kernel<{nt}, {pt}, {ld}, {str(ks1).lower()}, {str(fullw).lower()}>"
+            f"(prom::PwArgs)")
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of a kernel from the committed FETCH_SIZE/WRITE_SIZE profile
+    (lines 'traffic_bytes_per_launch[<kernel>] = N'); None if the profile does not list it."""
+    path = os.path.join(ROOT, "profiles", "pw_sweep_mobilenetv2_b128.hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch[") and f"[{name}]" in line:
+                return int(line.rsplit("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def layer_bytes(m, k, nc, residual=False):
     """Algorithmic HBM bytes of one layer: activations in + out (+ residual), 2-bit weights,
     12 bytes of requantisation parameters per output channel."""
@@ -75,7 +94,9 @@ def main():
                        torch.from_numpy(L.shift).to(dev), 0, 127)
         y = torch.empty((args.batch, s.hw, s.hw, s.cout), dtype=torch.int8, device=dev)
         plan = P.prom_pw_plan_query(args.batch, s.hw, s.hw, s.cin, s.cout)
-        variant = (plan["tiles_per_wave"], plan["pixel_tiles"], plan["load_bytes"])
+        # template arguments of the kernel instantiation this layer runs (as rocprofv3 names it)
+        variant = (plan["tiles_per_wave"], plan["pixel_tiles"], plan["load_bytes"], s.cin <= 64,
+                   s.cout % (16 * plan["tiles_per_wave"]) == 0)
         m = args.batch * s.hw * s.hw
         layers.append(dict(shape=s, L=L, x=x, wp=wp, rq=rq, y=y, plan=plan, variant=variant, m=m,
                            bytes=layer_bytes(m, s.cin, s.cout), ops=2 * m * s.cin * s.cout))
@@ -89,7 +110,7 @@ def main():
     for l in layers:
         by_variant.setdefault(l["variant"], []).append(l)
     dom_variant = max(by_variant, key=lambda v: sum(l["bytes"] for l in by_variant[v]))
-    dom_name = (f"prom::pw_kernel<{dom_variant[0]}, {dom_variant[1]}, {dom_variant[2]}, false, false>")
+    dom_name = kernel_name(dom_variant)
 
     # segments: maximal runs of non-dominant layers, and each dominant layer alone with events
     segments = []
@@ -161,7 +182,7 @@ def main():
         gops = l["ops"] / (us * 1e-6) / 1e9
         s = l["shape"]
         per_layer.append(dict(layer=s.name, us=round(us, 2), gbs=round(gbs, 1), gops=round(gops, 1)))
-        log(f"{s.name:<13}{s.hw:>4}{s.cin:>5}{s.cout:>6} {str(l['variant']):>15} {us:8.2f} {gbs:8.1f} "
+        log(f"{s.name:<13}{s.hw:>4}{s.cin:>5}{s.cout:>6} {str(l['variant'][:3]):>15} {us:8.2f} {gbs:8.1f} "
             f"{100 * gbs / HBM_PEAK_GBS:6.1f} {gops:9.1f} {100 * gops / (MFMA_I8_PEAK_TOPS * 1e3):6.1f}")
     sum_us = sum(p["us"] for p in per_layer)
     log(f"sum of per-layer event times: {sum_us:.1f} us  (timed region: {ms_per_step * 1e3:.1f} us/step)")
@@ -213,7 +234,7 @@ def main():
                      "frac": round(dom_achieved / HBM_PEAK_GBS, 4),
                      "avg_launch_us": round(dom_avg_us, 2),
                      "bytes_per_launch": int(dom_bytes_per_launch),
-                     "traffic": None},
+                     "traffic": measured_traffic(dom_name)},
         "per_layer": per_layer,
     }
 
