@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
     ap.add_argument("--cpu-sample-images", type=int, default=16)
+    ap.add_argument("--streams", type=int, default=4,
+                    help="streams of the extra 'concurrent' leg (the 34 layers are independent)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; multi-GPU runs are not part of it "
@@ -187,6 +189,42 @@ def main():
     sum_us = sum(p["us"] for p in per_layer)
     log(f"sum of per-layer event times: {sum_us:.1f} us  (timed region: {ms_per_step * 1e3:.1f} us/step)")
 
+    # ---- extra leg: the same 34 independent layers spread round-robin over several streams, so
+    # that one layer's launch, prologue and write-back overlap with another layer's streaming ----
+    conc = None
+    if args.streams > 1:
+        streams = [torch.cuda.Stream(device=dev) for _ in range(args.streams)]
+        order = sorted(range(len(layers)), key=lambda i: -layers[i]["bytes"])  # big layers first
+        per_stream = [[] for _ in streams]
+        for rank, i in enumerate(order):
+            l = layers[i]
+            per_stream[rank % len(streams)].append((l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"]))
+        stream_seqs = [P.PwSequence(lst) for lst in per_stream]
+
+        def conc_step():
+            start = torch.cuda.Event()
+            start.record()
+            for st, sq in zip(streams, stream_seqs):
+                st.wait_event(start)
+                sq.run(stream=st)
+                done = torch.cuda.Event()
+                done.record(st)
+                torch.cuda.current_stream().wait_event(done)
+        for _ in range(3):
+            conc_step()
+        torch.cuda.synchronize()
+        tc0 = time.perf_counter()
+        for _ in range(args.steps):
+            conc_step()
+        torch.cuda.synchronize()
+        conc_ms = (time.perf_counter() - tc0) * 1e3 / args.steps
+        conc = {"streams": args.streams, "ms_per_step": round(conc_ms, 4),
+                "gops": round(total_ops / (conc_ms * 1e-3) / 1e9, 1),
+                "gbs": round(total_bytes / (conc_ms * 1e-3) / 1e9, 1),
+                "frac_hbm_roofline": round(total_bytes / (conc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        log(f"[bench] {args.streams} streams, layers overlapped: {conc_ms * 1e3:.1f} us/step, "
+            f"{conc['gbs']:.0f} GB/s ({100 * conc['frac_hbm_roofline']:.1f}% of the HBM roofline)")
+
     # ---- HBM yardstick: the library's plain copy kernel on 512 MB --------------------------
     nb = 512 << 20
     src = torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -227,7 +265,8 @@ def main():
                   "frac_hbm_roofline": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "gadd_per_s": round(value / 2, 1),
                   "sum_layer_event_us": round(sum_us, 1),
-                  "copy_kernel_gbs": round(copy_gbs, 0)},
+                  "copy_kernel_gbs": round(copy_gbs, 0),
+                  "layers_overlapped_on_streams": conc},
         "roofline": {"bound": "hbm", "kernel": dom_name,
                      "layers": [l["shape"].name for l in by_variant[dom_variant]],
                      "achieved": round(dom_achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

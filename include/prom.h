@@ -137,6 +137,15 @@ typedef struct {
  * of the offending layer is stored in *bad_layer when bad_layer is not NULL. */
 int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream);
 
+/* The same layer computed by the other design that was evaluated: multiplication-free
+ * accumulation on the vector ALU (sums of the input bytes whose weight is +1 / -1, paper
+ * Section 2), one lane per pixel.  Bit-identical results; kept for the A/B measurement against
+ * the MFMA kernel, not for production use.  Limits: cin <= 256, cin % 4 == 0, cout % 4 == 0,
+ * 4-byte aligned pointers, tensors below 2 GiB (PROM_EUNSUPPORTED otherwise). */
+int prom_pw_conv_addsub(const int8_t *x, int n, int h, int w, int cin,
+                        const void *w_packed, int cout, const prom_requant_t *rq,
+                        const int8_t *residual, int8_t *y, void *stream);
+
 /* Raw int32 accumulators acc[m][co] = sum_k x[m][k] * W[co][k] (no bias, no requant), for
  * staged checking of the accumulation alone.  acc: dev int32 [n*h*w][cout]. */
 int prom_pw_accum_i32(const int8_t *x, int n, int h, int w, int cin,

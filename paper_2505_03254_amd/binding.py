@@ -68,6 +68,8 @@ def load_library():
     lib.prom_unpack_ternary.argtypes = [vp, sz, ci, ci, vp]
     lib.prom_pw_conv.restype = ci
     lib.prom_pw_conv.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp, vp]
+    lib.prom_pw_conv_addsub.restype = ci
+    lib.prom_pw_conv_addsub.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp, vp]
     lib.prom_pw_conv_ex.restype = ci
     lib.prom_pw_conv_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp,
                                     ctypes.POINTER(_PlanC), vp]
@@ -204,6 +206,24 @@ def prom_pw_conv(x, w_packed, cout: int, rq: Requant, residual=None, y=None, str
         x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout), ctypes.byref(rqc),
         residual.data_ptr() if residual is not None else None, y.data_ptr(), _stream_ptr(stream))
     _check(rc, "prom_pw_conv")
+    return y
+
+
+def prom_pw_conv_addsub(x, w_packed, cout: int, rq: Requant, residual=None, y=None, stream=None):
+    """The add/subtract (vector ALU) design of the same layer, for the A/B measurement."""
+    import torch
+    _dev_i8(x, "x")
+    n, h, w, cin = x.shape
+    if y is None:
+        y = torch.empty((n, h, w, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    if residual is not None:
+        _dev_i8(residual, "residual")
+    rqc = rq._c()
+    rc = load_library().prom_pw_conv_addsub(
+        x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout), ctypes.byref(rqc),
+        residual.data_ptr() if residual is not None else None, y.data_ptr(), _stream_ptr(stream))
+    _check(rc, "prom_pw_conv_addsub")
     return y
 
 

@@ -86,15 +86,14 @@ __device__ __forceinline__ v4i decode_word(uint32_t word)
 }
 
 // Decode the chunk's weights into LDS fragments frag[NT][KS][64 lanes] and the chunk's
-// requantisation parameters into lpar[NT][4 g][4 r] = (C lo, C hi, mult, shift).  Returns
-// (to every thread) whether any channel of the chunk has shift == 0.  Contains the barrier.
+// requantisation parameters into lpar[NT][4 g][4 r] = (C lo, C hi, mult, shift).  Ends with
+// the workgroup barrier that publishes both.
 template <int NT, bool WITH_PARAMS>
-__device__ __forceinline__ bool stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar)
+__device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar)
 {
     const int tid = threadIdx.x;
     const int KS = a.KS, Nc = a.Nc;
     const int nfrag = NT * KS * 64;
-    bool sh0 = false;
     int pb = 0, pm = 0, ps = 1;
     const bool ptid = WITH_PARAMS && tid < NT * 16;
     if (ptid) {
@@ -105,7 +104,7 @@ __device__ __forceinline__ bool stage_weights(const PwArgs &a, int cbase, v4i *f
             ps = a.shift[c];
         }
     }
-    constexpr int U = 8;  // words in flight per thread
+    constexpr int U = 16;  // words in flight per thread
     for (int base = 0; base < nfrag; base += 256 * U) {
         uint32_t word[U];
 #pragma unroll
@@ -131,9 +130,8 @@ __device__ __forceinline__ bool stage_weights(const PwArgs &a, int cbase, v4i *f
     if (ptid) {
         const long long C = (long long)pb * pm + (1LL << (30 + ps));
         lpar[tid] = v4i{(int)(uint32_t)C, (int)(C >> 32), pm, ps};
-        sh0 = ps == 0;
     }
-    return __syncthreads_or(sh0) != 0;
+    __syncthreads();
 }
 
 // t = acc*mult + C; q = t >> (31 + shift); clamp to [lo, hi].  pr = (C lo, C hi, mult, s) with
@@ -245,17 +243,27 @@ __global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
 
-    const bool general_shift = stage_weights<NT, true>(a, cbase, frag, lpar);
+    stage_weights<NT, true>(a, cbase, frag, lpar);
 
-    // per-lane parameters: 4 channels per tile slot; .w holds shift-1 on the fast path
+    // per-lane parameters: 4 channels per tile slot.  The lanes of a wavefront hold every channel
+    // of the chunk between them, so a wavefront can see by itself whether any shift is 0 and
+    // then takes the general form of the requantisation; otherwise .w holds shift-1.
     v4i par[NT][4];
+    bool sh0 = false;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             par[t][r] = lpar[(t * 4 + g) * 4 + r];
-            if (!general_shift) par[t][r][3] -= 1;
+            sh0 |= par[t][r][3] == 0;
         }
+    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+    if (!general_shift) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) par[t][r][3] -= 1;
+    }
     const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
     const int m128 = in_vgpr(-128), p127 = in_vgpr(127);
 

@@ -168,3 +168,22 @@ def test_zero_fraction_variants(P):
     for pz in (0.0, 0.31, 0.55, 1.0):
         L = make_pw_layer(4300, 1, 14, 14, 64, 384, p_zero=pz)
         assert_same(run_pw(P, L), oracle_pw(oracle, L), f"p_zero={pz}")
+
+
+ADDSUB_SHAPES = [(1, 14, 14, 64, 384), (2, 28, 28, 24, 144), (1, 9, 13, 144, 24), (3, 7, 7, 16, 96),
+                 (1, 5, 11, 256, 40), (1, 3, 3, 4, 4), (2, 14, 14, 192, 64), (1, 10, 10, 96, 576)]
+
+
+@pytest.mark.parametrize("shape", ADDSUB_SHAPES)
+@pytest.mark.parametrize("res", [False, True])
+def test_addsub_design_matches_oracle(P, shape, res):
+    """The vector-ALU add/subtract design (kept for the A/B measurement) is bit-exact too."""
+    torch = torch_cuda()
+    n, h, w, cin, cout = shape
+    L = make_pw_layer(7000 + cin + cout, n, h, w, cin, cout, signed_x=True,
+                      act_window=(-128, 127) if res else (0, 127), with_residual=res, shift_range=(2, 9))
+    L.x.reshape(-1)[::41] = -128
+    y = P.prom_pw_conv_addsub(dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, requant_dev(P, L),
+                              dev(L.residual) if res else None)
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), oracle_pw(oracle, L), f"addsub {shape} res={res}")
