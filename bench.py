@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--cpu-sample-images", type=int, default=16)
     ap.add_argument("--streams", type=int, default=4,
                     help="streams of the extra 'concurrent' leg (the 34 layers are independent)")
+    ap.add_argument("--ab", choices=["both", "mfma", "addsub"], default=None,
+                    help="instead of the sweep: time the two designs of the pointwise layer "
+                         "(MFMA vs add/subtract on the vector ALU) on four representative layers")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; multi-GPU runs are not part of it "
@@ -83,6 +86,9 @@ def main():
     P.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.ab:
+        print(json.dumps(ab_study(P, torch, dev, args.ab, args.batch)), flush=True)
+        return
     t_setup = time.time()
 
     # ---- build the workload ----------------------------------------------------------------
@@ -307,6 +313,47 @@ def main():
             f"GPU outputs of the sample differ in {mismatches} elements")
 
     print(json.dumps(result), flush=True)
+
+
+def ab_study(P, torch, dev, which, batch):
+    """Design A (int8 MFMA, prom_pw_conv) against design B (add/subtract on the vector ALU,
+    prom_pw_conv_addsub) on four layers of the sweep, cache-cold (rotating buffer sets)."""
+    from workloads import make_pw_layer
+    out = {"metric": "A/B of the pointwise designs, us per launch", "batch": batch, "layers": []}
+    for name, hw, cin, cout in (("b2.expand", 112, 16, 96), ("b3.project", 56, 144, 24),
+                                ("b8.expand", 14, 64, 384), ("b5.expand", 28, 32, 192)):
+        m = batch * hw * hw
+        nbytes = layer_bytes(m, cin, cout)
+        sets = max(2, int(600e6 // nbytes) + 1)
+        L = make_pw_layer(SEED + 4000 + cin, 1, 1, 1, cin, cout)
+        xs = [torch.randint(0, 128, (batch, hw, hw, cin), dtype=torch.int8, device=dev) for _ in range(sets)]
+        ys = [torch.empty((batch, hw, hw, cout), dtype=torch.int8, device=dev) for _ in range(sets)]
+        wp = torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev)
+        rq = P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
+                       torch.from_numpy(L.shift).to(dev), 0, 127)
+
+        def timeit(fn, reps=10):
+            for i in range(2):
+                fn(xs[i % sets], wp, cout, rq, None, ys[i % sets])
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                fn(xs[i % sets], wp, cout, rq, None, ys[i % sets])
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+        row = {"layer": name, "cin": cin, "cout": cout, "pixels": m,
+               "hbm_ideal_us": round(nbytes / (HBM_PEAK_GBS * 1e3), 2)}
+        if which in ("both", "mfma"):
+            row["mfma_us"] = round(timeit(P.prom_pw_conv), 2)
+        if which in ("both", "addsub"):
+            row["addsub_us"] = round(timeit(P.prom_pw_conv_addsub), 2)
+        out["layers"].append(row)
+        log(f"[ab] {row}")
+        del xs, ys
+    return out
 
 
 def extra_legs(P, torch, dev, batch, log):
