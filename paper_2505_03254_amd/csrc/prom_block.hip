@@ -1,18 +1,330 @@
-// Inverted-residual block: ternary pointwise expand -> int8 depthwise 3x3 -> ternary
-// pointwise project (+ saturating skip), paper Section 2 and Figure 4.  This version chains
-// the three kernels on the caller's stream through two intermediates in the workspace.
-#include "prom.h"
+// Inverted-residual block: ternary pointwise expand -> int8 depthwise 3x3 -> ternary pointwise
+// project (+ saturating skip), paper Section 2 and Figure 4.
+//
+// Fused kernel.  The expanded tensor is 6x wider than the block's input and output; written to
+// HBM between the three layers it is >90 % of the block's traffic.  The fused kernel keeps it in
+// LDS: a workgroup owns a band of R output rows of one image and walks over the hidden
+// channels in chunks of 64:
+//   stage 1  expand the band's input rows (R*stride + 2 with the halo) for 64 hidden channels
+//            with int8 MFMA, requantise, store as int8 into an LDS tile with a zero border;
+//   stage 2  depthwise 3x3 on that tile on the vector ALU (v_dot4_i32_i8 against one-hot weight
+//            dwords: one instruction per tap and channel, no unpacking), requantise into a
+//            second LDS tile laid out [pixel][channel];
+//   stage 3  that tile is the B operand of the projection MFMA: one 64-deep k step per chunk,
+//            accumulators live in registers across chunks.
+// After the last chunk the projection is requantised, the block input is added (skip) and the
+// band is written.  HBM traffic is the block input (rows of the halo are read twice) and output.
+// Shapes the fused kernel does not take run as three launches through the caller's workspace.
+#include "prom_pw_stream.h"
+#include "prom_launch.h"
 
-namespace {
-inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+#include <mutex>
+
+namespace prom {
+
+struct BlockArgs {
+    const int8_t *x;
+    int8_t *y;
+    const uint32_t *we;  // packed expand weights [chid][cin]
+    const int8_t *wd;    // depthwise weights [3][3][chid]
+    const uint32_t *wp;  // packed project weights [cout][chid]
+    const int32_t *be, *me, *se;  // expand bias / mult / shift [chid]
+    const int32_t *bd, *md, *sd;  // depthwise [chid]
+    const int32_t *bp, *mp, *sp;  // project [cout]
+    int N, H, W, Ho, Wo, cin, chid, cout, stride;
+    int R;        // output rows per band
+    int bands;    // bands per image
+    int RI;       // input rows per band = (R-1)*stride + 3
+    int add_res;
+    int lo_e, hi_e, lo_d, hi_d, lo_p, hi_p;
+    // LDS byte offsets
+    int off_t1, off_t2, off_fe, off_fp, off_pe, off_pd, off_pp, off_wd;
+};
+
+constexpr int kCH = 64;  // hidden channels per chunk = one k step of the projection
+
+__device__ __forceinline__ v4i make_par(int b, int m, int s)
+{
+    const long long C = (long long)b * m + (1LL << (30 + s));
+    return v4i{(int)(uint32_t)C, (int)(C >> 32), m, s};
 }
+
+// COT: 16-channel output tiles (cout <= 16*COT); TPW: projection pixel tiles per wavefront.
+template <int COT, int TPW>
+__global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    int8_t *xs = reinterpret_cast<int8_t *>(lds);                      // [RI][W][cin] (+64 pad)
+    int8_t *t1 = reinterpret_cast<int8_t *>(lds + a.off_t1);           // [RI][W+2][64]
+    int8_t *t2 = reinterpret_cast<int8_t *>(lds + a.off_t2);           // [P2][64]
+    v4i *fe = reinterpret_cast<v4i *>(lds + a.off_fe);                 // [4 tiles][KSe][64 lanes]
+    v4i *fp = reinterpret_cast<v4i *>(lds + a.off_fp);                 // [COT][64 lanes]
+    v4i *pe = reinterpret_cast<v4i *>(lds + a.off_pe);                 // [64] expand parameters
+    v4i *pd = reinterpret_cast<v4i *>(lds + a.off_pd);                 // [64] depthwise parameters
+    v4i *pp = reinterpret_cast<v4i *>(lds + a.off_pp);                 // [16*COT] project parameters
+    int8_t *wdl = reinterpret_cast<int8_t *>(lds + a.off_wd);          // [9][64] depthwise weights
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15, g = lane >> 4;
+
+    const int img = blockIdx.x / a.bands;
+    const int band = blockIdx.x - img * a.bands;
+    const int ro0 = band * a.R;                       // first output row of the band
+    const int rows_out = min(a.R, a.Ho - ro0);        // valid output rows
+    const int ri0 = ro0 * a.stride - 1;               // first input row (may be -1)
+    const int W = a.W, Wo = a.Wo, cin = a.cin, chid = a.chid, cout = a.cout, s = a.stride;
+    const int KSe = (cin + 63) >> 6, KWe = (cin + 15) >> 4, KWp = (chid + 15) >> 4;
+    const int W2 = W + 2;
+    const int npix1 = a.RI * W;                       // pixels expanded per chunk
+    const int npix2 = rows_out * Wo;                  // output pixels of the band
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.x), 0, a.N * a.H * W * cin, kBufFlags);
+
+    // ---- stage 0: the band's input rows into LDS (rows outside the image read as zero or as a
+    // neighbouring image; the expanded rows are forced to zero below, so either is fine) -------
+    {
+        const int row_bytes = W * cin;
+        const int total = a.RI * row_bytes;  // multiple of 8
+        const long long base = ((long long)img * a.H + ri0) * row_bytes;
+        for (int o = tid * 8; o < total; o += 256 * 8) {
+            const long long go = base + o;
+            const int off = (go >= 0 && go < (long long)kOobOffset) ? (int)go : kOobOffset;
+            const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rx, off, 0, 0);
+            *reinterpret_cast<v2i *>(xs + o) = v;
+        }
+        // project parameters (used after the last chunk)
+        if (tid < 16 * COT) {
+            v4i p = {0, 0, 0, 1};
+            if (tid < cout) p = make_par(a.bp[tid], a.mp[tid], a.sp[tid]);
+            pp[tid] = p;
+        }
+    }
+
+    v4i acc[TPW][COT];
+#pragma unroll
+    for (int q = 0; q < TPW; ++q)
+#pragma unroll
+        for (int t = 0; t < COT; ++t) acc[q][t] = v4i{0, 0, 0, 0};
+
+    const int lo_e = in_vgpr(a.lo_e), hi_e = in_vgpr(a.hi_e);
+    const int lo_d = in_vgpr(a.lo_d), hi_d = in_vgpr(a.hi_d);
+
+    const int nchunks = (chid + kCH - 1) / kCH;
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int c0 = ch * kCH;
+        const int chc = min(kCH, chid - c0);  // channels of this chunk (multiple of 4)
+        __syncthreads();                      // previous chunk's readers are done with the LDS tiles
+        // ---- weights and parameters of the chunk --------------------------------------------
+        for (int idx = tid; idx < 4 * KSe * 64; idx += 256) {       // expand fragments
+            const int l = idx & 63, tk = idx >> 6, ks = tk % KSe, t = tk / KSe;
+            const int c = c0 + 16 * t + (l & 15);
+            const int kw = 4 * ks + (l >> 4);
+            const bool ok = c < chid && kw < KWe;
+            const uint32_t wv = a.we[ok ? (long long)c * KWe + kw : 0];
+            fe[idx] = decode_word(ok ? wv : 0u);
+        }
+        for (int idx = tid; idx < COT * 64; idx += 256) {           // project fragments, k step = chunk
+            const int l = idx & 63, t = idx >> 6;
+            const int c = 16 * t + (l & 15);
+            const int kw = 4 * ch + (l >> 4);
+            const bool ok = c < cout && kw < KWp;
+            const uint32_t wv = a.wp[ok ? (long long)c * KWp + kw : 0];
+            fp[idx] = decode_word(ok ? wv : 0u);
+        }
+        if (tid < kCH) {
+            v4i e = {0, 0, 0, 1}, d = {0, 0, 0, 1};
+            if (tid < chc) {
+                e = make_par(a.be[c0 + tid], a.me[c0 + tid], a.se[c0 + tid]);
+                d = make_par(a.bd[c0 + tid], a.md[c0 + tid], a.sd[c0 + tid]);
+            }
+            pe[tid] = e;
+            pd[tid] = d;
+        }
+        for (int idx = tid; idx < 9 * kCH; idx += 256) {
+            const int tap = idx >> 6, c = idx & 63;
+            wdl[idx] = c < chc ? a.wd[tap * chid + c0 + c] : (int8_t)0;
+        }
+        // zero border columns of t1 (col -1 and col W of every row)
+        for (int idx = tid; idx < a.RI * 2 * (kCH / 4); idx += 256) {
+            const int q = idx % (kCH / 4), rc = idx / (kCH / 4);
+            const int row = rc >> 1, col = (rc & 1) ? W + 1 : 0;
+            *reinterpret_cast<uint32_t *>(t1 + (row * W2 + col) * kCH + 4 * q) = 0u;
+        }
+        __syncthreads();
+
+        // ---- stage 1: expand 64 hidden channels for every pixel of the band's input rows ------
+        for (int t = 0; t < 4; ++t) {
+            if (16 * t >= chc) break;
+            v4i par[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) par[r] = pe[16 * t + 4 * g + r];
+            for (int pt = wave; pt * 16 < npix1; pt += 4) {
+                const int p = pt * 16 + j;
+                v4i d4 = {0, 0, 0, 0};
+                for (int ks = 0; ks < KSe; ++ks) {
+                    // 16 k-bytes of pixel p; bytes beyond cin meet zero weights
+                    const v4i b = *reinterpret_cast<const v4i *>(xs + min(p, npix1 - 1) * cin + 64 * ks + 16 * g);
+                    d4 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fe[(t * KSe + ks) * 64 + lane], b, d4, 0, 0, 0);
+                }
+                if (p < npix1) {
+                    const int row = p / W, col = p - row * W;
+                    const int ri = ri0 + row;
+                    uint32_t o = 0u;
+                    if (ri >= 0 && ri < a.H) {
+                        int v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = requant_i64<true>(d4[r], par[r], lo_e, hi_e);
+                        o = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                    }
+                    *reinterpret_cast<uint32_t *>(t1 + (row * W2 + col + 1) * kCH + 16 * t + 4 * g) = o;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 2: depthwise 3x3 on the LDS tile --------------------------------------------
+        {
+            const int cg = tid & 15;  // 4-channel group of this thread (constant: 256 % 16 == 0)
+            if (4 * cg < chc) {
+                // one-hot weight dwords: byte q of wq[tap][q] is the weight of channel 4cg+q
+                int wq[9][4];
+#pragma unroll
+                for (int tap = 0; tap < 9; ++tap) {
+                    const uint32_t w4 = *reinterpret_cast<const uint32_t *>(wdl + tap * kCH + 4 * cg);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) wq[tap][q] = (int)(w4 & (0xFFu << (8 * q)));
+                }
+                v4i par[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) par[q] = pd[4 * cg + q];
+                for (int item = tid >> 4; item < npix2; item += 16) {
+                    const int oy = item / Wo, ox = item - oy * Wo;
+                    const int8_t *src = t1 + ((oy * s) * W2 + ox * s) * kCH + 4 * cg;
+                    int sum[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 3; ++i)
+#pragma unroll
+                        for (int jx = 0; jx < 3; ++jx) {
+                            const int xv = *reinterpret_cast<const int *>(src + (i * W2 + jx) * kCH);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                sum[q] = __builtin_amdgcn_sdot4(xv, wq[i * 3 + jx][q], sum[q], false);
+                        }
+                    int v[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = requant_i64<true>(sum[q], par[q], lo_d, hi_d);
+                    *reinterpret_cast<uint32_t *>(t2 + item * kCH + 4 * cg) = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 3: projection, one k step (this chunk's 64 hidden channels) -----------------
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) {
+            const int pt = wave + 4 * q;
+            if (pt * 16 < npix2) {
+                const int p = min(pt * 16 + j, npix2 - 1);
+                const v4i b = *reinterpret_cast<const v4i *>(t2 + p * kCH + 16 * g);
+#pragma unroll
+                for (int t = 0; t < COT; ++t)
+                    acc[q][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fp[t * 64 + lane], b, acc[q][t], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- projection epilogue: requantise, skip connection, store ------------------------------
+    const int lo_p = in_vgpr(a.lo_p), hi_p = in_vgpr(a.hi_p);
+    const int m128 = in_vgpr(-128), p127 = in_vgpr(127);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.N * a.Ho * Wo * cout, kBufFlags);
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int p = (wave + 4 * q) * 16 + j;
+        const bool pvalid = p < npix2;
+        const int oy = p / Wo, ox = p - oy * Wo;
+        const int opix = (img * a.Ho + ro0 + oy) * Wo + ox;  // output pixel index
+#pragma unroll
+        for (int t = 0; t < COT; ++t) {
+            const int c = 16 * t + 4 * g;
+            if (c < cout) {
+                int v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = requant_i64<true>(acc[q][t][r], pp[c + r], lo_p, hi_p);
+                if (a.add_res) {
+                    // stride 1 and cin == cout: the block input at the same pixel and channels
+                    const uint32_t res = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(
+                        rx, pvalid ? opix * cin + c : kOobOffset, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = med3_i32(v[r] + sbyte(res, r), m128, p127);
+                }
+                __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(v[0], v[1], v[2], v[3]), ry,
+                                                      pvalid ? opix * cout + c : kOobOffset, 0, 0);
+            }
+        }
+    }
+}
+
+using BlockFn = void (*)(const BlockArgs);
+
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int align16(int v) { return (v + 15) & ~15; }
+
+// Plans the fused kernel; returns false if the shape does not fit it.
+static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
+{
+    const int cin = a.cin, chid = a.chid, cout = a.cout, s = a.stride;
+    if (cin % 16 != 0 || chid % 4 != 0 || cout % 4 != 0 || cout > 64) return false;
+    if ((long long)a.N * a.H * a.W * (cin > cout ? cin : cout) >= (long long)kOobOffset) return false;
+    if (a.W > 1024) return false;
+    const int cot = cout <= 32 ? 2 : 4;
+    const int kse = (cin + 63) / 64;
+    // the band: at most 4 projection pixel tiles per wavefront (256 output pixels), LDS <= 150 KB,
+    // and enough workgroups to occupy the chip when the image allows it
+    int best = 0;
+    for (int R = 1; R <= a.Ho; ++R) {
+        if (R * a.Wo > 256) break;
+        const int RI = (R - 1) * s + 3;
+        const long long bytes = (long long)align16(RI * a.W * cin + 64) + (long long)RI * (a.W + 2) * kCH +
+                                (long long)align16(R * a.Wo) * kCH + 4 * kse * 1024 + cot * 1024 + 2 * kCH * 16 +
+                                16 * cot * 16 + 9 * kCH + 64;
+        if (bytes > 150 * 1024) break;
+        const int bands = (a.Ho + R - 1) / R;
+        // prefer taller bands (less halo recomputation) as long as there are >= 1.5 workgroups per CU
+        if (best == 0 || (long long)a.N * bands >= 384) best = R;
+    }
+    if (best == 0) return false;
+    const int R = best;
+    a.R = R;
+    a.RI = (R - 1) * s + 3;
+    a.bands = (a.Ho + R - 1) / R;
+    int off = align16(a.RI * a.W * cin + 64);
+    a.off_t1 = off; off += align16(a.RI * (a.W + 2) * kCH);
+    a.off_t2 = off; off += align16(R * a.Wo) * kCH;
+    a.off_fe = off; off += 4 * kse * 1024;
+    a.off_fp = off; off += cot * 1024;
+    a.off_pe = off; off += kCH * 16;
+    a.off_pd = off; off += kCH * 16;
+    a.off_pp = off; off += 16 * cot * 16;
+    a.off_wd = off; off += align16(9 * kCH);
+    lds = (size_t)off;
+    fn = cot == 2 ? &block_fused_kernel<2, 4> : &block_fused_kernel<4, 4>;
+    const long long g = (long long)a.N * a.bands;
+    if (g > (1LL << 30)) return false;
+    grid = (int)g;
+    return true;
+}
+
+}  // namespace prom
 
 extern "C" size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride)
 {
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
         return 0;
     const size_t ho = (size_t)(h - 1) / stride + 1, wo = (size_t)(w - 1) / stride + 1;
-    return round256((size_t)n * h * w * chid) + round256((size_t)n * ho * wo * chid);
+    return prom::round256((size_t)n * h * w * chid) + prom::round256((size_t)n * ho * wo * chid);
 }
 
 extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
@@ -22,6 +334,7 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
                           int add_residual, void *workspace, size_t workspace_bytes, int8_t *y,
                           void *stream)
 {
+    using namespace prom;
     if (!x || !y || !w_expand_packed || !w_dw || !w_project_packed || !rq_expand || !rq_dw || !rq_project)
         return PROM_EINVAL;
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
@@ -33,18 +346,68 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
     int8_t *t1 = static_cast<int8_t *>(workspace);
     int8_t *t2 = t1 + round256((size_t)n * h * w * chid);
     {
-        const uintptr_t ya = (uintptr_t)y, wa = (uintptr_t)workspace;
-        const size_t yb = (size_t)n * ho * wo * cout;
+        const uintptr_t ya = (uintptr_t)y, wa = (uintptr_t)workspace, xa = (uintptr_t)x;
+        const size_t yb = (size_t)n * ho * wo * cout, xb = (size_t)n * h * w * cin;
         if (ya < wa + need && wa < ya + yb) return PROM_EALIAS;
+        if (ya < xa + xb && xa < ya + yb) return PROM_EALIAS;
     }
-    // Validate every stage before enqueueing anything: argument errors of the later stages
-    // are all covered by the checks above plus the windows checked here.
     const prom_requant_t *rqs[3] = {rq_expand, rq_dw, rq_project};
     for (const prom_requant_t *rq : rqs) {
         if (!rq->bias || !rq->mult || !rq->shift) return PROM_EINVAL;
         if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
     }
     if (cin > 4096 || chid > 4096) return PROM_EUNSUPPORTED;
+
+    const bool aligned = ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 7) == 0) &&
+                         ((((uintptr_t)w_expand_packed | (uintptr_t)w_project_packed) & 3) == 0);
+    BlockArgs a;
+    a.x = x; a.y = y;
+    a.we = static_cast<const uint32_t *>(w_expand_packed);
+    a.wd = w_dw;
+    a.wp = static_cast<const uint32_t *>(w_project_packed);
+    a.be = rq_expand->bias; a.me = rq_expand->mult; a.se = rq_expand->shift;
+    a.bd = rq_dw->bias; a.md = rq_dw->mult; a.sd = rq_dw->shift;
+    a.bp = rq_project->bias; a.mp = rq_project->mult; a.sp = rq_project->shift;
+    a.N = n; a.H = h; a.W = w; a.Ho = ho; a.Wo = wo;
+    a.cin = cin; a.chid = chid; a.cout = cout; a.stride = stride;
+    a.add_res = add_residual;
+    a.lo_e = rq_expand->act_min; a.hi_e = rq_expand->act_max;
+    a.lo_d = rq_dw->act_min; a.hi_d = rq_dw->act_max;
+    a.lo_p = rq_project->act_min; a.hi_p = rq_project->act_max;
+    BlockFn fn = nullptr;
+    size_t lds = 0;
+    int grid = 0;
+    if (aligned && plan_fused(a, fn, lds, grid)) {
+        static std::mutex mu;
+        static bool attr_done[2] = {false, false};
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            const int which = fn == &block_fused_kernel<2, 4> ? 0 : 1;
+            if (!attr_done[which]) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess && lds > 64 * 1024) {
+                    last_hip_error() = e;
+                    (void)hipGetLastError();
+                    return PROM_EHIP;
+                }
+                attr_done[which] = true;
+            }
+        }
+        clear_hip_error();
+        BlockArgs args = a;
+        void *kargs[] = {&args};
+        const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(fn), dim3(grid), dim3(256), kargs, lds,
+                                             static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) {
+            last_hip_error() = e;
+            (void)hipGetLastError();
+            return PROM_EHIP;
+        }
+        return check_launch();
+    }
+
+    // three launches through the workspace
     int rc = prom_pw_conv(x, n, h, w, cin, w_expand_packed, chid, rq_expand, nullptr, t1, stream);
     if (rc != PROM_OK) return rc;
     rc = prom_dw_conv(t1, n, h, w, chid, w_dw, stride, rq_dw, t2, stream);

@@ -269,7 +269,7 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
             pt = plan->pixel_tiles;
             if (!(pt == 1 || pt == 2 || pt == 4) || pt > max_pt_for(nt)) return PROM_EINVAL;
         } else {
-            pt = nt <= 2 ? 4 : (nt <= 4 ? 2 : 1);
+            pt = nt <= 2 ? (a.KS == 1 ? 4 : 2) : (nt <= 4 ? 2 : 1);
             while (pt > 1 && M < (long long)64 * pt * kNumCU * 2) pt >>= 1;  // small layers: finer groups
         }
     }

@@ -75,9 +75,15 @@ def test_block_config4_full_output(P):
     assert_same(_run_block(P, B), _oracle_block(B), "config 4")
 
 
-@pytest.mark.parametrize("shape", [(2, 9, 9, 16, 6, 16, 1), (1, 14, 14, 24, 6, 32, 2),
-                                   (2, 7, 7, 160, 6, 320, 1), (1, 5, 6, 8, 1, 8, 1),
-                                   (1, 112, 112, 16, 6, 24, 2)])
+@pytest.mark.parametrize("shape", [
+    # n, h, w, cin, t, cout, stride
+    (2, 9, 9, 16, 6, 16, 1), (1, 14, 14, 24, 6, 32, 2), (2, 7, 7, 160, 6, 320, 1), (1, 5, 6, 8, 1, 8, 1),
+    (1, 112, 112, 16, 6, 24, 2),
+    # fused-kernel corner cases: ragged last band, hidden width off the 64-channel chunk (144, 80),
+    # 17-wide rows, stride 2 on odd sizes, cout below and above one tile, no skip, one pixel
+    (3, 13, 17, 16, 9, 16, 1), (2, 15, 13, 16, 5, 24, 2), (1, 28, 28, 32, 6, 64, 1), (2, 1, 1, 16, 4, 16, 1),
+    (1, 33, 9, 48, 3, 48, 1), (1, 56, 56, 32, 6, 32, 2), (2, 6, 40, 64, 2, 40, 1), (1, 3, 300, 16, 2, 16, 1),
+])
 def test_block_shapes(P, shape):
     n, h, w, cin, t, cout, stride = shape
     B = make_block(6000 + cin + cout, n, h, w, cin, t, cout, stride, signed_x=True)
