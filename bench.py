@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
     ap.add_argument("--cpu-sample-images", type=int, default=16)
+    ap.add_argument("--no-batching", action="store_true",
+                    help="one launch per layer (the library's batching of small independent layers off)")
     ap.add_argument("--streams", type=int, default=4,
                     help="streams of the extra 'concurrent' leg (the 34 layers are independent)")
     ap.add_argument("--ab", choices=["both", "mfma", "addsub"], default=None,
@@ -113,31 +115,51 @@ def main():
     log(f"[bench] workload built in {time.time() - t_setup:.1f}s: {len(layers)} layers, "
         f"{total_bytes / 1e6:.1f} MB algorithmic, {total_ops / 1e9:.2f} Gop per step")
 
-    # dominant kernel variant = the template instantiation moving the most bytes
-    by_variant = {}
+    # ---- launch groups: prom_pw_conv_sequence puts consecutive small independent layers into
+    # one launch (kernel prom::pw_batch_kernel); every other layer is its own launch.  A group is
+    # what one kernel name covers: a batch, or all single launches of one template instantiation.
     for l in layers:
-        by_variant.setdefault(l["variant"], []).append(l)
-    dom_variant = max(by_variant, key=lambda v: sum(l["bytes"] for l in by_variant[v]))
-    dom_name = kernel_name(dom_variant)
-
-    # segments: maximal runs of non-dominant layers, and each dominant layer alone with events
-    segments = []
-    run = []
+        s_ = l["shape"]
+        l["batch"] = P.prom_pw_batchable(args.batch, s_.hw, s_.hw, s_.cin, s_.cout) and not args.no_batching
+    runs = []  # consecutive layers that go into one PwSequence call
     for l in layers:
-        tup = (l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"])
-        if l["variant"] == dom_variant:
-            if run:
-                segments.append((False, P.PwSequence(run), None))
-                run = []
-            segments.append((True, P.PwSequence([tup]), l))
+        if l["batch"] and runs and runs[-1][0]["batch"] and len(runs[-1]) < 32:
+            runs[-1].append(l)
         else:
-            run.append(tup)
-    if run:
-        segments.append((False, P.PwSequence(run), None))
-    n_dom = sum(1 for s in segments if s[0])
+            runs.append([l])
+    BATCH_NAME = "prom::pw_batch_kernel(prom::PwBatchArgs)"
+    groups = {}
+    for r in runs:
+        name = BATCH_NAME if len(r) > 1 else kernel_name(r[0]["variant"])
+        g = groups.setdefault(name, {"bytes": 0, "launches": 0, "layers": []})
+        g["bytes"] += sum(l["bytes"] for l in r)
+        g["launches"] += 1
+        g["layers"] += [l["shape"].name for l in r]
+    dom_name = max(groups, key=lambda k: groups[k]["bytes"])
+    segments = []
+    for r in runs:
+        name = BATCH_NAME if len(r) > 1 else kernel_name(r[0]["variant"])
+        seq = P.PwSequence([(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"]) for l in r])
+        segments.append((name == dom_name, seq))
+    # merge neighbouring non-dominant segments into single host calls (not when batching is off:
+    # a multi-layer call would batch again)
+    merged, acc_layers = [], []
+    for (is_dom, seq), r in zip(segments, runs):
+        if is_dom or args.no_batching:
+            if acc_layers:
+                merged.append((False, P.PwSequence(acc_layers)))
+                acc_layers = []
+            merged.append((is_dom, seq))
+        else:
+            acc_layers += [(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"]) for l in r]
+    if acc_layers:
+        merged.append((False, P.PwSequence(acc_layers)))
+    segments = merged
+    log(f"[bench] {len(runs)} launches per step; dominant kernel: {dom_name} "
+        f"({groups[dom_name]['launches']} launch(es), {groups[dom_name]['bytes'] / 1e6:.1f} MB per step)")
 
     def one_step(events=None):
-        for is_dom, seq, _ in segments:
+        for is_dom, seq in segments:
             if is_dom and events is not None:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
@@ -162,7 +184,7 @@ def main():
     value = total_ops / (ms_per_step * 1e-3) / 1e9  # Gop/s
     dom_ms = [e0.elapsed_time(e1) for e0, e1 in events]
     dom_avg_us = 1e3 * sum(dom_ms) / len(dom_ms)
-    dom_bytes_per_launch = sum(l["bytes"] for l in by_variant[dom_variant]) / n_dom
+    dom_bytes_per_launch = groups[dom_name]["bytes"] / groups[dom_name]["launches"]
     dom_achieved = dom_bytes_per_launch / (dom_avg_us * 1e-6) / 1e9
 
     # ---- per-layer table: a separate, instrumented pass (events around every launch) -------
@@ -264,8 +286,8 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": "configs[3]: the 34 ternary pointwise layers of MobileNetV2 1.0 (224x224), "
-                               f"batch {args.batch}, int8 NHWC, one launch per layer",
-                   "batch": args.batch, "layers": len(layers)},
+                               f"batch {args.batch}, int8 NHWC, through prom_pw_conv_sequence",
+                   "batch": args.batch, "layers": len(layers), "launches_per_step": len(runs)},
         "sweep": {"algorithmic_bytes": total_bytes, "dense_equiv_ops": total_ops,
                   "gbs": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                   "frac_hbm_roofline": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -274,7 +296,7 @@ def main():
                   "copy_kernel_gbs": round(copy_gbs, 0),
                   "layers_overlapped_on_streams": conc},
         "roofline": {"bound": "hbm", "kernel": dom_name,
-                     "layers": [l["shape"].name for l in by_variant[dom_variant]],
+                     "layers": groups[dom_name]["layers"],
                      "achieved": round(dom_achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom_achieved / HBM_PEAK_GBS, 4),
                      "avg_launch_us": round(dom_avg_us, 2),
@@ -303,7 +325,11 @@ def main():
             t_cpu += time.perf_counter() - tc
             ops += 2 * ns * s.hw * s.hw * s.cin * s.cout
             got = l["y"][:ns].cpu().numpy()
-            mismatches += int((got != want).sum())
+            bad = int((got != want).sum())
+            if bad:
+                where = np.argwhere(got != want)
+                log(f"[bench] PARITY: layer {s.name} differs from the oracle in {bad} elements, first at {where[0].tolist()}, last at {where[-1].tolist()}")
+            mismatches += bad
         result["cpu_baseline"] = {"value": round(ops / t_cpu / 1e9, 2), "unit": "Gop/s",
                                   "cores": oracle.max_threads(), "kind": "oracle",
                                   "sample": f"first {ns} of {args.batch} images of every layer "

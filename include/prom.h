@@ -132,10 +132,18 @@ typedef struct {
     int8_t *y;
 } prom_pw_layer_t;
 
-/* Enqueue `count` pointwise layers back to back on `stream` (one host call instead of
- * `count`).  All layers are validated first; on any error nothing is enqueued and the index
- * of the offending layer is stored in *bad_layer when bad_layer is not NULL. */
+/* Enqueue `count` pointwise layers on `stream` with one host call.  The results are those of
+ * running the layers one after the other in the given order.  Consecutive small layers that do
+ * not touch each other's data (no layer's output overlaps another's input, residual, weights
+ * or output) are put into one kernel launch and run concurrently, which hides their launch,
+ * first-load and write-back latencies; anything else is launched layer by layer.  All layers
+ * are validated first; on an argument error nothing is enqueued and the index of the offending
+ * layer is stored in *bad_layer when bad_layer is not NULL. */
 int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream);
+
+/* 1 if a layer of this shape (4-byte aligned pointers assumed) is small enough and regular
+ * enough to join a batched launch of prom_pw_conv_sequence, 0 if not, negative on bad shapes. */
+int prom_pw_batchable(int n, int h, int w, int cin, int cout);
 
 /* The same layer computed by the other design that was evaluated: multiplication-free
  * accumulation on the vector ALU (sums of the input bytes whose weight is +1 / -1, paper

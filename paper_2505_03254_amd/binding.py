@@ -87,6 +87,8 @@ def load_library():
     lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC)]
     lib.prom_pw_conv_sequence.restype = ci
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_pw_batchable.restype = ci
+    lib.prom_pw_batchable.argtypes = [ci, ci, ci, ci, ci]
     lib.prom_copy_bytes.restype = ci
     lib.prom_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.prom_strerror.restype = ctypes.c_char_p
@@ -289,6 +291,13 @@ def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:
     _check(load_library().prom_pw_plan_query(n, h, w, cin, cout, ctypes.byref(p)), "prom_pw_plan_query")
     return {"tiles_per_wave": p.tiles_per_wave, "pixel_tiles": p.pixel_tiles,
             "workgroups": p.workgroups, "load_bytes": p.reserved}
+
+
+def prom_pw_batchable(n: int, h: int, w: int, cin: int, cout: int) -> bool:
+    rc = load_library().prom_pw_batchable(n, h, w, cin, cout)
+    if rc < 0:
+        raise PromError(rc, "prom_pw_batchable")
+    return bool(rc)
 
 
 class PwSequence:

@@ -90,6 +90,33 @@ __global__ __launch_bounds__(256) void pw_generic_kernel(const PwArgs a)
     }
 }
 
+// ============================================================================================
+// Several independent layers in one launch: workgroups [start[i], start[i+1]) (both multiples
+// of 8) run layer i with the plan NT = 4, PT = 1 and 16-byte activation loads.  The launch,
+// prologue and write-back latencies of one layer overlap with the streaming of the others.
+constexpr int kMaxBatch = 32;
+constexpr int kBatchNT = 4;
+#ifndef PROM_BATCH_DEPTH
+#define PROM_BATCH_DEPTH 4
+#endif
+constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flight per wavefront
+struct PwBatchArgs {
+    int count;
+    int start[kMaxBatch + 1];
+    PwArgs layer[kMaxBatch];
+};
+
+__global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int bid = blockIdx.x;
+    int i = 0;
+    while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
+    const int local = bid - b.start[i];
+    const int nblk = b.start[i + 1] - b.start[i];
+    pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth>(b.layer[i], logical_block_id(local, nblk), lds_raw);
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst,
                                                    long long n16)
 {
@@ -374,29 +401,145 @@ extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_p
     return PROM_OK;
 }
 
+namespace prom {
+
+// A layer can join a batched launch if the streaming kernel takes it with 16-byte loads, every
+// chunk row is whole 16-byte pieces, and it is small enough that its own launch would be
+// dominated by fixed costs.
+constexpr long long kBatchMaxBytes = 32LL << 20;
+constexpr long long kBatchBytesPerWg = 128LL << 10;  // activation bytes one workgroup of a batch moves
+
+static bool batchable(const PwLaunch &L)
+{
+    const PwArgs &a = L.a;
+    if (!L.fast || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
+    if (kBatchNT * a.KS * 1024 > kLdsBudget) return false;
+    return (long long)a.M * (a.K + a.Nc) <= kBatchMaxBytes;
+}
+
+struct Range { uintptr_t lo, hi; };
+static bool hits(const Range &p, const Range &q) { return p.lo < q.hi && q.lo < p.hi; }
+
+// true if running `b` concurrently with `a` could change a result: one writes what the other
+// reads or writes
+static bool conflicts(const PwArgs &a, const PwArgs &b)
+{
+    const Range ya{(uintptr_t)a.y, (uintptr_t)a.y + (size_t)a.M * a.Nc};
+    const Range yb{(uintptr_t)b.y, (uintptr_t)b.y + (size_t)b.M * b.Nc};
+    const Range xa{(uintptr_t)a.x, (uintptr_t)a.x + (size_t)a.M * a.K};
+    const Range xb{(uintptr_t)b.x, (uintptr_t)b.x + (size_t)b.M * b.K};
+    if (hits(ya, yb) || hits(ya, xb) || hits(yb, xa)) return true;
+    if (b.residual && hits(ya, Range{(uintptr_t)b.residual, (uintptr_t)b.residual + (size_t)b.M * b.Nc})) return true;
+    if (a.residual && hits(yb, Range{(uintptr_t)a.residual, (uintptr_t)a.residual + (size_t)a.M * a.Nc})) return true;
+    // parameters and weights are read-only inputs: a layer writing into another's weights is
+    // not something the single-layer entry point allows either, but stay safe
+    const Range wa{(uintptr_t)a.wq, (uintptr_t)a.wq + (size_t)a.Nc * a.KW * 4};
+    const Range wb{(uintptr_t)b.wq, (uintptr_t)b.wq + (size_t)b.Nc * b.KW * 4};
+    return hits(ya, wb) || hits(yb, wa);
+}
+
+static int launch_batch(const PwLaunch *const *members, int count, hipStream_t st)
+{
+    static thread_local PwBatchArgs b;
+    b.count = count;
+    size_t lds = 0;
+    int start = 0;
+    for (int i = 0; i < count; ++i) {
+        PwArgs a = members[i]->a;  // re-planned: NT = kBatchNT, PT = 1
+        const int n_tiles = (a.Nc + 15) / 16;
+        a.n_chunks = (n_tiles + kBatchNT - 1) / kBatchNT;
+        a.units = (a.M + 15) / 16;
+        const long long wg_units = (a.units + 3) / 4;
+        const long long work = (long long)a.M * (a.K + 16 * kBatchNT);  // bytes one chunk moves
+        long long wgs = (work + kBatchBytesPerWg - 1) / kBatchBytesPerWg;
+        if (wgs < 1) wgs = 1;
+        if (wgs > wg_units) wgs = wg_units;
+        a.wg_per_chunk = (int)wgs;
+        const int nblk = (int)((wgs * a.n_chunks + 7) / 8 * 8);
+        b.layer[i] = a;
+        b.start[i] = start;
+        start += nblk;
+        const size_t l = lds_bytes_fast(kBatchNT, a.KS);
+        if (l > lds) lds = l;
+    }
+    b.start[count] = start;
+    if (resident_workgroups(reinterpret_cast<KernelFn>(&pw_batch_kernel), lds) < 1) return PROM_EHIP;
+    clear_hip_error();
+    void *kargs[] = {&b};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&pw_batch_kernel), dim3(start), dim3(256),
+                                         kargs, lds, st);
+    if (e != hipSuccess) {
+        last_hip_error() = e;
+        (void)hipGetLastError();
+        return PROM_EHIP;
+    }
+    return check_launch();
+}
+
+}  // namespace prom
+
+extern "C" int prom_pw_batchable(int n, int h, int w, int cin, int cout)
+{
+    prom::PwLaunch L;
+    const int rc = prom::pw_prepare(nullptr, n, h, w, cin, nullptr, cout, nullptr, nullptr, nullptr,
+                                    nullptr, nullptr, 0, true, L);
+    if (rc != PROM_OK) return rc;
+    return prom::batchable(L) ? 1 : 0;
+}
+
 extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream)
 {
+    using namespace prom;
     if (!layers || count <= 0) return PROM_EINVAL;
     constexpr int kMaxSeq = 256;
     if (count > kMaxSeq) return PROM_EUNSUPPORTED;
-    static thread_local prom::PwLaunch plans[kMaxSeq];
+    static thread_local PwLaunch plans[kMaxSeq];
     for (int i = 0; i < count; ++i) {
         const prom_pw_layer_t &l = layers[i];
-        const int rc = prom::pw_prepare(l.x, l.n, l.h, l.w, l.cin, l.w_packed, l.cout, &l.rq, l.residual,
-                                        l.y, nullptr, nullptr, 0, false, plans[i]);
+        const int rc = pw_prepare(l.x, l.n, l.h, l.w, l.cin, l.w_packed, l.cout, &l.rq, l.residual,
+                                  l.y, nullptr, nullptr, 0, false, plans[i]);
         if (rc != PROM_OK) {
             if (bad_layer) *bad_layer = i;
             return rc;
         }
     }
+    // Results are those of running the layers one after the other.  Small layers that do not
+    // touch each other's data wait in a pending batch, which becomes one launch where its layers
+    // run concurrently.  A layer that conflicts with a pending one forces the batch out first; a
+    // larger layer that does not may overtake it.
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const PwLaunch *pending[kMaxBatch];
+    int npending = 0;
+    int first_pending = 0;
+    auto flush = [&]() -> int {
+        int rc = PROM_OK;
+        if (npending == 1)
+            rc = pw_launch(*pending[0], st);
+        else if (npending > 1)
+            rc = launch_batch(pending, npending, st);
+        npending = 0;
+        if (rc != PROM_OK && bad_layer) *bad_layer = first_pending;
+        return rc;
+    };
     for (int i = 0; i < count; ++i) {
-        const int rc = prom::pw_launch(plans[i], static_cast<hipStream_t>(stream));
-        if (rc != PROM_OK) {
-            if (bad_layer) *bad_layer = i;
-            return rc;
+        bool clash = npending == kMaxBatch && batchable(plans[i]);
+        for (int k = 0; k < npending && !clash; ++k) clash = conflicts(pending[k]->a, plans[i].a);
+        if (clash) {
+            const int rc = flush();
+            if (rc != PROM_OK) return rc;
+        }
+        if (batchable(plans[i])) {
+            if (npending == 0) first_pending = i;
+            pending[npending++] = &plans[i];
+        } else {
+            const int rc = pw_launch(plans[i], st);
+            if (rc != PROM_OK) {
+                if (bad_layer) *bad_layer = i;
+                return rc;
+            }
         }
     }
-    return PROM_OK;
+    return flush();
 }
 
 extern "C" int prom_copy_bytes(const void *src, void *dst, size_t nbytes, void *stream)

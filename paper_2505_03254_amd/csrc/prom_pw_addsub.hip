@@ -133,7 +133,8 @@ __global__ __launch_bounds__(256) void pw_addsub_kernel(const AddSubArgs a)
                     go = row * Nc + 16 * (q - row * per_row);
                 }
                 const v4i v = *reinterpret_cast<const v4i *>(stage + 16 * q);
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, go, tile_off, 0);
+                // tile offset in the vector offset: see the note at the store of the streaming kernel
+                __builtin_amdgcn_raw_buffer_store_b128(v, ry, go + tile_off, 0, 0);
             }
         } else {
             for (int q = lane; q < 16 * RW; q += 64) {  // dword pieces

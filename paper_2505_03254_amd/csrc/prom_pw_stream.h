@@ -151,11 +151,11 @@ __device__ __forceinline__ int requant_i64(int accv, const v4i &pr, int lo, int 
 
 // XCD-aware logical workgroup id: consecutive hardware ids go round-robin over the 8 XCDs;
 // make logical neighbours (the chunks of one pixel range) land on the same XCD and L2.
-__device__ __forceinline__ int logical_block_id()
+__device__ __forceinline__ int logical_block_id(int bid, int nblk /* multiple of 8 */)
 {
-    const int nblk = gridDim.x;  // multiple of 8
-    return (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+    return (bid & 7) * (nblk >> 3) + (bid >> 3);
 }
+__device__ __forceinline__ int logical_block_id() { return logical_block_id(blockIdx.x, gridDim.x); }
 
 // Depth of the activation prefetch ring (load groups in flight per wavefront).
 template <int PT> __host__ __device__ constexpr int ring_depth() { return PT == 1 ? 4 : 3; }
@@ -182,12 +182,11 @@ constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled
 //   FULLW: cout % (16*NT) == 0, every chunk is 16*NT valid channels wide (no per-lane channel
 //          conditions, compile-time staging geometry).
 // ============================================================================================
-template <int NT, int PT, int XMODE, bool KS1, bool FULLW>
-__global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
+// `lid` is the workgroup's logical id within this layer's grid (see logical_block_id).
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>()>
+__device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
-    constexpr int D = ring_depth<PT>();
     constexpr int NI = (NT + 3) / 4;  // 16-byte store instructions per staged tile
-    extern __shared__ __align__(16) unsigned char lds_raw[];
     const int KS = KS1 ? 1 : a.KS;
     v4i *frag = reinterpret_cast<v4i *>(lds_raw);  // [NT][KS][64 lanes] decoded A operands
     v4i *lpar = frag + NT * KS * 64;               // [NT][4 g][4 r] requantisation parameters
@@ -197,7 +196,6 @@ __global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
     const int j = lane & 15;  // pixel within a 16-pixel tile
     const int g = lane >> 4;  // k group on the input side, channel group on the output side
 
-    const int lid = logical_block_id();
     const int chunk = lid % a.n_chunks;
     const int wg = lid / a.n_chunks;
     if (wg >= a.wg_per_chunk) return;
@@ -242,19 +240,19 @@ __global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
     v4i ring[D][PT];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
-
     stage_weights<NT, true>(a, cbase, frag, lpar);
 
     // per-lane parameters: 4 channels per tile slot.  The lanes of a wavefront hold every channel
     // of the chunk between them, so a wavefront can see by itself whether any shift is 0 and
     // then takes the general form of the requantisation; otherwise .w holds shift-1.
     v4i par[NT][4];
+    const v4i *lpg = lpar + g * 4;
     bool sh0 = false;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            par[t][r] = lpar[(t * 4 + g) * 4 + r];
+            par[t][r] = lpg[t * 16 + r];
             sh0 |= par[t][r][3] == 0;
         }
     const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
@@ -295,103 +293,125 @@ __global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
     const unsigned ystep = (unsigned)Wv * (16 * PT) * (unsigned)Nc;
 
     const int my_groups = w0 < a.units ? (a.units - w0 + Wv - 1) / Wv : 0;
-    const int outer = (my_groups * KS + D - 1) / D;
+    const int total_steps = my_groups * KS;
+    const int full_rounds = total_steps / D;
+    const int tail_steps = total_steps - full_rounds * D;
     const v4i *fl = frag + lane;
 
-    // ---- main loop: D ring slots per iteration, straight-line; steps past the end of this
-    // wavefront's work load zeros and store nothing (their offsets are beyond the tensor).
-    // The loop is instantiated per (residual, general shift) so that its body has no branch
-    // on either. ------------------------------------------------------------------------------
+    // ---- main loop: D ring slots per round, straight-line.  Refills past the end of this
+    // wavefront's work read zeros (their offsets are beyond the tensor) and are never used.
+    // The last total_steps % D steps run one at a time on slot 0 with the ring rotated down.
+    // The loop is instantiated per (residual, general shift) so that its body has no branch on
+    // either. ------------------------------------------------------------------------------------
     auto run = [&](auto has_res_tag, auto general_tag) {
         constexpr bool HAS_RES = decltype(has_res_tag)::value;
         constexpr bool GENERAL = decltype(general_tag)::value;
         v4i acc[PT][NT];
         const v4i zero4 = {0, 0, 0, 0};
         int ck = 0;
-        for (int it = 0; it < outer; ++it) {
+        auto step = [&](v4i(&slot)[PT], auto refill_tag) {
+            constexpr bool REFILL = decltype(refill_tag)::value;
+            // opaque offset: the fragment reads stay inside the loop (4 registers in flight per
+            // tile) instead of being hoisted into 4*NT*KS registers when the weights are loop-invariant
+            int fo = ck * 64;
+            asm volatile("" : "+v"(fo));
+            const v4i *fk = fl + fo;
+            if (KS1 || ck == 0) {
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const v4i *fk = fl + ck * 64;
-                if (KS1 || ck == 0) {
+                for (int t = 0; t < NT; ++t) {
+                    const v4i wfrag = fk[t * KS * 64];
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const v4i wfrag = fk[t * KS * 64];
-#pragma unroll
-                        for (int p = 0; p < PT; ++p)
-                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, ring[d][p], zero4, 0, 0, 0);
-                    }
-                } else {
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const v4i wfrag = fk[t * KS * 64];
-#pragma unroll
-                        for (int p = 0; p < PT; ++p)
-                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, ring[d][p], acc[p][t], 0, 0, 0);
-                    }
+                    for (int p = 0; p < PT; ++p)
+                        acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, slot[p], zero4, 0, 0, 0);
                 }
-                load_group(ring[d]);  // refill this slot with the group D steps ahead
-                if (KS1 || ++ck == KS) {
-                    ck = 0;
+            } else {
 #pragma unroll
-                    for (int p = 0; p < PT; ++p) {
-                        const int tile_off = (int)(ytile + (unsigned)((16 * p) * Nc));
+                for (int t = 0; t < NT; ++t) {
+                    const v4i wfrag = fk[t * KS * 64];
 #pragma unroll
-                        for (int t0 = 0; t0 < NT; t0 += grp_size<NT>(t0)) {
-                            const int S = grp_size<NT>(t0);
-                            const int cl = chan_of<NT>(t0, g, 0);  // lane's first channel of the group
-                            uint32_t res[4] = {0, 0, 0, 0};
-                            if constexpr (HAS_RES) {
-                                const int ro = j * Nc + cl;
-                                if (S == 4) {
-                                    const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, tile_off, 0);
-                                    res[0] = v[0]; res[1] = v[1]; res[2] = v[2]; res[3] = v[3];
-                                } else if (S == 2) {
-                                    const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, tile_off, 0);
-                                    res[0] = v[0]; res[1] = v[1];
-                                } else {
-                                    res[0] = __builtin_amdgcn_raw_buffer_load_b32(rr, ro, tile_off, 0);
-                                }
-                            }
-                            uint32_t out[4] = {0, 0, 0, 0};
-#pragma unroll
-                            for (int tt = 0; tt < 4; ++tt) {
-                                if (tt < S) {
-                                    int v[4];
-#pragma unroll
-                                    for (int r = 0; r < 4; ++r)
-                                        v[r] = requant_i64<GENERAL>(acc[p][t0 + tt][r], par[t0 + tt][r], lo, hi);
-                                    if constexpr (HAS_RES) {
-#pragma unroll
-                                        for (int r = 0; r < 4; ++r)
-                                            v[r] = med3_i32(v[r] + sbyte(res[tt], r), m128, p127);
-                                    }
-                                    out[tt] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
-                                }
-                            }
-                            // stage the lane's dwords at [pixel j][channel cl..] of the wavefront's tile
-                            unsigned char *sp = stage + j * RW + cl;
-                            const bool full = FULLW || cl + 4 * S <= RW;
-                            if (full && S == 4 && (FULLW || rw16)) {
-                                *reinterpret_cast<v4i *>(sp) = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
-                            } else if (full && S == 2 && (FULLW || rw8)) {
-                                *reinterpret_cast<v2i *>(sp) = v2i{(int)out[0], (int)out[1]};
-                            } else {
-#pragma unroll
-                                for (int tt = 0; tt < 4; ++tt)
-                                    if (tt < S && (FULLW || cl + 4 * tt + 4 <= RW))
-                                        *reinterpret_cast<uint32_t *>(sp + 4 * tt) = out[tt];
-                            }
-                        }
-                        // write the staged tile; pieces outside the tile or the tensor are dropped
-#pragma unroll
-                        for (int i = 0; i < NI; ++i) {
-                            const v4i v = *reinterpret_cast<const v4i *>(stage + (i * 64 + lane) * 16);
-                            __builtin_amdgcn_raw_buffer_store_b128(v, ry, goff[i], tile_off, 0);
-                        }
-                    }
-                    ytile = min(ytile + ystep, (unsigned)kOobOffset);
+                    for (int p = 0; p < PT; ++p)
+                        acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, slot[p], acc[p][t], 0, 0, 0);
                 }
             }
+            if constexpr (REFILL) load_group(slot);  // refill this slot with the group D steps ahead
+            if (KS1 || ++ck == KS) {
+                ck = 0;
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    const int tile_off = (int)(ytile + (unsigned)((16 * p) * Nc));
+#pragma unroll
+                    for (int t0 = 0; t0 < NT; t0 += grp_size<NT>(t0)) {
+                        const int S = grp_size<NT>(t0);
+                        const int cl = chan_of<NT>(t0, g, 0);  // lane's first channel of the group
+                        uint32_t res[4] = {0, 0, 0, 0};
+                        if constexpr (HAS_RES) {
+                            const int ro = j * Nc + cl;
+                            if (S == 4) {
+                                const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, tile_off, 0);
+                                res[0] = v[0]; res[1] = v[1]; res[2] = v[2]; res[3] = v[3];
+                            } else if (S == 2) {
+                                const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, tile_off, 0);
+                                res[0] = v[0]; res[1] = v[1];
+                            } else {
+                                res[0] = __builtin_amdgcn_raw_buffer_load_b32(rr, ro, tile_off, 0);
+                            }
+                        }
+                        uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+                        for (int tt = 0; tt < 4; ++tt) {
+                            if (tt < S) {
+                                int v[4];
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    v[r] = requant_i64<GENERAL>(acc[p][t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                if constexpr (HAS_RES) {
+#pragma unroll
+                                    for (int r = 0; r < 4; ++r)
+                                        v[r] = med3_i32(v[r] + sbyte(res[tt], r), m128, p127);
+                                }
+                                out[tt] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                            }
+                        }
+                        // stage the lane's dwords at [pixel j][channel cl..] of the wavefront's tile
+                        unsigned char *sp = stage + j * RW + cl;
+                        const bool full = FULLW || cl + 4 * S <= RW;
+                        if (full && S == 4 && (FULLW || rw16)) {
+                            *reinterpret_cast<v4i *>(sp) = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+                        } else if (full && S == 2 && (FULLW || rw8)) {
+                            *reinterpret_cast<v2i *>(sp) = v2i{(int)out[0], (int)out[1]};
+                        } else {
+#pragma unroll
+                            for (int tt = 0; tt < 4; ++tt)
+                                if (tt < S && (FULLW || cl + 4 * tt + 4 <= RW))
+                                    *reinterpret_cast<uint32_t *>(sp + 4 * tt) = out[tt];
+                        }
+                    }
+                    // write the staged tile; pieces outside the tile or the tensor are dropped
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) {
+                        const v4i v = *reinterpret_cast<const v4i *>(stage + (i * 64 + lane) * 16);
+                        // The tile offset goes into the vector offset, not the scalar one: with a
+                        // scalar offset register the compiler assumes that the registers holding
+                        // the 16 bytes of data may be overwritten right after the store is issued,
+                        // and on this chip the store then now and then picked up the new contents.
+                        // goff is unsigned-saturated, so the sum cannot wrap into the tensor.
+                        __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min((unsigned)goff[i] + (unsigned)tile_off, (unsigned)kOobOffset), 0, 0);
+                    }
+                }
+                ytile = min(ytile + ystep, (unsigned)kOobOffset);
+            }
+        };
+        for (int it = 0; it < full_rounds; ++it) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) step(ring[d], std::true_type{});
+        }
+#pragma nounroll
+        for (int r = 0; r < tail_steps; ++r) {
+            step(ring[0], std::false_type{});
+#pragma unroll
+            for (int d = 0; d + 1 < D; ++d)
+#pragma unroll
+                for (int p = 0; p < PT; ++p) ring[d][p] = ring[d + 1][p];
         }
     };
 
@@ -406,6 +426,13 @@ __global__ __launch_bounds__(256) void pw_stream_kernel(const PwArgs a)
         else
             run(std::false_type{}, std::false_type{});
     }
+}
+
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW>
+__global__ __launch_bounds__(256, (NT * PT <= 7 ? 2 : 1)) void pw_stream_kernel(const PwArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    pw_stream_body<NT, PT, XMODE, KS1, FULLW>(a, logical_block_id(), lds_raw);
 }
 
 using PwKernelFn = void (*)(const PwArgs);

@@ -187,3 +187,60 @@ def test_addsub_design_matches_oracle(P, shape, res):
                               dev(L.residual) if res else None)
     torch.cuda.synchronize()
     assert_same(y.cpu().numpy(), oracle_pw(oracle, L), f"addsub {shape} res={res}")
+
+
+def test_sequence_batches_independent_layers_and_respects_dependencies(P):
+    """prom_pw_conv_sequence puts consecutive small independent layers into one launch; its
+    results must be those of running the layers one after the other, also when a layer reads
+    what an earlier one wrote, writes what an earlier one read, or adds its own output buffer."""
+    torch = torch_cuda()
+    shapes = [(64, 64), (64, 96), (96, 160), (160, 64), (64, 384), (384, 64), (64, 32), (32, 192), (24, 144)]
+    n, h, w = 3, 7, 9
+    Ls = [make_pw_layer(8000 + i, n, h, w, ci, co, signed_x=True, act_window=(-128, 127), shift_range=(3, 8))
+          for i, (ci, co) in enumerate(shapes)]
+    # oracle: a chain where layer i+1 reads layer i's output when the channel counts match
+    want, x_in = [], []
+    prev = None
+    for i, L in enumerate(Ls):
+        x = prev if (prev is not None and prev.shape[-1] == L.cin) else L.x
+        x_in.append(x)
+        prev = oracle.pw_conv(x, L.weight, L.bias, L.mult, L.shift, -128, 127)
+        want.append(prev)
+    # device: same wiring, buffers shared exactly as in the chain
+    ys = [torch.empty((n, h, w, L.cout), dtype=torch.int8, device="cuda") for L in Ls]
+    layers = []
+    for i, L in enumerate(Ls):
+        chained = i > 0 and Ls[i - 1].cout == L.cin
+        xd = ys[i - 1] if chained else dev(L.x)
+        layers.append((xd, dev(P.prom_pack_ternary(L.weight)), L.cout, requant_dev(P, L, (-128, 127)), None, ys[i]))
+    P.PwSequence(layers).run()
+    torch.cuda.synchronize()
+    for i, (y, wnt) in enumerate(zip(ys, want)):
+        assert_same(y.cpu().numpy(), wnt, f"sequence layer {i} {shapes[i]}")
+    # fully independent copies of the same layers (all batchable ones in one launch) + in-place residual
+    ys2 = [dev(np.ascontiguousarray(w_)) for w_ in want]  # used as residual and output at once
+    layers2 = [(dev(x_in[i]), dev(P.prom_pack_ternary(L.weight)), L.cout, requant_dev(P, L, (-128, 127)), ys2[i], ys2[i])
+               for i, L in enumerate(Ls)]
+    P.PwSequence(layers2).run()
+    torch.cuda.synchronize()
+    for i, L in enumerate(Ls):
+        wnt = oracle.pw_conv(x_in[i], L.weight, L.bias, L.mult, L.shift, -128, 127, want[i])
+        assert_same(ys2[i].cpu().numpy(), wnt, f"independent layer {i} with in-place residual")
+
+
+def test_pixel_tile_plans_agree_on_a_full_size_layer(P):
+    """Regression: with two or four pixel tiles per step the 16-byte output stores of one step
+    follow each other closely, and the registers of a store were once reused before the store had
+    read them (a few wrong dwords per launch, only under full load).  Every output of a
+    full-size 96->24 layer, for every pixel-tile count, on several runs, against the oracle."""
+    torch = torch_cuda()
+    L = make_pw_layer(4242, 128, 56, 56, 96, 24)
+    x, wp, rq = dev(L.x), dev(P.prom_pack_ternary(L.weight)), requant_dev(P, L)
+    want = dev(oracle.pw_conv(L.x, L.weight, L.bias, L.mult, L.shift, L.act_min, L.act_max))
+    for plan in (None, P.PwPlan(2, 1, 0), P.PwPlan(2, 2, 0), P.PwPlan(2, 4, 0)):
+        for run in range(6):
+            y = torch.full((128, 56, 56, 24), -99, dtype=torch.int8, device="cuda")
+            P.prom_pw_conv_ex(x, wp, 24, rq, None, y, plan)
+            torch.cuda.synchronize()
+            bad = int((y != want).sum())
+            assert bad == 0, f"plan {plan}, run {run}: {bad} outputs differ"
