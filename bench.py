@@ -32,7 +32,9 @@ def log(*a):
 
 
 def kernel_name(variant):
-    nt, pt, ld, ks1, fullw = variant
+    nt, pt, ld, ks1, fullw = variant[:5]
+    if len(variant) > 5 and variant[5]:  # row-cooperative kernel
+        return f"void prom::pw_rows_kernel<{nt}, {str(ks1).lower()}>(prom::PwArgs)"
     return (f"void prom::pw_stream_kernel<{nt}, {pt}, {ld}, {str(ks1).lower()}, {str(fullw).lower()}>"
             f"(prom::PwArgs)")
 
@@ -106,7 +108,7 @@ def main():
         plan = P.prom_pw_plan_query(args.batch, s.hw, s.hw, s.cin, s.cout)
         # template arguments of the kernel instantiation this layer runs (as rocprofv3 names it)
         variant = (plan["tiles_per_wave"], plan["pixel_tiles"], plan["load_bytes"], s.cin <= 64,
-                   s.cout % (16 * plan["tiles_per_wave"]) == 0)
+                   s.cout % (16 * plan["tiles_per_wave"]) == 0, plan["row_waves"])
         m = args.batch * s.hw * s.hw
         layers.append(dict(shape=s, L=L, x=x, wp=wp, rq=rq, y=y, plan=plan, variant=variant, m=m,
                            bytes=layer_bytes(m, s.cin, s.cout), ops=2 * m * s.cin * s.cout))

@@ -63,12 +63,18 @@ typedef struct {
     int32_t act_max;         /*  output scale maps 6.0 to 127                                 */
 } prom_requant_t;
 
-/* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default". */
+/* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default".
+ * With tiles_per_wave or pixel_tiles given and row_waves == 0 the plain streaming kernel runs
+ * (every wavefront on its own pixel groups, one chunk of 16*tiles_per_wave channels per
+ * workgroup).  row_waves = 2 or 4 asks for the row-cooperative kernel: that many wavefronts of a
+ * workgroup share a pixel group and write whole rows of 16*tiles_per_wave*row_waves channels
+ * together; it needs tiles_per_wave in 1..6, pixel_tiles 0 or 1, cin % 16 == 0 and
+ * cout % (16*tiles_per_wave*row_waves) == 0. */
 typedef struct {
     int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..10)       */
     int32_t pixel_tiles;     /* PT: 16-pixel tiles a wavefront processes per iteration (1,2,4)*/
-    int32_t workgroups;      /* workgroups launched per output-channel chunk                  */
-    int32_t reserved;
+    int32_t workgroups;      /* workgroups launched per output-channel chunk (per row piece)  */
+    int32_t row_waves;       /* 0, 2 or 4: wavefronts per pixel group, see above              */
 } prom_pw_plan_t;
 
 /* ---- ternary weight packing (host side, once per layer: the paper notes that weights are
@@ -117,9 +123,11 @@ int prom_pw_conv_ex(const int8_t *x, int n, int h, int w, int cin,
                     void *stream);
 
 /* The launch plan prom_pw_conv would use for this shape (all pointers assumed 4-byte aligned):
- * fills tiles_per_wave, pixel_tiles, workgroups (per chunk) and, in `reserved`, the activation
- * load width in bytes (16, 8, or 1 for the slow generic kernel).  Host only, launches nothing. */
-int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out);
+ * fills every field of plan_out (row_waves = 0 for the plain streaming kernel) and, if
+ * load_bytes_out is not NULL, the activation load width in bytes (16, 8, or 1 for the slow
+ * generic kernel).  Host only, launches nothing. */
+int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out,
+                       int *load_bytes_out);
 
 /* One layer of a sequence for prom_pw_conv_sequence: the arguments of prom_pw_conv. */
 typedef struct {

@@ -38,7 +38,7 @@ class _PwLayerC(ctypes.Structure):
 
 class _PlanC(ctypes.Structure):
     _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
-                ("workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("workgroups", ctypes.c_int32), ("row_waves", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -84,7 +84,7 @@ def load_library():
     lib.prom_block_workspace_size.restype = sz
     lib.prom_block_workspace_size.argtypes = [ci] * 7
     lib.prom_pw_plan_query.restype = ci
-    lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC)]
+    lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC), ctypes.POINTER(ci)]
     lib.prom_pw_conv_sequence.restype = ci
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
     lib.prom_pw_batchable.restype = ci
@@ -130,9 +130,10 @@ class PwPlan:
     tiles_per_wave: int = 0
     pixel_tiles: int = 0
     workgroups: int = 0
+    row_waves: int = 0
 
     def _c(self) -> _PlanC:
-        return _PlanC(self.tiles_per_wave, self.pixel_tiles, self.workgroups, 0)
+        return _PlanC(self.tiles_per_wave, self.pixel_tiles, self.workgroups, self.row_waves)
 
 
 def _stream_ptr(stream) -> int:
@@ -288,9 +289,11 @@ def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:
     """Launch plan the library picks for a shape: tiles per wave, pixel tiles, workgroups per
     chunk and activation load width."""
     p = _PlanC()
-    _check(load_library().prom_pw_plan_query(n, h, w, cin, cout, ctypes.byref(p)), "prom_pw_plan_query")
+    lb = ctypes.c_int(0)
+    _check(load_library().prom_pw_plan_query(n, h, w, cin, cout, ctypes.byref(p), ctypes.byref(lb)),
+           "prom_pw_plan_query")
     return {"tiles_per_wave": p.tiles_per_wave, "pixel_tiles": p.pixel_tiles,
-            "workgroups": p.workgroups, "load_bytes": p.reserved}
+            "workgroups": p.workgroups, "row_waves": p.row_waves, "load_bytes": lb.value}
 
 
 def prom_pw_batchable(n: int, h: int, w: int, cin: int, cout: int) -> bool:

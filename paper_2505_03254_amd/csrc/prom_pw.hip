@@ -1,7 +1,7 @@
 // Host side of the ternary pointwise convolution (argument checks, launch planning, the
 // C entry points) and the generic any-shape kernel.  The streaming kernel lives in
 // prom_pw_stream.h and is instantiated per NT in prom_pw_inst.hip.
-#include "prom_pw_stream.h"
+#include "prom_pw_rows.h"
 #include "prom_launch.h"
 
 #include <mutex>
@@ -203,12 +203,33 @@ static bool overlaps(const void *p, size_t pn, const void *q, size_t qn)
 
 static int max_pt_for(int nt) { return nt <= 2 ? 4 : (nt <= 6 ? 2 : 1); }
 
+// Row-cooperative plan for a layer whose row does not fit one wavefront's chunk: CW chunks of NT
+// tiles per workgroup that together are the whole row, cout == 16*NT*CW.  (Splitting a wider
+// row into several such pieces was measured and is no faster than the plain kernel.)  Prefers
+// 4 wavefronts per row (fewer registers each).  Returns false if there is no such split or it
+// does not fit the LDS budget.
+static bool plan_rows(int cin, int cout, int ks, int *cw_out, int *nt_out)
+{
+    if (cin % 16 != 0) return false;
+    for (int cw = 4; cw >= 2; cw -= 2) {
+        if (cout % (16 * cw) != 0) continue;
+        const int nt = cout / (16 * cw);
+        if (nt < 1 || nt > kRowsMaxNT) continue;
+        if ((long long)cw * nt * ks * 1024 > kLdsBudget) continue;
+        *cw_out = cw;
+        *nt_out = nt;
+        return true;
+    }
+    return false;
+}
+
 struct PwLaunch {
     PwArgs a;
     KernelFn fn;
     int nt, pt, xmode, grid;
     size_t lds;
     bool fast;
+    bool rows;  // row-cooperative kernel (a.cw != 0)
     int mode;
 };
 
@@ -300,18 +321,46 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
             while (pt > 1 && M < (long long)64 * pt * kNumCU * 2) pt >>= 1;  // small layers: finer groups
         }
     }
+    // A layer that would be split into several chunks takes the row-cooperative kernel when
+    // its shape allows (an explicit tile plan keeps the plain streaming kernel).
+    a.cw = 0;
+    L.rows = false;
+    if (plan && plan->row_waves) {
+        const int cw = plan->row_waves, rnt = plan->tiles_per_wave;
+        if (!fast || (cw != 2 && cw != 4) || rnt < 1 || rnt > kRowsMaxNT || plan->pixel_tiles > 1) return PROM_EINVAL;
+        if (cin % 16 != 0 || cout % (16 * rnt * cw) != 0) return PROM_EINVAL;
+        if (lds_bytes_rows(rnt, cw, a.KS) > (size_t)kLdsMax) return PROM_EINVAL;
+        L.rows = true;
+        a.cw = cw;
+        nt = rnt;
+        pt = 1;
+    } else if (fast && !(plan && (plan->tiles_per_wave || plan->pixel_tiles)) && (n_tiles + nt - 1) / nt > 1) {
+        int cw = 0, rnt = 0;
+        if (plan_rows(cin, cout, a.KS, &cw, &rnt)) {
+            L.rows = true;
+            a.cw = cw;
+            nt = rnt;
+            pt = 1;
+        }
+    }
     L.nt = nt;
     L.pt = pt;
     L.fast = fast;
     L.mode = mode;
     L.xmode = !fast ? 1 : (cin % 16 == 0 ? 16 : 8);
-    L.lds = fast ? lds_bytes_fast(nt, a.KS) : lds_bytes_generic(nt, a.KS);
-    L.fn = select_kernel(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, fast, mode);
+    if (L.rows) {
+        L.lds = lds_bytes_rows(nt, a.cw, a.KS);
+        L.fn = pw_rows_select(nt, a.KS == 1);
+    } else {
+        L.lds = fast ? lds_bytes_fast(nt, a.KS) : lds_bytes_generic(nt, a.KS);
+        L.fn = select_kernel(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, fast, mode);
+    }
     if (!L.fn) return PROM_EINVAL;
 
-    a.n_chunks = (n_tiles + nt - 1) / nt;
+    a.n_chunks = L.rows ? cout / (16 * nt * a.cw) : (n_tiles + nt - 1) / nt;
     a.units = (int)((M + 16 * pt - 1) / (16 * pt));
-    const long long wg_units = (a.units + 3) / 4;  // a workgroup's 4 wavefronts take 4 groups per round
+    // a workgroup's 4 wavefronts take 4 groups per round (4 / cw groups in the row-cooperative kernel)
+    const long long wg_units = L.rows ? (a.units + 4 / a.cw - 1) / (4 / a.cw) : (a.units + 3) / 4;
     long long wgs;
     if (plan && plan->workgroups) {
         if (plan->workgroups < 1) return PROM_EINVAL;
@@ -387,7 +436,8 @@ extern "C" int prom_pw_accum_i32(const int8_t *x, int n, int h, int w, int cin, 
                              stream, 1);
 }
 
-extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out)
+extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_pw_plan_t *plan_out,
+                                  int *load_bytes_out)
 {
     if (!plan_out) return PROM_EINVAL;
     prom::PwLaunch L;
@@ -397,7 +447,8 @@ extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_p
     plan_out->tiles_per_wave = L.nt;
     plan_out->pixel_tiles = L.pt;
     plan_out->workgroups = L.a.wg_per_chunk;
-    plan_out->reserved = L.xmode;
+    plan_out->row_waves = L.a.cw;
+    if (load_bytes_out) *load_bytes_out = L.xmode;
     return PROM_OK;
 }
 
@@ -445,7 +496,11 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     size_t lds = 0;
     int start = 0;
     for (int i = 0; i < count; ++i) {
-        PwArgs a = members[i]->a;  // re-planned: NT = kBatchNT, PT = 1
+        // re-planned for the batch body: NT = kBatchNT, PT = 1, plain streaming (measured: the
+        // row-cooperative form gains nothing inside a batch, where fixed costs per workgroup and
+        // the balance between layers decide)
+        PwArgs a = members[i]->a;
+        a.cw = 0;
         const int n_tiles = (a.Nc + 15) / 16;
         a.n_chunks = (n_tiles + kBatchNT - 1) / kBatchNT;
         a.units = (a.M + 15) / 16;

@@ -1,0 +1,290 @@
+// Row-cooperative variant of the streaming pointwise kernel, for layers whose output row is
+// wider than one wavefront's chunk of channels.
+//
+// In the plain streaming kernel the chunks of a row belong to different workgroups: each writes
+// row pieces of 16*NT bytes at a stride of the row and re-reads the activations.  Measured on
+// gfx950 that costs about 40 % of the rate of a layer whose chunk is the whole row: the memory
+// traffic is the same, but a store instruction then touches twice as many 128-byte lines on its
+// way through the vector L1, and that path is what limits a write-heavy layer.
+//
+// Here the CW = 2 or 4 chunks of one pixel group sit on the wavefronts of ONE workgroup
+// (G = 4 / CW pixel groups per workgroup step).  Every wavefront computes its 16 pixels x 16*NT
+// channels as before and puts them into a shared LDS tile [16*G pixels][16*NT*CW bytes]; after a
+// workgroup barrier all 256 lanes write the tile as whole rows, in 16-byte pieces that follow each
+// other in memory.  The tile is double buffered, so one barrier per step suffices: a wavefront
+// can reach the writes of step s+2 only through the barrier of step s+1, which every wavefront
+// passes after its reads of step s have returned.  The activations of a pixel group are loaded by
+// each of its CW wavefronts (same lines at the same time: hits in the vector L1).
+//
+// A row wider than 16*NT*CW bytes is split into "super-chunks" of that width, handled by different
+// workgroups as before (a.n_chunks counts super-chunks here).
+#pragma once
+#include "prom_pw_stream.h"
+
+namespace prom {
+
+// LDS bytes: fragments and parameters of the CW*NT tiles, two output tiles of 1024*NT bytes.
+__host__ __device__ constexpr size_t lds_bytes_rows(int nt, int cw, int ks)
+{
+    return (size_t)cw * nt * ks * 1024 + (size_t)cw * nt * 256 + (size_t)2 * 1024 * nt;
+}
+
+// Fragments frag[CW*NT][KS][64] and parameters lpar[CW*NT][4 g][4 r] of a super-chunk; tile slot
+// cw*NT + t holds the channels base + 16*NT*cw + chan_of<NT>(t, ., .).  Ends with the barrier.
+template <int NT>
+__device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, int CW, v4i *frag, v4i *lpar)
+{
+    const int tid = threadIdx.x;
+    const int KS = a.KS, Nc = a.Nc;
+    const int NTT = CW * NT;
+    const int nfrag = NTT * KS * 64;
+    constexpr int U = 8;  // words in flight per thread
+    for (int base = 0; base < nfrag; base += 256 * U) {
+        uint32_t word[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            const int tk = idx >> 6;
+            const int ks = tk % KS;
+            const int tt = tk / KS;
+            const int cw = tt / NT;
+            const int t = tt - cw * NT;
+            const int i = idx & 15;
+            const int c = cbase + cw * NT * 16 + chan_of<NT>(t, i >> 2, i & 3);
+            const int kw = 4 * ks + ((idx & 63) >> 4);
+            const bool ok = idx < nfrag && c < Nc && kw < a.KW;
+            const uint32_t v = a.wq[ok ? (long long)c * a.KW + kw : 0];
+            word[q] = ok ? v : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            if (idx < nfrag) frag[idx] = decode_word(word[q]);
+        }
+    }
+    for (int s = tid; s < NTT * 16; s += 256) {
+        const int tt = s >> 4;
+        const int cw = tt / NT;
+        const int t = tt - cw * NT;
+        const int c = cbase + cw * NT * 16 + chan_of<NT>(t, (s >> 2) & 3, s & 3);
+        int pb = 0, pm = 0, ps = 1;
+        if (c < Nc) {
+            pb = a.bias[c];
+            pm = a.mult[c];
+            ps = a.shift[c];
+        }
+        const long long C = (long long)pb * pm + (1LL << (30 + ps));
+        lpar[s] = v4i{(int)(uint32_t)C, (int)(C >> 32), pm, ps};
+    }
+    __syncthreads();
+}
+
+// Requirements (checked by the host): cin % 16 == 0, cout % (16*NT*CW) == 0, 4-byte aligned
+// tensors below 2^31 bytes, CW in {2, 4} (a.cw), a.units counts groups of 16 pixels.
+template <int NT, bool KS1, int D = 4>
+__device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    constexpr int NI = (NT + 3) / 4;  // 16-byte pieces per lane per step: 64*NT pieces, 256 lanes
+    const int KS = KS1 ? 1 : a.KS;
+    const int CW = a.cw, G = 4 / CW, NTT = CW * NT;
+    v4i *frag = reinterpret_cast<v4i *>(lds_raw);
+    v4i *lpar = frag + NTT * KS * 64;
+    unsigned char *tiles = reinterpret_cast<unsigned char *>(lpar + NTT * 16);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15;
+    const int g = lane >> 4;
+
+    const int sc = lid % a.n_chunks;
+    const int wg = lid / a.n_chunks;
+    if (wg >= a.wg_per_chunk) return;  // the whole workgroup leaves: no barrier is missed
+    const int cwi = wave & (CW - 1);   // this wavefront's chunk within the super-chunk
+    const int gsub = wave / CW;        // and its pixel group within the workgroup step
+    const int cbase = sc * NTT * 16;
+    const int RWs = NTT * 16;          // bytes of a tile row
+    const int K = a.K, Nc = a.Nc;
+
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.M * K, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.M * Nc, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.residual ? a.residual : a.y), 0, a.M * Nc, kBufFlags);
+
+    // workgroup steps: step i of workgroup wg covers the pixel groups (wg + i*wg_per_chunk)*G + 0..G-1
+    const int units_wg = (a.units + G - 1) / G;
+    const int my_steps = wg < units_wg ? (units_wg - wg + a.wg_per_chunk - 1) / a.wg_per_chunk : 0;
+
+    int lk = 0;
+    unsigned xoff = min((unsigned)kOobOffset, (unsigned)((wg * G + gsub) * 16 + j) * (unsigned)K + 16u * g);
+    const unsigned xstep = (unsigned)a.wg_per_chunk * (unsigned)(G * 16) * (unsigned)K;
+    auto load_group = [&](v4i &b) {
+        b = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xoff, 64 * lk, 0);
+        if (KS1 || ++lk == KS) {
+            lk = 0;
+            xoff = min(xoff + xstep, (unsigned)kOobOffset);
+        }
+    };
+    v4i ring[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_group(ring[d]);
+
+    stage_weights_rows<NT>(a, cbase, CW, frag, lpar);
+
+    v4i par[NT][4];
+    const v4i *lpg = lpar + cwi * NT * 16 + g * 4;
+    bool sh0 = false;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            par[t][r] = lpg[t * 16 + r];
+            sh0 |= par[t][r][3] == 0;
+        }
+    // per wavefront: the wavefronts of a workgroup may take different forms of the loop; they
+    // still meet at the same number of barriers
+    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+    if (!general_shift) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) par[t][r][3] -= 1;
+    }
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int m128 = in_vgpr(-128), p127 = in_vgpr(127);
+
+    // where this lane puts its outputs in the tile: row gsub*16 + j, this wavefront's columns
+    const int wbase = (gsub * 16 + j) * RWs + cwi * NT * 16;
+    // the pieces this lane writes to memory: piece q = 256*i + tid of 64*NT, row-major in the tile
+    int goff[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int q = i * 256 + tid;
+        const int row = q / NTT;
+        goff[i] = q < 64 * NT ? row * Nc + 16 * (q - row * NTT) : kOobOffset;
+    }
+    // byte offset of (first pixel of the workgroup step, super-chunk base)
+    unsigned ytile = min((unsigned)kOobOffset, (unsigned)(wg * G * 16) * (unsigned)Nc + (unsigned)cbase);
+    const unsigned ystep = (unsigned)a.wg_per_chunk * (unsigned)(G * 16) * (unsigned)Nc;
+    const unsigned rwave = (unsigned)(gsub * 16) * (unsigned)Nc + (unsigned)(cwi * NT * 16);  // for the residual
+
+    const int total_steps = my_steps * KS;
+    const int full_rounds = total_steps / D;
+    const int tail_steps = total_steps - full_rounds * D;
+    const v4i *fl = frag + cwi * NT * KS * 64 + lane;
+
+    auto run = [&](auto has_res_tag, auto general_tag) {
+        constexpr bool HAS_RES = decltype(has_res_tag)::value;
+        constexpr bool GENERAL = decltype(general_tag)::value;
+        v4i acc[NT];
+        const v4i zero4 = {0, 0, 0, 0};
+        int ck = 0;
+        int buf = 0;
+        auto step = [&](v4i &slot, auto refill_tag) {
+            constexpr bool REFILL = decltype(refill_tag)::value;
+            // opaque offset: keeps the fragment reads inside the loop (see the streaming kernel)
+            int fo = ck * 64;
+            asm volatile("" : "+v"(fo));
+            const v4i *fk = fl + fo;
+            if (KS1 || ck == 0) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KS * 64], slot, zero4, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KS * 64], slot, acc[t], 0, 0, 0);
+            }
+            if constexpr (REFILL) load_group(slot);
+            if (KS1 || ++ck == KS) {
+                ck = 0;
+                unsigned char *tile = tiles + buf * (1024 * NT);
+#pragma unroll
+                for (int t0 = 0; t0 < NT; t0 += grp_size<NT>(t0)) {
+                    const int S = grp_size<NT>(t0);
+                    const int cl = chan_of<NT>(t0, g, 0);
+                    uint32_t res[4] = {0, 0, 0, 0};
+                    if constexpr (HAS_RES) {
+                        const int ro = (int)min(ytile + rwave, (unsigned)kOobOffset) + j * Nc + cl;
+                        if (S == 4) {
+                            const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, 0, 0);
+                            res[0] = v[0]; res[1] = v[1]; res[2] = v[2]; res[3] = v[3];
+                        } else if (S == 2) {
+                            const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, 0, 0);
+                            res[0] = v[0]; res[1] = v[1];
+                        } else {
+                            res[0] = __builtin_amdgcn_raw_buffer_load_b32(rr, ro, 0, 0);
+                        }
+                    }
+                    uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int tt = 0; tt < 4; ++tt) {
+                        if (tt < S) {
+                            int v[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                v[r] = requant_i64<GENERAL>(acc[t0 + tt][r], par[t0 + tt][r], lo, hi);
+                            if constexpr (HAS_RES) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) v[r] = med3_i32(v[r] + sbyte(res[tt], r), m128, p127);
+                            }
+                            out[tt] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                        }
+                    }
+                    unsigned char *sp = tile + wbase + cl;
+                    if (S == 4)
+                        *reinterpret_cast<v4i *>(sp) = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+                    else if (S == 2)
+                        *reinterpret_cast<v2i *>(sp) = v2i{(int)out[0], (int)out[1]};
+                    else
+                        *reinterpret_cast<uint32_t *>(sp) = out[0];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const v4i v = *reinterpret_cast<const v4i *>(tile + (i * 256 + tid) * 16);
+                    // tile offset in the vector offset: see the store of the streaming kernel
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        v, ry, (int)min((unsigned)goff[i] + ytile, (unsigned)kOobOffset), 0, 0);
+                }
+                buf ^= 1;
+                ytile = min(ytile + ystep, (unsigned)kOobOffset);
+            }
+        };
+        for (int it = 0; it < full_rounds; ++it) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) step(ring[d], std::true_type{});
+        }
+#pragma nounroll
+        for (int r = 0; r < tail_steps; ++r) {
+            step(ring[0], std::false_type{});
+#pragma unroll
+            for (int d = 0; d + 1 < D; ++d) ring[d] = ring[d + 1];
+        }
+    };
+
+    if (a.residual) {
+        if (general_shift)
+            run(std::true_type{}, std::true_type{});
+        else
+            run(std::true_type{}, std::false_type{});
+    } else {
+        if (general_shift)
+            run(std::false_type{}, std::true_type{});
+        else
+            run(std::false_type{}, std::false_type{});
+    }
+}
+
+template <int NT, bool KS1>
+__global__ __launch_bounds__(256, (NT <= 7 ? 2 : 1)) void pw_rows_kernel(const PwArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    pw_rows_body<NT, KS1>(a, logical_block_id(), lds_raw);
+}
+
+// Defined in prom_pw_rows.hip: the instantiation for NT in 1..6, or nullptr.
+PwKernelFn pw_rows_select(int nt, bool ks1);
+constexpr int kRowsMaxNT = 6;
+
+}  // namespace prom

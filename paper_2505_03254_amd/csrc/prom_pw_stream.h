@@ -51,6 +51,7 @@ struct PwArgs {
     int n_chunks;      // output-channel chunks of 16*NT channels
     int wg_per_chunk;  // workgroups per chunk; 4*wg_per_chunk wavefronts share the units
     int lo, hi;        // activation window
+    int cw;            // row-cooperative kernel only: chunks of a pixel group per workgroup (2 or 4), else 0
 };
 
 // Tiles of a chunk are stored in groups of 4, then 2, then 1 so that a lane's outputs of a

@@ -103,6 +103,47 @@ def test_every_tile_plan(P, nt):
                 assert_same(run_pw(P, L, plan=plan), want, f"nt={nt} pt={pt} wgs={wgs} cin={cin}")
 
 
+@pytest.mark.parametrize("cw", [2, 4])
+def test_row_cooperative_plans(P, cw):
+    """The row-cooperative kernel (2 or 4 wavefronts of a workgroup share a pixel group and write
+    whole rows): every tile count, one and several k steps, ragged pixel counts down to a single
+    pixel, few and many workgroups, with and without the skip connection."""
+    for nt in range(1, 7):
+        cout = 16 * nt * cw
+        for (n, h, w, cin) in ((2, 9, 13, 32), (1, 7, 7, 160), (1, 1, 1, 64), (3, 5, 11, 16)):
+            L = make_pw_layer(5000 + 10 * nt + cw + cin, n, h, w, cin, cout, signed_x=True,
+                              act_window=(-100, 100), with_residual=(cin == 32))
+            want = oracle_pw(oracle, L)
+            for wgs in (0, 1, 5):
+                plan = P.PwPlan(nt, 0, wgs, cw)
+                assert_same(run_pw(P, L, plan=plan), want, f"rows cw={cw} nt={nt} cin={cin} wgs={wgs}")
+    # a row of several pieces (two pieces of 16*nt*cw channels)
+    L = make_pw_layer(5900 + cw, 2, 6, 7, 48, 2 * 16 * 2 * cw, signed_x=True, with_residual=True,
+                      act_window=(-128, 127))
+    assert_same(run_pw(P, L, plan=P.PwPlan(2, 1, 0, cw)), oracle_pw(oracle, L), f"rows cw={cw} two pieces")
+    # plans that cannot be realised
+    L = make_pw_layer(5950, 1, 4, 4, 32, 96)
+    for bad in (P.PwPlan(4, 0, 0, cw), P.PwPlan(7, 0, 0, cw), P.PwPlan(3, 2, 0, cw), P.PwPlan(3, 0, 0, 3)):
+        with pytest.raises(P.PromError) as e:
+            run_pw(P, L, plan=bad)
+        assert e.value.code == -1
+    L = make_pw_layer(5960, 1, 4, 4, 24, 16 * cw)  # cin % 16 != 0
+    with pytest.raises(P.PromError) as e:
+        run_pw(P, L, plan=P.PwPlan(1, 0, 0, cw))
+    assert e.value.code == -1
+
+
+def test_library_picks_row_cooperative_kernel_for_wide_rows(P):
+    """A 32->192 and a 64->384 layer (rows wider than one wavefront's chunk, whole row = 4
+    wavefronts) take the row-cooperative kernel by default; results as the oracle's."""
+    for cin, cout in ((32, 192), (64, 384), (32, 256)):
+        q = P.prom_pw_plan_query(2, 28, 28, cin, cout)
+        assert q["row_waves"] in (2, 4) and 16 * q["tiles_per_wave"] * q["row_waves"] == cout, q
+        L = make_pw_layer(5980 + cin, 2, 28, 28, cin, cout)
+        assert_same(run_pw(P, L), oracle_pw(oracle, L), f"default plan {cin}->{cout}")
+    assert P.prom_pw_plan_query(2, 28, 28, 16, 96)["row_waves"] == 0  # one chunk: plain kernel
+
+
 def test_raw_accumulators(P):
     torch = torch_cuda()
     for cin, cout in ((64, 384), (24, 144), (17, 5), (960, 160)):
