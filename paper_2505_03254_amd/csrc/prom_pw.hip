@@ -106,6 +106,13 @@ struct PwBatchArgs {
     PwArgs layer[kMaxBatch];
 };
 
+// Tiles per wavefront of a batch member: kBatchNT, or half of it for a layer with many k
+// steps, whose decoded fragments would otherwise set the LDS size (and with it the number of
+// resident workgroups) of the whole launch.
+constexpr int kBatchNTDeep = 2;
+constexpr int kBatchDeepKS = 10;
+__host__ __device__ constexpr int batch_nt(int ks) { return ks >= kBatchDeepKS ? kBatchNTDeep : kBatchNT; }
+
 __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -114,7 +121,24 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
     const int local = bid - b.start[i];
     const int nblk = b.start[i + 1] - b.start[i];
-    pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth>(b.layer[i], logical_block_id(local, nblk), lds_raw);
+    const PwArgs &a = b.layer[i];
+    const int lid = logical_block_id(local, nblk);
+    // FULLW bodies (every chunk 16*NT channels wide) have no per-lane conditions in the epilogue;
+    // with one k step there is no branch around the epilogue either, so the waits on the prefetch
+    // ring are exact (a store in a conditional epilogue makes them conservative)
+    if (a.KS >= kBatchDeepKS) {
+        if (a.Nc % (16 * kBatchNTDeep) == 0)
+            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth>(a, lid, lds_raw);
+        else
+            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth>(a, lid, lds_raw);
+    } else if (a.Nc % (16 * kBatchNT) == 0) {
+        if (a.KS == 1)
+            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth>(a, lid, lds_raw);
+        else
+            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth>(a, lid, lds_raw);
+    } else {
+        pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth>(a, lid, lds_raw);
+    }
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst,
@@ -458,13 +482,13 @@ namespace prom {
 // chunk row is whole 16-byte pieces, and it is small enough that its own launch would be
 // dominated by fixed costs.
 constexpr long long kBatchMaxBytes = 32LL << 20;
-constexpr long long kBatchBytesPerWg = 128LL << 10;  // activation bytes one workgroup of a batch moves
+constexpr long long kBatchBytesPerWg = 256LL << 10;  // bytes the first workgroups of a batch move (later ones less)
 
 static bool batchable(const PwLaunch &L)
 {
     const PwArgs &a = L.a;
     if (!L.fast || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
-    if (kBatchNT * a.KS * 1024 > kLdsBudget) return false;
+    if (batch_nt(a.KS) * a.KS * 1024 > kLdsBudget) return false;
     return (long long)a.M * (a.K + a.Nc) <= kBatchMaxBytes;
 }
 
@@ -495,18 +519,33 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     b.count = count;
     size_t lds = 0;
     int start = 0;
+    // Work of a member = bytes its chunks move (activations are read once per chunk).  Workgroups
+    // are dispatched in table order: the first ones get large pieces (each workgroup pays one cold
+    // round trip for its weights and first loads before it streams), the last ones small pieces so
+    // that the chip drains evenly at the end of the launch.
+    long long total_work = 0, done_work = 0;
     for (int i = 0; i < count; ++i) {
-        // re-planned for the batch body: NT = kBatchNT, PT = 1, plain streaming (measured: the
-        // row-cooperative form gains nothing inside a batch, where fixed costs per workgroup and
-        // the balance between layers decide)
+        const PwArgs &m = members[i]->a;
+        const int nt = batch_nt(m.KS);
+        total_work += (long long)m.M * (m.K + 16 * nt) * (((m.Nc + 15) / 16 + nt - 1) / nt);
+    }
+    for (int i = 0; i < count; ++i) {
+        // re-planned for the batch body: PT = 1, plain streaming (measured: the row-cooperative
+        // form gains nothing inside a batch, where fixed costs per workgroup and the balance
+        // between layers decide)
         PwArgs a = members[i]->a;
         a.cw = 0;
         const int n_tiles = (a.Nc + 15) / 16;
-        a.n_chunks = (n_tiles + kBatchNT - 1) / kBatchNT;
+        const int nt = batch_nt(a.KS);
+        a.n_chunks = (n_tiles + nt - 1) / nt;
         a.units = (a.M + 15) / 16;
         const long long wg_units = (a.units + 3) / 4;
-        const long long work = (long long)a.M * (a.K + 16 * kBatchNT);  // bytes one chunk moves
-        long long wgs = (work + kBatchBytesPerWg - 1) / kBatchBytesPerWg;
+        const long long work = (long long)a.M * (a.K + 16 * nt);  // bytes one chunk moves
+        const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
+                                 : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
+                                                                   : kBatchBytesPerWg / 4;
+        done_work += work * a.n_chunks;
+        long long wgs = (work + per_wg - 1) / per_wg;
         if (wgs < 1) wgs = 1;
         if (wgs > wg_units) wgs = wg_units;
         a.wg_per_chunk = (int)wgs;
@@ -514,7 +553,7 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         b.layer[i] = a;
         b.start[i] = start;
         start += nblk;
-        const size_t l = lds_bytes_fast(kBatchNT, a.KS);
+        const size_t l = lds_bytes_fast(nt, a.KS);
         if (l > lds) lds = l;
     }
     b.start[count] = start;
