@@ -1,9 +1,19 @@
 // int8 depthwise 3x3 convolution (pad 1, stride 1 or 2), NHWC, with the exact integer
 // requantisation epilogue.  This is the 8-bit convolution that sits between the two ternary
 // pointwise convolutions of a block (paper Section 2; Section 3.1 "Depthwise Convolutions").
-// It is not a dense contraction (9 taps per output, channels independent), so it runs on
-// the vector ALU: a thread owns 4 consecutive channels (one dword of the NHWC row) of one
-// output column and walks down a strip of output rows.
+// It is not a dense contraction (9 taps per output, channels independent), so it runs on the
+// vector ALU, and the work per output byte decides its speed.
+//
+// dw_kernel_v4: a thread owns 4 consecutive channels (one dword of the NHWC row) of one output
+// column and 4 consecutive output rows; lanes run over channels, then columns, so every load and
+// store instruction of a wavefront covers one contiguous run.  The input rows feeding the 4
+// outputs (6 at stride 1, 9 at stride 2) are loaded for each of the 3 kernel columns as one
+// dword per pixel and transposed in registers (v_perm_b32, 4x4 bytes) so that a dword holds 4
+// vertically neighbouring pixels of ONE channel; the 3 vertical taps of an output are then one
+// v_dot4_i32_i8 against the dword (w[0][j], w[1][j], w[2][j], 0) of that channel and kernel
+// column, on a byte window cut out with v_alignbyte_b32.  About 12 vector instructions per
+// output byte against about 32 for one multiply-add per tap.  Requantisation as in the pointwise kernels:
+// t = acc*mult + C (one v_mad_i64_i32, C = bias*mult + 2^(30+shift)), q = (t >> 31) >> shift.
 #include "prom.h"
 #include "prom_device.h"
 #include "prom_launch.h"
@@ -24,64 +34,121 @@ struct DwArgs {
     long long total;  // threads with work
 };
 
-// C % 4 == 0, 4-byte aligned x / y / w.
-__global__ __launch_bounds__(256) void dw_kernel_c4(const DwArgs a)
+// 4x4 byte transpose: in[p] = 4 channels of pixel p  ->  out[q] = channel q of pixels 0..3.
+__device__ __forceinline__ void transpose4x4(const uint32_t (&in)[4], uint32_t (&out)[4])
 {
-    set_f64_round_down();
-    const long long tid = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (tid >= a.total) return;
+    const uint32_t t0 = __builtin_amdgcn_perm(in[1], in[0], 0x05010400u);  // a0 b0 a1 b1
+    const uint32_t t1 = __builtin_amdgcn_perm(in[1], in[0], 0x07030602u);  // a2 b2 a3 b3
+    const uint32_t u0 = __builtin_amdgcn_perm(in[3], in[2], 0x05010400u);  // c0 d0 c1 d1
+    const uint32_t u1 = __builtin_amdgcn_perm(in[3], in[2], 0x07030602u);  // c2 d2 c3 d3
+    out[0] = __builtin_amdgcn_perm(u0, t0, 0x05040100u);
+    out[1] = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
+    out[2] = __builtin_amdgcn_perm(u1, t1, 0x05040100u);
+    out[3] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
+}
+
+// C % 4 == 0, 4-byte aligned x / y / w, one image below 2^31 bytes.
+// Grid: x over Wo * C/4 (channels fastest, then output columns: the lanes of a wavefront read and
+// write contiguous runs), y = group of 4 output rows, z = image.  Row and image indices are
+// uniform per workgroup, so every address is a per-lane column offset plus a scalar row offset;
+// the image is addressed through a buffer resource of its own, which makes rows above and below
+// it read as zero (and such output rows vanish) without a test, and a column outside the image
+// gets an offset beyond the resource.
+template <int S>
+__global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
+{
+    constexpr int NPIX = S == 1 ? 6 : 9;  // input rows feeding 4 output rows
+    constexpr int NB = (NPIX + 3) / 4;    // transposed dwords per channel
+    constexpr int kFlags = 0x00020000;
+    constexpr int kOob = 0x7ffff000;
     const int C4 = a.C >> 2;
-    const int c4 = (int)(tid % C4);
-    long long r = tid / C4;
-    const int ox = (int)(r % a.Wo);
-    r /= a.Wo;
-    const int strip = (int)(r % a.strips);
-    const int n = (int)(r / a.strips);
-    const int c = c4 * 4;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.Wo * C4) return;
+    const int ox = t / C4;
+    const int c = (t - ox * C4) * 4;
+    const int oy0 = blockIdx.y * 4;
+    const int n = blockIdx.z;
 
-    int wt[9][4];
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.x) + (long long)n * a.H * a.W * a.C, 0, a.H * a.W * a.C, kFlags);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(a.y + (long long)n * a.Ho * a.Wo * a.C, 0, a.Ho * a.Wo * a.C, kFlags);
+    const __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.w), 0, 9 * a.C, kFlags);
+
+    // activations first: 3 columns x NPIX rows
+    const int rowbytes = a.W * a.C;
+    const int iy0 = oy0 * S - 1;
+    uint32_t v[3][NB * 4];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        const uint32_t v = *reinterpret_cast<const uint32_t *>(a.w + (long long)t * a.C + c);
+    for (int jx = 0; jx < 3; ++jx) {
+        const int ix = ox * S + jx - 1;
+        const int coff = (ix >= 0 && ix < a.W) ? ix * a.C + c : kOob;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) wt[t][q] = sbyte(v, q);
+        for (int p = 0; p < NB * 4; ++p)
+            v[jx][p] = p < NPIX ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rx, coff, (iy0 + p) * rowbytes, 0) : 0u;
     }
-    int bias[4];
-    double scale[4];
+    // weights: wcol[jx][q] = (w[0][jx][c+q], w[1][jx][c+q], w[2][jx][c+q], 0)
+    uint32_t wcol[3][4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        bias[q] = a.bias[c + q];
-        scale[q] = make_scale(a.mult[c + q], a.shift[c + q]);
+    for (int jx = 0; jx < 3; ++jx) {
+        uint32_t in[4];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) in[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rw, c, (i * 3 + jx) * a.C, 0);
+        in[3] = 0;
+        transpose4x4(in, wcol[jx]);
     }
+    // requantisation: C = bias*mult + 2^(30+shift), mult, shift per channel
+    const v4i pb = *reinterpret_cast<const v4i *>(a.bias + c);
+    const v4i pm = *reinterpret_cast<const v4i *>(a.mult + c);
+    const v4i ps = *reinterpret_cast<const v4i *>(a.shift + c);
+    long long Cq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) Cq[q] = (long long)pb[q] * pm[q] + (1LL << (30 + ps[q]));
+    const int lo = in_vgpr(a.lo_b - kQBias), hi = in_vgpr(a.hi_b - kQBias);
 
-    const int oy0 = strip * a.strip_rows;
-    const int oy1 = min(oy0 + a.strip_rows, a.Ho);
-    const int8_t *xn = a.x + (long long)n * a.H * a.W * a.C + c;
-    int8_t *yn = a.y + (long long)n * a.Ho * a.Wo * a.C + c;
-    const int ix0 = ox * a.stride - 1;
-
-    for (int oy = oy0; oy < oy1; ++oy) {
-        int acc[4] = {bias[0], bias[1], bias[2], bias[3]};
-        const int iy0 = oy * a.stride - 1;
+    int acc[4][4];  // [output row][channel]
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int iy = iy0 + i;
-            const bool rowok = iy >= 0 && iy < a.H;
+    for (int jx = 0; jx < 3; ++jx) {
+        uint32_t tr[NB][4];
 #pragma unroll
-            for (int jx = 0; jx < 3; ++jx) {
-                const int ix = ix0 + jx;
-                uint32_t v = 0;
-                if (rowok && ix >= 0 && ix < a.W)
-                    v = *reinterpret_cast<const uint32_t *>(xn + ((long long)iy * a.W + ix) * a.C);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) acc[q] += sbyte(v, q) * wt[i * 3 + jx][q];
-            }
+        for (int b = 0; b < NB; ++b) {
+            const uint32_t in[4] = {v[jx][4 * b], v[jx][4 * b + 1], v[jx][4 * b + 2], v[jx][4 * b + 3]};
+            transpose4x4(in, tr[b]);
         }
-        int o[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) o[q] = requant_to_biased(acc[q], scale[q], a.lo_b, a.hi_b);
-        *reinterpret_cast<uint32_t *>(yn + ((long long)oy * a.Wo + ox) * a.C) =
-            pack4_low_bytes(o[0], o[1], o[2], o[3]);
+        for (int q = 0; q < 4; ++q) {
+            // byte window of channel q for output row o: input rows S*o .. S*o+3 of this column
+            uint32_t w[4];
+            if (S == 1) {
+                w[0] = tr[0][q];
+                w[1] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 1);
+                w[2] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 2);
+                w[3] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 3);
+            } else {
+                w[0] = tr[0][q];
+                w[1] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 2);
+                w[2] = tr[1][q];
+                w[3] = __builtin_amdgcn_alignbyte(tr[NB - 1][q], tr[1][q], 2);
+            }
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+                acc[o][q] = __builtin_amdgcn_sdot4((int)w[o], (int)wcol[jx][q], jx == 0 ? 0 : acc[o][q], false);
+        }
+    }
+    const int yoff = ox * a.C + c;
+    const int yrow = a.Wo * a.C;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        int out[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const long long tq = (long long)acc[o][q] * (long long)pm[q] + Cq[q];
+            out[q] = med3_i32((int)(tq >> 31) >> ps[q], lo, hi);
+        }
+        // an output row below the image is beyond the resource and is dropped
+        __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(out[0], out[1], out[2], out[3]), ry, yoff,
+                                              (oy0 + o) * yrow, 0);
     }
 }
 
@@ -139,19 +206,21 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
     if (overlaps(y, ybytes, x, xbytes) || overlaps(y, ybytes, w_dw, (size_t)9 * c)) return PROM_EALIAS;
     hipStream_t st = static_cast<hipStream_t>(stream);
     clear_hip_error();
-    const bool fast = (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 3) == 0);
+    // the fast kernel addresses one image with 32-bit offsets and reads the parameters 16 bytes at a time
+    const bool fast = (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 3) == 0) &&
+                      ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->shift) & 15) == 0) &&
+                      (long long)h * w * c < (1LL << 31) - (1LL << 24) && n <= 65535;
     if (fast) {
-        // enough threads to fill the chip, otherwise long strips to amortise the per-thread setup
-        const long long cols = (long long)n * a.Wo * (c / 4);
-        int strip_rows = a.Ho;
-        while (strip_rows > 1 && cols * ((a.Ho + strip_rows - 1) / strip_rows) < 256LL * 256 * 8)
-            strip_rows = (strip_rows + 1) / 2;
-        a.strip_rows = strip_rows;
-        a.strips = (a.Ho + strip_rows - 1) / strip_rows;
-        a.total = cols * a.strips;
-        const long long blocks = (a.total + 255) / 256;
-        if (blocks > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
-        hipLaunchKernelGGL(dw_kernel_c4, dim3((unsigned)blocks), dim3(256), 0, st, a);
+        a.strip_rows = 4;
+        a.strips = (a.Ho + 3) / 4;
+        a.total = 0;
+        const long long xblocks = ((long long)a.Wo * (c / 4) + 255) / 256;
+        if (xblocks > (1LL << 31) - 1 || a.strips > 65535 || n > 65535) return PROM_EUNSUPPORTED;
+        const dim3 grid((unsigned)xblocks, (unsigned)a.strips, (unsigned)n);
+        if (stride == 1)
+            hipLaunchKernelGGL(dw_kernel_v4<1>, grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(dw_kernel_v4<2>, grid, dim3(256), 0, st, a);
     } else {
         a.strips = a.strip_rows = 0;
         a.total = (long long)ybytes;

@@ -21,6 +21,9 @@ DW_SHAPES = [
     (1, 1, 1, 4, 1), (1, 3, 3, 8, 1), (2, 4, 5, 12, 1), (2, 4, 5, 12, 2), (1, 7, 7, 960, 1),
     (3, 14, 14, 384, 1), (2, 28, 28, 192, 2), (1, 9, 11, 20, 2), (1, 112, 112, 32, 1),
     (1, 56, 56, 144, 2), (2, 5, 4, 5, 1), (2, 5, 4, 7, 2), (1, 2, 7, 1, 2), (1, 15, 1, 16, 2),
+    # row groups of 4 with 1, 2, 3 rows left over, both strides, even and odd sizes
+    (2, 5, 6, 8, 1), (2, 6, 6, 8, 2), (1, 7, 3, 24, 1), (1, 13, 10, 4, 2), (3, 10, 9, 36, 1),
+    (1, 12, 12, 64, 2), (2, 1, 9, 8, 1), (2, 9, 1, 8, 1), (2, 2, 2, 4, 2),
 ]
 
 
@@ -35,6 +38,36 @@ def test_dw_shapes(P, shape):
     torch.cuda.synchronize()
     want = oracle.dw_conv(D.x, D.weight, stride, D.bias, D.mult, D.shift, -128, 127)
     assert_same(y.cpu().numpy(), want, f"dw {shape}")
+
+
+def test_dw_full_shift_range_and_unaligned_parameters(P):
+    """Shifts from 0 to 31 (the kernel takes the general form of the requantisation), and
+    parameter arrays that are not 16-byte aligned (the one-thread-per-output kernel takes over)."""
+    torch = torch_cuda()
+    D = make_dw_layer(5050, 2, 11, 13, 40, 1, signed_x=True, act_window=(-128, 127), shift_range=(0, 31))
+    want = oracle.dw_conv(D.x, D.weight, 1, D.bias, D.mult, D.shift, -128, 127)
+    y = P.prom_dw_conv(dev(D.x), dev(D.weight), 1, requant_dev(P, D))
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), want, "dw shifts 0..31")
+    pad = lambda a: dev(np.concatenate([np.zeros(1, a.dtype), a]))[1:]
+    rq = P.Requant(pad(D.bias), pad(D.mult), pad(D.shift), -128, 127)
+    y = P.prom_dw_conv(dev(D.x), dev(D.weight), 1, rq)
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), want, "dw unaligned parameters")
+
+
+def test_dw_full_size_layer_every_output(P):
+    """A full-size layer of the batch-128 sweep (56x56x144, both strides), every output."""
+    torch = torch_cuda()
+    for stride in (1, 2):
+        D = make_dw_layer(5060 + stride, 128, 56, 56, 144, stride)
+        want = dev(oracle.dw_conv(D.x, D.weight, stride, D.bias, D.mult, D.shift, D.act_min, D.act_max))
+        x, w, rq = dev(D.x), dev(D.weight), requant_dev(P, D)
+        for run in range(3):
+            y = P.prom_dw_conv(x, w, stride, rq)
+            torch.cuda.synchronize()
+            bad = int((y != want).sum())
+            assert bad == 0, f"stride {stride}, run {run}: {bad} outputs differ"
 
 
 def test_dw_relu6_window(P):
