@@ -69,8 +69,8 @@ def main():
     ap.add_argument("--cpu-sample-images", type=int, default=16)
     ap.add_argument("--no-batching", action="store_true",
                     help="one launch per layer (the library's batching of small independent layers off)")
-    ap.add_argument("--streams", type=int, default=4,
-                    help="streams of the extra 'concurrent' leg (the 34 layers are independent)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="with N > 1: an extra leg that spreads the 34 independent layers over N streams")
     ap.add_argument("--ab", choices=["both", "mfma", "addsub"], default=None,
                     help="instead of the sweep: time the two designs of the pointwise layer "
                          "(MFMA vs add/subtract on the vector ALU) on four representative layers")
