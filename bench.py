@@ -67,6 +67,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
     ap.add_argument("--cpu-sample-images", type=int, default=16)
+    ap.add_argument("--zero-fraction", type=float, default=0.5,
+                    help="P(weight == 0) of the synthetic ternary weights (the paper reports about 0.31 at "
+                         "initialisation and 0.5-0.55 after training); the kernels are dense, so the "
+                         "timing does not depend on it")
     ap.add_argument("--no-batching", action="store_true",
                     help="one launch per layer (the library's batching of small independent layers off)")
     ap.add_argument("--streams", type=int, default=1,
@@ -99,7 +103,7 @@ def main():
     shapes = mobilenetv2_pointwise_layers()
     layers = []
     for i, s in enumerate(shapes):
-        L = make_pw_layer(SEED + i, args.batch, s.hw, s.hw, s.cin, s.cout)
+        L = make_pw_layer(SEED + i, args.batch, s.hw, s.hw, s.cin, s.cout, p_zero=args.zero_fraction)
         x = torch.from_numpy(L.x).to(dev)
         wp = torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev)
         rq = P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
@@ -289,7 +293,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[3]: the 34 ternary pointwise layers of MobileNetV2 1.0 (224x224), "
                                f"batch {args.batch}, int8 NHWC, through prom_pw_conv_sequence",
-                   "batch": args.batch, "layers": len(layers), "launches_per_step": len(runs)},
+                   "batch": args.batch, "layers": len(layers), "launches_per_step": len(runs),
+                   "weight_zero_fraction": args.zero_fraction},
         "sweep": {"algorithmic_bytes": total_bytes, "dense_equiv_ops": total_ops,
                   "gbs": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                   "frac_hbm_roofline": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -442,9 +447,69 @@ def extra_legs(P, torch, dev, batch, log):
     m = B.n * B.h * B.w
     compulsory = m * (B.cin + B.cout)
     out["block_config4"] = {"us": round(dt * 1e6, 1),
+                            "fused": P.prom_block_is_fused(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
                             "compulsory_gbs": round(compulsory / dt / 1e9, 1),
                             "pw_gops": round(2 * m * B.cin * B.chid * 2 / dt / 1e9, 1)}
     log(f"[bench] block (config 4): {dt * 1e6:.1f} us per call")
+    del xs, ys
+
+    # the whole body as a chain: 17 blocks in network order (4 stride-2 depthwise layers), each fed
+    # with the previous block's output; block 1 (no expansion) is a depthwise + a projection call
+    from workloads import make_pw_layer, mobilenetv2_blocks
+    blocks = mobilenetv2_blocks()
+    cur = torch.randint(0, 128, (batch, blocks[0].hw_in, blocks[0].hw_in, blocks[0].cin), dtype=torch.int8,
+                        device=dev)
+    steps, fused, io_bytes, mid_bytes, ws_bytes = [], [], 0, 0, 0
+    for i, b in enumerate(blocks):
+        hw, ho = b.hw_in, (b.hw_in - 1) // b.stride + 1
+        y = torch.empty((batch, ho, ho, b.cout), dtype=torch.int8, device=dev)
+        io_bytes += batch * (hw * hw * b.cin + ho * ho * b.cout)
+        if b.t == 1:
+            D = make_dw_layer(SEED + 3000 + i, 1, hw, hw, b.cin, b.stride, make_x=False)
+            Q = make_pw_layer(SEED + 3100 + i, 1, hw, hw, b.cin, b.cout, act_window=(-128, 127), make_x=False)
+            mid = torch.empty((batch, ho, ho, b.cin), dtype=torch.int8, device=dev)
+            mid_bytes += 2 * mid.numel()
+            steps.append(("dwpw", cur, mid, y, b, t(D.weight), P.Requant(t(D.bias), t(D.mult), t(D.shift), 0, 127),
+                          t(P.prom_pack_ternary(Q.weight)), P.Requant(t(Q.bias), t(Q.mult), t(Q.shift), -128, 127)))
+        else:
+            Bk = make_block(SEED + 3200 + i, 1, hw, hw, b.cin, b.t, b.cout, b.stride)
+            e, d, p = Bk.expand, Bk.dw, Bk.project
+            rq3 = [P.Requant(t(l.bias), t(l.mult), t(l.shift), l.act_min, l.act_max) for l in (e, d, p)]
+            ws_bytes = max(ws_bytes, P.prom_block_workspace_size(batch, hw, hw, b.cin, Bk.chid, b.cout, b.stride))
+            is_fused = P.prom_block_is_fused(batch, hw, hw, b.cin, Bk.chid, b.cout, b.stride)
+            if is_fused:
+                fused.append(b.name)
+            else:
+                mid_bytes += 2 * batch * Bk.chid * (hw * hw + ho * ho)
+            steps.append(("block", cur, None, y, b, Bk.chid, t(P.prom_pack_ternary(e.weight)), t(d.weight),
+                          t(P.prom_pack_ternary(p.weight)), rq3, Bk.add_residual))
+        cur = y
+    ws = torch.empty(ws_bytes, dtype=torch.int8, device=dev)
+
+    def chain():
+        for st in steps:
+            if st[0] == "dwpw":
+                _, xi, mid, yo, b, wd_, rqd, wp_, rqp = st
+                P.prom_dw_conv(xi, wd_, b.stride, rqd, mid)
+                P.prom_pw_conv(mid, wp_, b.cout, rqp, None, yo)
+            else:
+                _, xi, _m, yo, b, chid, we_, wd_, wp_, rq3, addres = st
+                P.prom_block(xi, chid, b.cout, b.stride, we_, rq3[0], wd_, rq3[1], wp_, rq3[2], addres, ws, yo)
+    for _ in range(2):
+        chain()
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        chain()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    out["block_chain"] = {"blocks": len(blocks), "us": round(dt * 1e6, 1), "fused_blocks": fused,
+                          "block_io_mb": round(io_bytes / 1e6, 1),
+                          "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),
+                          "gbs_incl_intermediates": round((io_bytes + mid_bytes) / dt / 1e9, 1)}
+    log(f"[bench] 17-block chain: {dt * 1e6:.1f} us per pass, fused: {', '.join(fused)}; "
+        f"{io_bytes / 1e6:.0f} MB block inputs+outputs, {mid_bytes / 1e6:.0f} MB intermediates of unfused blocks")
     return out
 
 

@@ -193,6 +193,11 @@ int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout
 
 size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
 
+/* 1 if prom_block runs this shape as one fused kernel (the expanded tensor stays on chip; pointers
+ * assumed 8-byte aligned), 0 if as three launches through the workspace, PROM_EINVAL for bad
+ * dimensions.  Host only, launches nothing. */
+int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride);
+
 /* ---- measurement utility ------------------------------------------------------------------
  * Plain streaming copy of nbytes (multiple of 16, both pointers 16-byte aligned) from src to
  * dst, dev to dev, as a kernel of this library: the HBM-bandwidth yardstick the pointwise

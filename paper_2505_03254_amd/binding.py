@@ -87,6 +87,8 @@ def load_library():
     lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC), ctypes.POINTER(ci)]
     lib.prom_pw_conv_sequence.restype = ci
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_block_is_fused.restype = ci
+    lib.prom_block_is_fused.argtypes = [ci] * 7
     lib.prom_pw_batchable.restype = ci
     lib.prom_pw_batchable.argtypes = [ci, ci, ci, ci, ci]
     lib.prom_copy_bytes.restype = ci
@@ -283,6 +285,13 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
         _stream_ptr(stream))
     _check(rc, "prom_block")
     return y
+
+
+def prom_block_is_fused(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:
+    rc = load_library().prom_block_is_fused(n, h, w, cin, chid, cout, stride)
+    if rc < 0:
+        raise PromError(rc, "prom_block_is_fused")
+    return bool(rc)
 
 
 def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:

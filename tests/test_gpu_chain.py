@@ -1,0 +1,85 @@
+"""The whole MobileNetV2 body as a chain: the 17 inverted-residual blocks in network order (the
+four stride-2 depthwise layers included), each block fed with the previous block's output, then
+the 1x1 head.  Block 1 has no expansion convolution (depthwise + projection calls); blocks 2-17
+go through prom_block, which fuses the shapes it can and runs the others as three launches.
+Every block output is compared with the oracle's, which walks the same chain on the CPU, for
+ternary weights with the zero fractions the paper reports at initialisation and after training
+(Section 4.3 / appendix on sparsity: about 0.31, 0.5, 0.55)."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import SplitMix64, make_block, make_dw_layer, make_pw_layer, mobilenetv2_blocks
+from gpu_util import assert_same, dev, requant_dev, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2505_03254_amd as P
+    P.load_library()
+    return P
+
+
+def _pw_shift(k):
+    """A shift range that keeps the output of a k-input ternary layer spread over the int8 range
+    (accumulator spread grows with sqrt(k)); with the generators' default range a chain of layers
+    collapses to per-channel constants after two layers."""
+    s = max(0, int(round(np.log2(np.sqrt(k) + 1.0))))
+    return (s, s + 1)
+
+
+DW_SHIFT = (8, 9)
+
+
+def _tup(l):
+    return (l.weight, l.bias, l.mult, l.shift, l.act_min, l.act_max)
+
+
+@pytest.mark.parametrize("p_zero,input_hw,n", [(0.5, 32, 2), (0.31, 16, 3), (0.55, 20, 1)])
+def test_mobilenetv2_block_chain(P, p_zero, input_hw, n):
+    torch = torch_cuda()
+    blocks = mobilenetv2_blocks(input_hw)
+    seed = 7700 + int(p_zero * 100)
+    x_host = SplitMix64(seed).bytes_masked(n * input_hw * input_hw * blocks[0].cin, 0x7F).view(np.int8)
+    x_host = x_host.reshape(n, input_hw, input_hw, blocks[0].cin)
+    x_dev = dev(x_host)
+    fused = []
+    for i, b in enumerate(blocks):
+        hw = b.hw_in
+        if b.t == 1:
+            D = make_dw_layer(seed + 10 * i + 1, n, hw, hw, b.cin, b.stride, act_window=(0, 127),
+                              shift_range=DW_SHIFT, make_x=False)
+            Q = make_pw_layer(seed + 10 * i + 2, n, hw, hw, b.cin, b.cout, act_window=(-128, 127),
+                              p_zero=p_zero, shift_range=_pw_shift(b.cin), make_x=False)
+            t = P.prom_dw_conv(x_dev, dev(D.weight), b.stride, requant_dev(P, D))
+            y_dev = P.prom_pw_conv(t, dev(P.prom_pack_ternary(Q.weight)), b.cout, requant_dev(P, Q))
+            th = oracle.dw_conv(x_host, D.weight, b.stride, D.bias, D.mult, D.shift, 0, 127)
+            y_host = oracle.pw_conv(th, Q.weight, Q.bias, Q.mult, Q.shift, -128, 127)
+        else:
+            B = make_block(seed + 10 * i, n, hw, hw, b.cin, b.t, b.cout, b.stride, p_zero=p_zero,
+                           expand_shift=_pw_shift(b.cin), dw_shift=DW_SHIFT,
+                           project_shift=_pw_shift(b.cin * b.t))
+            ws = torch.empty(P.prom_block_workspace_size(n, hw, hw, b.cin, B.chid, b.cout, b.stride),
+                             dtype=torch.int8, device="cuda")
+            y_dev = P.prom_block(x_dev, B.chid, b.cout, b.stride,
+                                 dev(P.prom_pack_ternary(B.expand.weight)), requant_dev(P, B.expand),
+                                 dev(B.dw.weight), requant_dev(P, B.dw),
+                                 dev(P.prom_pack_ternary(B.project.weight)), requant_dev(P, B.project),
+                                 B.add_residual, ws)
+            y_host, _, _ = oracle.block(x_host, _tup(B.expand), _tup(B.dw), _tup(B.project), b.stride,
+                                        B.add_residual)
+            fused.append(P.prom_block_is_fused(n, hw, hw, b.cin, B.chid, b.cout, b.stride))
+        torch.cuda.synchronize()
+        assert_same(y_dev.cpu().numpy(), y_host, f"chain p_zero={p_zero} {b.name}")
+        assert len(np.unique(y_host)) > 24, f"{b.name}: the chain's activations degenerated"
+        x_dev, x_host = y_dev, y_host
+    # the chain must exercise both forms of prom_block
+    assert any(fused) and not all(fused)
+    hw = x_host.shape[1]
+    H = make_pw_layer(seed + 999, n, hw, hw, blocks[-1].cout, 1280, p_zero=p_zero,
+                      shift_range=_pw_shift(blocks[-1].cout), make_x=False)
+    y_dev = P.prom_pw_conv(x_dev, dev(P.prom_pack_ternary(H.weight)), 1280, requant_dev(P, H))
+    torch.cuda.synchronize()
+    assert_same(y_dev.cpu().numpy(), oracle.pw_conv(x_host, H.weight, H.bias, H.mult, H.shift, 0, 127), "head")

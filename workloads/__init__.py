@@ -10,6 +10,7 @@ from .generators import (  # noqa: F401
     make_pw_layer, make_dw_layer, make_block, CONFIG_SEED_BASE,
 )
 from .mobilenetv2 import (  # noqa: F401
-    PwShape, DwShape, mobilenetv2_pointwise_layers, mobilenetv2_depthwise_layers,
+    PwShape, DwShape, BlockShape, mobilenetv2_pointwise_layers, mobilenetv2_depthwise_layers,
+    mobilenetv2_blocks,
     mobilenetv2_param_counts, BASELINE_CONFIGS,
 )

@@ -193,7 +193,9 @@ def make_dw_layer(seed: int, n: int, h: int, w: int, c: int, stride: int = 1, *,
 
 
 def make_block(seed: int, n: int, h: int, w: int, cin: int, t: int, cout: Optional[int] = None,
-               stride: int = 1, *, signed_x: bool = False) -> BlockInputs:
+               stride: int = 1, *, signed_x: bool = False, p_zero: float = 0.5,
+               expand_shift: Tuple[int, int] = (8, 14), dw_shift: Tuple[int, int] = (8, 14),
+               project_shift: Tuple[int, int] = (8, 14)) -> BlockInputs:
     """Inverted-residual block: expand (clamp [0,127]) -> depthwise 3x3 (clamp [0,127]) ->
     project (clamp [-128,127]) + saturating add of the block input when stride==1 and
     cin==cout."""
@@ -205,10 +207,10 @@ def make_block(seed: int, n: int, h: int, w: int, cin: int, t: int, cout: Option
     ho = (h + 2 - 3) // stride + 1
     wo = (w + 2 - 3) // stride + 1
     expand = make_pw_layer(int(root.substream(21).seed), n, h, w, cin, chid,
-                           act_window=(0, 127), make_x=False)
+                           act_window=(0, 127), p_zero=p_zero, shift_range=expand_shift, make_x=False)
     dw = make_dw_layer(int(root.substream(22).seed), n, h, w, chid, stride,
-                       act_window=(0, 127), make_x=False)
+                       act_window=(0, 127), shift_range=dw_shift, make_x=False)
     project = make_pw_layer(int(root.substream(23).seed), n, ho, wo, chid, cout,
-                            act_window=(-128, 127), make_x=False)
+                            act_window=(-128, 127), p_zero=p_zero, shift_range=project_shift, make_x=False)
     add_res = (stride == 1 and cin == cout)
     return BlockInputs(n, h, w, cin, chid, cout, stride, add_res, x, expand, dw, project)

@@ -36,6 +36,30 @@ class DwShape:
     stride: int
 
 
+@dataclass(frozen=True)
+class BlockShape:
+    name: str
+    hw_in: int
+    cin: int
+    t: int       # expansion factor; 1 = no expansion convolution
+    cout: int
+    stride: int
+
+
+def mobilenetv2_blocks(input_hw: int = INPUT_RES // 2) -> List[BlockShape]:
+    """The 17 inverted-residual blocks in network order; input_hw is the spatial size after the
+    stem (112 for 224x224 images; smaller values give the same chain on smaller maps)."""
+    out: List[BlockShape] = []
+    hw, cin, b = input_hw, STEM_CHANNELS, 0
+    for t, c, n, s in BOTTLENECKS:
+        for i in range(n):
+            b += 1
+            stride = s if i == 0 else 1
+            out.append(BlockShape(f"b{b}", hw, cin, t, c, stride))
+            hw, cin = (hw + 2 - 3) // stride + 1, c
+    return out
+
+
 def _walk():
     pw: List[PwShape] = []
     dw: List[DwShape] = []
