@@ -1,0 +1,51 @@
+"""CPU oracle of the weight quantisers that feed the path (test infrastructure only; the HIP
+product path never imports this).
+
+What it computes follows the paper's Section 3.1 and its pseudocode of the weight quantisation
+(appendix figure "quantization of conv weights"), where the two disagree the pseudocode:
+  pointwise (ternary, channel-wise absmean)
+      scale_i = 1 / max(mean_j |W[i][j]|, eps)             (the pseudocode clamps the mean at eps;
+                                                            Eq. 3 adds eps instead)
+      What[i][j] = clamp(round(W[i][j] * scale_i), -1, 1)
+  depthwise (8-bit, channel-wise absmax)
+      scale_i = 127 / max(max_{k,l} |W[i][k][l]|, eps)      (the pseudocode has the factor 127 that
+                                                            Eq. 5 leaves out)
+      What[i][k][l] = clamp(round(W * scale_i), -128, 127)
+round() is round-half-to-even, as torch.round in the pseudocode.
+
+Precision.  The paper's code runs in float32 and a quantised code is decided by a float32
+product, so the decision is taken in float32 here as well: the mean of |W| is the sum of the row
+in float64 (sequential, numpy's) divided by cin and rounded once to float32 -- the one place where
+the order of a float32 reduction would otherwise be left to the implementation --, the scale is
+one correctly rounded float32 division, and W * scale is one float32 multiplication.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def quantize_pw_absmean(w: np.ndarray, eps: float = 1e-5):
+    """w: float32 [cout][cin].  Returns (codes int8 [cout][cin] in {-1,0,1}, scale float32 [cout])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    cout, cin = w.shape
+    mean = np.empty(cout, dtype=np.float32)
+    for i in range(cout):
+        s = 0.0
+        for v in np.abs(w[i]).astype(np.float64):  # plain sequential float64 sum
+            s += float(v)
+        mean[i] = np.float32(s / cin)
+    scale = (np.float32(1.0) / np.maximum(mean, np.float32(eps))).astype(np.float32)
+    q = np.rint((w * scale[:, None]).astype(np.float32))  # float32 product, half-to-even
+    return np.clip(q, -1, 1).astype(np.int8), scale
+
+
+def quantize_dw_absmax(w: np.ndarray, eps: float = 1e-5):
+    """w: float32 [c][3][3] (one 3x3 filter per channel, the paper's [c_out,1,k,k] without the
+    singleton).  Returns (q int8 [3][3][c], the layout prom_dw_conv takes, scale float32 [c])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    c = w.shape[0]
+    amax = np.max(np.abs(w.reshape(c, -1)), axis=1).astype(np.float32)
+    scale = (np.float32(127.0) / np.maximum(amax, np.float32(eps))).astype(np.float32)
+    q = np.rint((w.reshape(c, -1) * scale[:, None]).astype(np.float32))
+    q = np.clip(q, -128, 127).astype(np.int8).reshape(c, 3, 3)
+    return np.ascontiguousarray(np.transpose(q, (1, 2, 0))), scale
