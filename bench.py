@@ -504,6 +504,31 @@ def extra_legs(P, torch, dev, batch, log):
         chain()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
+    # weight preparation: float32 weights of all 34 pointwise and 17 depthwise layers through the
+    # device quantisers (ternary absmean straight into the packed layout, 8-bit absmax)
+    from workloads import float_conv_weights, mobilenetv2_pointwise_layers
+    pws = [torch.from_numpy(float_conv_weights(SEED + 4000 + i, s_.cout, s_.cin)).to(dev)
+           for i, s_ in enumerate(mobilenetv2_pointwise_layers())]
+    dwf = [torch.from_numpy(float_conv_weights(SEED + 4100 + i, d.c, 9).reshape(d.c, 3, 3)).to(dev)
+           for i, d in enumerate(mobilenetv2_depthwise_layers())]
+
+    def prep():
+        for w_ in pws:
+            P.prom_quantize_pw_absmean(w_)
+        for w_ in dwf:
+            P.prom_quantize_dw_absmax(w_)
+    prep()
+    torch.cuda.synchronize()
+    tq0 = time.perf_counter()
+    for _ in range(3):
+        prep()
+    torch.cuda.synchronize()
+    dq = (time.perf_counter() - tq0) / 3
+    nweights = sum(w_.numel() for w_ in pws) + sum(w_.numel() for w_ in dwf)
+    out["weight_prep"] = {"layers": len(pws) + len(dwf), "weights": nweights, "us": round(dq * 1e6, 1),
+                          "note": "51 small launches; host call overhead dominates"}
+    log(f"[bench] weight preparation: {nweights} float32 weights of {len(pws) + len(dwf)} layers in {dq * 1e6:.0f} us")
+
     out["block_chain"] = {"blocks": len(blocks), "us": round(dt * 1e6, 1), "fused_blocks": fused,
                           "block_io_mb": round(io_bytes / 1e6, 1),
                           "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),

@@ -100,6 +100,29 @@ int prom_pack_ternary(const int8_t *w_host, int cout, int cin, void *packed_host
 int prom_unpack_ternary(const void *packed_host, size_t packed_bytes, int cout, int cin,
                         int8_t *w_host);
 
+/* ---- weight preparation (the step before the path; paper Section 3.1 and its pseudocode of the
+ * weight quantisation) ------------------------------------------------------------------
+ * Channel-wise absmean ternary quantisation of a pointwise layer, on the device:
+ *   scale[i] = 1 / max(mean_j |w[i][j]|, eps),  code = clamp(round(w[i][j] * scale[i]), -1, 1),
+ * round half to even; the mean is the float64 sum of the row divided by cin and rounded to
+ * float32, the scale one float32 division, the product one float32 multiplication (the paper's
+ * code is float32).  The per-channel dequantisation factor of the layer is 1 / scale[i].
+ *   w       dev float32 [cout][cin]
+ *   packed  dev, receives the prom_pack_ternary layout (prom_packed_size(cout, cin) bytes,
+ *           4-byte aligned): ready to be passed as w_packed
+ *   codes   dev int8 [cout][cin] or NULL: the codes unpacked, for inspection
+ *   scale   dev float32 [cout]
+ * PROM_EINVAL for null / misaligned pointers, non-positive sizes or eps <= 0; PROM_EWORKSPACE
+ * if packed_bytes is too small. */
+int prom_quantize_pw_absmean(const float *w, int cout, int cin, float eps, void *packed,
+                             size_t packed_bytes, int8_t *codes, float *scale, void *stream);
+
+/* Channel-wise absmax 8-bit quantisation of a depthwise 3x3 layer, on the device:
+ *   scale[c] = 127 / max(max_t |w[c][t]|, eps),  q = clamp(round(w[c][t] * scale[c]), -128, 127).
+ *   w   dev float32 [c][3][3] (the paper's [c_out][1][k][k])
+ *   wq  dev int8 [3][3][c], the layout prom_dw_conv takes;  scale dev float32 [c] */
+int prom_quantize_dw_absmax(const float *w, int c, float eps, int8_t *wq, float *scale, void *stream);
+
 /* ---- pointwise 1x1 convolution with ternary weights ------------------------------------
  * y[m][co] = requant_co( sum_k x[m][k] * W[co][k] ),  m over n*h*w pixels.
  *   x         dev int8 [n][h][w][cin]

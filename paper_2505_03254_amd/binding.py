@@ -87,6 +87,10 @@ def load_library():
     lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC), ctypes.POINTER(ci)]
     lib.prom_pw_conv_sequence.restype = ci
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_quantize_pw_absmean.restype = ci
+    lib.prom_quantize_pw_absmean.argtypes = [vp, ci, ci, ctypes.c_float, vp, sz, vp, vp, vp]
+    lib.prom_quantize_dw_absmax.restype = ci
+    lib.prom_quantize_dw_absmax.argtypes = [vp, ci, ctypes.c_float, vp, vp, vp]
     lib.prom_block_is_fused.restype = ci
     lib.prom_block_is_fused.argtypes = [ci] * 7
     lib.prom_pw_batchable.restype = ci
@@ -285,6 +289,37 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
         _stream_ptr(stream))
     _check(rc, "prom_block")
     return y
+
+
+def prom_quantize_pw_absmean(w, eps: float = 1e-5, want_codes: bool = False, stream=None):
+    """w: float32 [cout, cin] device.  Returns (packed uint8 device tensor in the prom_pack_ternary
+    layout, scale float32 [cout], codes int8 [cout, cin] or None)."""
+    import torch
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 2):
+        raise TypeError("w must be a contiguous float32 [cout, cin] device tensor")
+    cout, cin = w.shape
+    nbytes = prom_packed_size(cout, cin)
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    scale = torch.empty(cout, dtype=torch.float32, device=w.device)
+    codes = torch.empty((cout, cin), dtype=torch.int8, device=w.device) if want_codes else None
+    _check(load_library().prom_quantize_pw_absmean(
+        w.data_ptr(), cout, cin, float(eps), packed.data_ptr(), nbytes,
+        codes.data_ptr() if codes is not None else None, scale.data_ptr(), _stream_ptr(stream)),
+        "prom_quantize_pw_absmean")
+    return packed, scale, codes
+
+
+def prom_quantize_dw_absmax(w, eps: float = 1e-5, stream=None):
+    """w: float32 [c, 3, 3] device.  Returns (int8 [3, 3, c] device tensor, scale float32 [c])."""
+    import torch
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and tuple(w.shape[1:]) == (3, 3)):
+        raise TypeError("w must be a contiguous float32 [c, 3, 3] device tensor")
+    c = w.shape[0]
+    wq = torch.empty((3, 3, c), dtype=torch.int8, device=w.device)
+    scale = torch.empty(c, dtype=torch.float32, device=w.device)
+    _check(load_library().prom_quantize_dw_absmax(w.data_ptr(), c, float(eps), wq.data_ptr(), scale.data_ptr(),
+                                                  _stream_ptr(stream)), "prom_quantize_dw_absmax")
+    return wq, scale
 
 
 def prom_block_is_fused(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:

@@ -214,3 +214,22 @@ def make_block(seed: int, n: int, h: int, w: int, cin: int, t: int, cout: Option
                             act_window=(-128, 127), p_zero=p_zero, shift_range=project_shift, make_x=False)
     add_res = (stride == 1 and cin == cout)
     return BlockInputs(n, h, w, cin, chid, cout, stride, add_res, x, expand, dw, project)
+
+
+def float_conv_weights(seed: int, cout: int, fan: int, *, kind: str = "kaiming") -> np.ndarray:
+    """Seeded float32 weights [cout][fan] as a network holds them before quantisation: Kaiming
+    normal (std sqrt(2/cout), the initialisation the paper's appendix analyses) or, with
+    kind="trained", the same with every tenth row scaled by 1e-3 .. 1e3 and a few exact zeros and
+    half-way values planted, to exercise the per-channel scale, the eps clamp and the rounding ties."""
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((cout, fan)) * np.sqrt(2.0 / cout)).astype(np.float32)
+    if kind == "trained":
+        for i in range(0, cout, 10):
+            w[i] *= np.float32(10.0 ** rng.integers(-3, 4))
+        w[rng.integers(0, cout, 8), rng.integers(0, fan, 8)] = 0.0
+        if cout > 3:
+            w[3] = 0.0            # a dead channel: the eps clamp decides
+        if cout > 5 and fan >= 4:
+            w[5, :] = 0.0
+            w[5, :4] = np.array([0.5, -0.5, 1.5, -1.5], dtype=np.float32)[: min(4, fan)]
+    return w
