@@ -6,4 +6,4 @@ package; the HIP product path never does.
 from .prom_oracle import (  # noqa: F401
     build, requant, pw_accum, pw_conv, dw_conv, block, max_threads, set_threads,
 )
-from .quant_oracle import quantize_pw_absmean, quantize_dw_absmax  # noqa: F401,E402
+from .quant_oracle import quantize_pw_absmean, quantize_dw_absmax, quantize_activation_absmax  # noqa: F401,E402

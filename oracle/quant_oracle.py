@@ -49,3 +49,17 @@ def quantize_dw_absmax(w: np.ndarray, eps: float = 1e-5):
     q = np.rint((w.reshape(c, -1) * scale[:, None]).astype(np.float32))
     q = np.clip(q, -128, 127).astype(np.int8).reshape(c, 3, 3)
     return np.ascontiguousarray(np.transpose(q, (1, 2, 0))), scale
+
+
+def quantize_activation_absmax(x: np.ndarray, eps: float = 1e-5):
+    """The paper's activation quantiser (Section 3.1, Eq. 6-7, with the factor 127 and the eps
+    clamp of its pseudocode): one scale per batch element over all its channels and pixels.
+    x: float32 [n][...].  Returns (q int8, same shape; scale float32 [n]).  The maximum is exact,
+    the scale one float32 division, the code one float32 product rounded half to even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n = x.shape[0]
+    flat = x.reshape(n, -1)
+    amax = np.max(np.abs(flat), axis=1).astype(np.float32)
+    scale = (np.float32(127.0) / np.maximum(amax, np.float32(eps))).astype(np.float32)
+    q = np.rint((flat * scale[:, None]).astype(np.float32))
+    return np.clip(q, -128, 127).astype(np.int8).reshape(x.shape), scale

@@ -93,3 +93,38 @@ def test_against_the_papers_pseudocode_in_torch():
     # torch evaluates 127.0 / t as reciprocal(t) * 127, one rounding more than the single division
     # taken here: scales agree to the last bit or so, codes wherever w*scale is not on a threshold
     assert (qd != np.transpose(wantd, (1, 2, 0))).mean() < 1e-3 and np.allclose(s2, sd.numpy().ravel(), rtol=3e-7)
+
+
+def test_activation_absmax_hand_example_and_properties():
+    x = np.zeros((3, 2, 2, 2), dtype=np.float32)
+    x[0].reshape(-1)[:] = [2.0, -1.0, 0.5, 0.0, 0.0078125, 1.0, -2.0, 0.25]   # absmax 2 -> scale 63.5
+    x[2].reshape(-1)[:] = [1e-7, 0, 0, 0, 0, 0, 0, -2e-7]                      # below eps: scale 127/eps
+    q, scale = oracle.quantize_activation_absmax(x, eps=1e-5)
+    # 63.5 * (2, -1, .5, 0, 2^-7, 1, -2, .25) = 127, -63.5 -> -64 (even), 31.75 -> 32, 0, 0.496 -> 0, 63.5 -> 64, -127, 15.875 -> 16
+    assert q[0].reshape(-1).tolist() == [127, -64, 32, 0, 0, 64, -127, 16]
+    assert scale[0] == np.float32(63.5)
+    assert not q[1].any() and scale[1] == np.float32(127.0) / np.float32(1e-5)
+    # 1e-7 * 1.27e7 = 1.27 -> 1, -2e-7 -> -2.54 -> -3
+    assert q[2].reshape(-1).tolist() == [1, 0, 0, 0, 0, 0, 0, -3]
+    rng = np.random.default_rng(5)
+    y = rng.standard_normal((4, 7, 5, 3)).astype(np.float32) * np.float32(3.0)
+    qy, sy = oracle.quantize_activation_absmax(y)
+    for i in range(4):                      # the extreme element of every image maps to +-127
+        k = np.argmax(np.abs(y[i]))
+        assert abs(int(qy[i].reshape(-1)[k])) == 127
+    q2, s2 = oracle.quantize_activation_absmax(y * np.float32(4.0))   # power of two: same codes
+    assert np.array_equal(q2, qy) and np.array_equal(s2 * np.float32(4.0), sy)
+    # images are independent: quantising one alone gives the same codes
+    q1, _ = oracle.quantize_activation_absmax(y[2:3])
+    assert np.array_equal(q1[0], qy[2])
+
+
+def test_activation_absmax_against_the_papers_pseudocode_in_torch():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((5, 16, 9, 9)).astype(np.float32)
+    t = torch.from_numpy(x)
+    scale = 127.0 / t.abs().flatten(start_dim=1).max(dim=-1, keepdim=True).values.clamp_(min=1e-5)
+    want = (t.flatten(start_dim=1) * scale).round().clamp_(-128, 127).numpy().astype(np.int8).reshape(x.shape)
+    q, s = oracle.quantize_activation_absmax(x)
+    assert (q != want).mean() < 1e-3 and np.allclose(s, scale.numpy().ravel(), rtol=3e-7)
