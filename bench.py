@@ -529,6 +529,26 @@ def extra_legs(P, torch, dev, batch, log):
                           "note": "51 small launches; host call overhead dominates"}
     log(f"[bench] weight preparation: {nweights} float32 weights of {len(pws) + len(dwf)} layers in {dq * 1e6:.0f} us")
 
+    # dynamic per-sample activation quantisation (float32 -> int8, one absmax scale per image)
+    xa = torch.randn((batch, 56, 56, 144), dtype=torch.float32, device=dev)
+    qa = torch.empty(xa.shape, dtype=torch.int8, device=dev)
+    sa = torch.empty(batch, dtype=torch.float32, device=dev)
+    for _ in range(2):
+        P.prom_quantize_activation_absmax(xa, q=qa, scale=sa)
+    torch.cuda.synchronize()
+    ta0 = time.perf_counter()
+    for _ in range(10):
+        P.prom_quantize_activation_absmax(xa, q=qa, scale=sa)
+    torch.cuda.synchronize()
+    da = (time.perf_counter() - ta0) / 10
+    alg = xa.numel() * 5  # read once as float32, write int8
+    out["activation_quant"] = {"shape": list(xa.shape), "us": round(da * 1e6, 1),
+                               "algorithmic_gbs": round(alg / da / 1e9, 1),
+                               "frac_hbm_roofline": round(alg / da / 1e9 / HBM_PEAK_GBS, 4),
+                               "note": "two passes over the float32 input (maximum, then quantise)"}
+    log(f"[bench] activation quantiser {list(xa.shape)}: {da * 1e6:.1f} us, {alg / da / 1e9:.0f} GB/s algorithmic")
+    del xa, qa
+
     out["block_chain"] = {"blocks": len(blocks), "us": round(dt * 1e6, 1), "fused_blocks": fused,
                           "block_io_mb": round(io_bytes / 1e6, 1),
                           "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),

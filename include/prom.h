@@ -123,6 +123,17 @@ int prom_quantize_pw_absmean(const float *w, int cout, int cin, float eps, void 
  *   wq  dev int8 [3][3][c], the layout prom_dw_conv takes;  scale dev float32 [c] */
 int prom_quantize_dw_absmax(const float *w, int c, float eps, int8_t *wq, float *scale, void *stream);
 
+/* Activation quantisation with one dynamic scale per batch element (paper Section 3.1, Eq. 6-7;
+ * factor 127 and eps clamp as in its pseudocode), on the device:
+ *   scale[i] = 127 / max(max over the image |x[i][...]|, eps),
+ *   q[i][...] = clamp(round(x[i][...] * scale[i]), -128, 127), round half to even, float32.
+ *   x      dev float32 [n][per_image] (any layout inside an image: the scale is over all of it)
+ *   q      dev int8 [n][per_image];  scale dev float32 [n] (also used as scratch during the call)
+ * Two passes over x (maximum, then quantise) plus two tiny kernels; n <= 65535.  PROM_EINVAL
+ * for null or misaligned pointers, non-positive sizes, eps <= 0. */
+int prom_quantize_activation_absmax(const float *x, int n, long long per_image, float eps, int8_t *q,
+                                    float *scale, void *stream);
+
 /* ---- pointwise 1x1 convolution with ternary weights ------------------------------------
  * y[m][co] = requant_co( sum_k x[m][k] * W[co][k] ),  m over n*h*w pixels.
  *   x         dev int8 [n][h][w][cin]

@@ -89,6 +89,8 @@ def load_library():
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
     lib.prom_quantize_pw_absmean.restype = ci
     lib.prom_quantize_pw_absmean.argtypes = [vp, ci, ci, ctypes.c_float, vp, sz, vp, vp, vp]
+    lib.prom_quantize_activation_absmax.restype = ci
+    lib.prom_quantize_activation_absmax.argtypes = [vp, ci, ctypes.c_longlong, ctypes.c_float, vp, vp, vp]
     lib.prom_quantize_dw_absmax.restype = ci
     lib.prom_quantize_dw_absmax.argtypes = [vp, ci, ctypes.c_float, vp, vp, vp]
     lib.prom_block_is_fused.restype = ci
@@ -307,6 +309,23 @@ def prom_quantize_pw_absmean(w, eps: float = 1e-5, want_codes: bool = False, str
         codes.data_ptr() if codes is not None else None, scale.data_ptr(), _stream_ptr(stream)),
         "prom_quantize_pw_absmean")
     return packed, scale, codes
+
+
+def prom_quantize_activation_absmax(x, eps: float = 1e-5, q=None, scale=None, stream=None):
+    """x: float32 [n, ...] device.  Returns (int8 tensor of x's shape, scale float32 [n])."""
+    import torch
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() >= 1):
+        raise TypeError("x must be a contiguous float32 device tensor [n, ...]")
+    n = x.shape[0]
+    per = x.numel() // n
+    if q is None:
+        q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    if scale is None:
+        scale = torch.empty(n, dtype=torch.float32, device=x.device)
+    _check(load_library().prom_quantize_activation_absmax(x.data_ptr(), n, per, float(eps), q.data_ptr(),
+                                                          scale.data_ptr(), _stream_ptr(stream)),
+           "prom_quantize_activation_absmax")
+    return q, scale
 
 
 def prom_quantize_dw_absmax(w, eps: float = 1e-5, stream=None):

@@ -9,6 +9,7 @@
 //   scale = 1.0f / max(mean, eps)          (one correctly rounded division; 127.0f / ... for absmax)
 //   code  = clamp(rint(w * scale))         (float32 product, round half to even)
 // One wavefront per output channel; a lane owns whole 16-weight words of the packed row.
+// Also here: the paper's activation quantiser (one absmax scale per batch element).
 #include "prom.h"
 #include "prom_launch.h"
 
@@ -80,7 +81,107 @@ __global__ __launch_bounds__(256) void quant_dw_kernel(const float *__restrict__
     }
 }
 
+// ---- activations: one absmax scale per batch element (paper Section 3.1, Eq. 6-7) -------------
+// Pass 1: absmax per image.  |x| >= 0, so the float bits order like unsigned integers and the
+// per-image maximum is an atomic max on the bit pattern (the target is cleared by a fill kernel).
+// Pass 2: scale = 127 / max(absmax, eps); q = clamp(rint(x * scale), -128, 127), 4 per dword.
+// Pass 3 turns the stored absmax into the scale the caller gets.
+__global__ __launch_bounds__(256) void act_clear_kernel(uint32_t *amax_bits, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) amax_bits[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void act_absmax_kernel(const float *__restrict__ x, long long per_image,
+                                                         uint32_t *__restrict__ amax_bits)
+{
+    __shared__ float part[4];
+    const int img = blockIdx.y;
+    const float *xi = x + (long long)img * per_image;
+    const long long n4 = per_image >> 2;  // whole float4 groups (the image base is 16-byte aligned when per_image % 4 == 0)
+    const bool vec = ((per_image & 3) == 0) && ((((uintptr_t)x) & 15) == 0);
+    float m = 0.0f;
+    const long long stride = (long long)gridDim.x * 256;
+    if (vec) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(xi);
+        for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+            const float4 v = x4[i];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+    } else {
+        for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < per_image; i += stride)
+            m = fmaxf(m, fabsf(xi[i]));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        atomicMax(&amax_bits[img], __float_as_uint(m));
+    }
+}
+
+__device__ __forceinline__ int quant_i8(float v, float scale)
+{
+    const float q = rintf(__fmul_rn(v, scale));
+    return (int)fminf(fmaxf(q, -128.0f), 127.0f);
+}
+
+__global__ __launch_bounds__(256) void act_quant_kernel(const float *__restrict__ x, long long per_image, float eps,
+                                                        const uint32_t *__restrict__ amax_bits,
+                                                        int8_t *__restrict__ q)
+{
+    const int img = blockIdx.y;
+    const float scale = __fdiv_rn(127.0f, fmaxf(__uint_as_float(amax_bits[img]), eps));
+    const float *xi = x + (long long)img * per_image;
+    int8_t *qi = q + (long long)img * per_image;
+    const bool vec = ((per_image & 3) == 0) && ((((uintptr_t)x) & 15) == 0) && ((((uintptr_t)q) & 3) == 0);
+    const long long stride = (long long)gridDim.x * 256;
+    if (vec) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(xi);
+        uint32_t *q4 = reinterpret_cast<uint32_t *>(qi);
+        const long long n4 = per_image >> 2;
+        for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+            const float4 v = x4[i];
+            q4[i] = ((uint32_t)quant_i8(v.x, scale) & 255u) | (((uint32_t)quant_i8(v.y, scale) & 255u) << 8) |
+                    (((uint32_t)quant_i8(v.z, scale) & 255u) << 16) | ((uint32_t)quant_i8(v.w, scale) << 24);
+        }
+    } else {
+        for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < per_image; i += stride)
+            qi[i] = (int8_t)quant_i8(xi[i], scale);
+    }
+}
+
+__global__ __launch_bounds__(256) void act_scale_kernel(uint32_t *amax_bits, int n, float eps)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) amax_bits[i] = __float_as_uint(__fdiv_rn(127.0f, fmaxf(__uint_as_float(amax_bits[i]), eps)));
+}
+
 }  // namespace prom
+
+extern "C" int prom_quantize_activation_absmax(const float *x, int n, long long per_image, float eps, int8_t *q,
+                                               float *scale, void *stream)
+{
+    using namespace prom;
+    if (!x || !q || !scale || n <= 0 || per_image <= 0 || !(eps > 0.0f)) return PROM_EINVAL;
+    if ((((uintptr_t)x | (uintptr_t)scale) & 3) != 0 || n > 65535) return PROM_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t *bits = reinterpret_cast<uint32_t *>(scale);
+    // enough workgroups per image to fill the chip, each with at least a few KB to stream
+    long long per = (per_image / 4 + 255) / 256;
+    long long want = (256LL * 8 + n - 1) / n;
+    if (want < 1) want = 1;
+    const unsigned bx = (unsigned)(per < want ? (per < 1 ? 1 : per) : want);
+    clear_hip_error();
+    hipLaunchKernelGGL(act_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bits, n);
+    hipLaunchKernelGGL(act_absmax_kernel, dim3(bx, (unsigned)n), dim3(256), 0, st, x, per_image, bits);
+    hipLaunchKernelGGL(act_quant_kernel, dim3(bx, (unsigned)n), dim3(256), 0, st, x, per_image, eps,
+                       static_cast<const uint32_t *>(bits), q);
+    hipLaunchKernelGGL(act_scale_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bits, n, eps);
+    return check_launch();
+}
 
 extern "C" int prom_quantize_pw_absmean(const float *w, int cout, int cin, float eps, void *packed,
                                         size_t packed_bytes, int8_t *codes, float *scale, void *stream)

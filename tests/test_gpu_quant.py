@@ -90,3 +90,31 @@ def test_quantiser_argument_errors(P):
     assert lib.prom_quantize_pw_absmean(w.data_ptr(), 4, 16, 0.0, out.data_ptr(), 64, None, sc.data_ptr(), st) == -1
     assert lib.prom_quantize_pw_absmean(None, 4, 16, 1e-5, out.data_ptr(), 64, None, sc.data_ptr(), st) == -1
     assert lib.prom_quantize_dw_absmax(w.data_ptr(), 0, 1e-5, out.data_ptr(), sc.data_ptr(), st) == -1
+
+
+def test_activation_absmax_per_sample(P):
+    """The paper's dynamic activation quantiser: one absmax scale per batch element.  Codes and
+    scales bit for bit, for images of very different magnitude, sizes off the 4-element vector
+    width, an all-zero image and one below eps."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(8400)
+    for shape in ((6, 14, 14, 384), (3, 5, 7, 3), (1, 56, 56, 144), (5, 1), (2, 1025), (64, 7, 7, 160)):
+        x = rng.standard_normal(shape).astype(np.float32)
+        for i in range(shape[0]):
+            x[i] *= np.float32(10.0 ** rng.integers(-4, 5))
+        if shape[0] > 2:
+            x[1] = 0.0
+            x[2] *= np.float32(1e-9)
+        q, scale = P.prom_quantize_activation_absmax(dev(x))
+        torch.cuda.synchronize()
+        want, s = oracle.quantize_activation_absmax(x)
+        assert_same(q.cpu().numpy(), want, f"activation codes {shape}")
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)), f"scales {shape}"
+    # twice in a row into the same buffers: the scratch use of `scale` leaves nothing behind
+    x = rng.standard_normal((4, 28, 28, 32)).astype(np.float32)
+    xd = dev(x)
+    q, scale = P.prom_quantize_activation_absmax(xd)
+    q2, scale2 = P.prom_quantize_activation_absmax(dev(x * np.float32(0.5)), q=q, scale=scale)
+    torch.cuda.synchronize()
+    want, s = oracle.quantize_activation_absmax(x * np.float32(0.5))
+    assert_same(q2.cpu().numpy(), want, "second call") and np.array_equal(scale2.cpu().numpy(), s)
