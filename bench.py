@@ -121,46 +121,36 @@ def main():
     log(f"[bench] workload built in {time.time() - t_setup:.1f}s: {len(layers)} layers, "
         f"{total_bytes / 1e6:.1f} MB algorithmic, {total_ops / 1e9:.2f} Gop per step")
 
-    # ---- launch groups: prom_pw_conv_sequence puts consecutive small independent layers into
-    # one launch (kernel prom::pw_batch_kernel); every other layer is its own launch.  A group is
-    # what one kernel name covers: a batch, or all single launches of one template instantiation.
+    # ---- launch groups: prom_pw_conv_sequence puts independent small layers into one launch
+    # (prom::pw_batch_kernel) and independent large layers whose plan it carries into another
+    # (prom::pw_bigbatch_kernel); every other layer is its own launch.  A group is what one kernel
+    # name covers: a batch, or all single launches of one template instantiation.  The step calls
+    # prom_pw_conv_sequence once per group, in the order a single call over all 34 layers would
+    # launch them (large batch, single layers, small batch), so that the launches of the dominant
+    # group can be bracketed by events.
     for l in layers:
         s_ = l["shape"]
-        l["batch"] = P.prom_pw_batchable(args.batch, s_.hw, s_.hw, s_.cin, s_.cout) and not args.no_batching
-    runs = []  # consecutive layers that go into one PwSequence call
-    for l in layers:
-        if l["batch"] and runs and runs[-1][0]["batch"] and len(runs[-1]) < 32:
-            runs[-1].append(l)
+        l["class"] = 0 if args.no_batching else P.prom_pw_batch_class(args.batch, s_.hw, s_.hw, s_.cin, s_.cout)
+    BATCH_NAME = {1: "prom::pw_batch_kernel(prom::PwBatchArgs)", 2: "prom::pw_bigbatch_kernel(prom::PwBatchArgs)"}
+    runs = []  # layers that go into one PwSequence call
+    for cls in (2, 0, 1):
+        members = [l for l in layers if l["class"] == cls]
+        if cls == 0 or len(members) == 1:
+            runs += [[l] for l in members]
         else:
-            runs.append([l])
-    BATCH_NAME = "prom::pw_batch_kernel(prom::PwBatchArgs)"
+            runs += [members[i:i + 32] for i in range(0, len(members), 32)]
     groups = {}
+    run_names = []
     for r in runs:
-        name = BATCH_NAME if len(r) > 1 else kernel_name(r[0]["variant"])
+        name = BATCH_NAME[r[0]["class"]] if len(r) > 1 else kernel_name(r[0]["variant"])
+        run_names.append(name)
         g = groups.setdefault(name, {"bytes": 0, "launches": 0, "layers": []})
         g["bytes"] += sum(l["bytes"] for l in r)
         g["launches"] += 1
         g["layers"] += [l["shape"].name for l in r]
     dom_name = max(groups, key=lambda k: groups[k]["bytes"])
-    segments = []
-    for r in runs:
-        name = BATCH_NAME if len(r) > 1 else kernel_name(r[0]["variant"])
-        seq = P.PwSequence([(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"]) for l in r])
-        segments.append((name == dom_name, seq))
-    # merge neighbouring non-dominant segments into single host calls (not when batching is off:
-    # a multi-layer call would batch again)
-    merged, acc_layers = [], []
-    for (is_dom, seq), r in zip(segments, runs):
-        if is_dom or args.no_batching:
-            if acc_layers:
-                merged.append((False, P.PwSequence(acc_layers)))
-                acc_layers = []
-            merged.append((is_dom, seq))
-        else:
-            acc_layers += [(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"]) for l in r]
-    if acc_layers:
-        merged.append((False, P.PwSequence(acc_layers)))
-    segments = merged
+    segments = [(name == dom_name, P.PwSequence([(l["x"], l["wp"], l["shape"].cout, l["rq"], None, l["y"])
+                                                 for l in r])) for name, r in zip(run_names, runs)]
     log(f"[bench] {len(runs)} launches per step; dominant kernel: {dom_name} "
         f"({groups[dom_name]['launches']} launch(es), {groups[dom_name]['bytes'] / 1e6:.1f} MB per step)")
 

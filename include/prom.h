@@ -66,15 +66,15 @@ typedef struct {
 /* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default".
  * With tiles_per_wave or pixel_tiles given and row_waves == 0 the plain streaming kernel runs
  * (every wavefront on its own pixel groups, one chunk of 16*tiles_per_wave channels per
- * workgroup).  row_waves = 2 or 4 asks for the row-cooperative kernel: that many wavefronts of a
- * workgroup share a pixel group and write whole rows of 16*tiles_per_wave*row_waves channels
- * together; it needs tiles_per_wave in 1..6, pixel_tiles 0 or 1, cin % 16 == 0 and
- * cout % (16*tiles_per_wave*row_waves) == 0. */
+ * workgroup).  row_waves = 2, 3 or 4 asks for the row-cooperative kernel: that many wavefronts
+ * of a workgroup share a pixel group and write whole rows of 16*tiles_per_wave*row_waves
+ * channels together; it needs tiles_per_wave in 1..6, pixel_tiles 0 or 1 and
+ * cout % (16*tiles_per_wave*row_waves) == 0 (and, like the fast path in general, cin % 8 == 0). */
 typedef struct {
     int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..10)       */
     int32_t pixel_tiles;     /* PT: 16-pixel tiles a wavefront processes per iteration (1,2,4)*/
     int32_t workgroups;      /* workgroups launched per output-channel chunk (per row piece)  */
-    int32_t row_waves;       /* 0, 2 or 4: wavefronts per pixel group, see above              */
+    int32_t row_waves;       /* 0, 2, 3 or 4: wavefronts per pixel group, see above           */
 } prom_pw_plan_t;
 
 /* ---- ternary weight packing (host side, once per layer: the paper notes that weights are
@@ -186,6 +186,11 @@ int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_lay
 /* 1 if a layer of this shape (4-byte aligned pointers assumed) is small enough and regular
  * enough to join a batched launch of prom_pw_conv_sequence, 0 if not, negative on bad shapes. */
 int prom_pw_batchable(int n, int h, int w, int cin, int cout);
+
+/* Which shared launch prom_pw_conv_sequence would put a layer of this shape into (pointers assumed
+ * 4-byte aligned): 1 = the launch of small layers, 2 = the launch of large layers, 0 = none (the
+ * layer is launched alone); negative = error code.  Host only, launches nothing. */
+int prom_pw_batch_class(int n, int h, int w, int cin, int cout);
 
 /* The same layer computed by the other design that was evaluated: multiplication-free
  * accumulation on the vector ALU (sums of the input bytes whose weight is +1 / -1, paper

@@ -95,6 +95,8 @@ def load_library():
     lib.prom_quantize_dw_absmax.argtypes = [vp, ci, ctypes.c_float, vp, vp, vp]
     lib.prom_block_is_fused.restype = ci
     lib.prom_block_is_fused.argtypes = [ci] * 7
+    lib.prom_pw_batch_class.restype = ci
+    lib.prom_pw_batch_class.argtypes = [ci, ci, ci, ci, ci]
     lib.prom_pw_batchable.restype = ci
     lib.prom_pw_batchable.argtypes = [ci, ci, ci, ci, ci]
     lib.prom_copy_bytes.restype = ci
@@ -357,6 +359,14 @@ def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:
            "prom_pw_plan_query")
     return {"tiles_per_wave": p.tiles_per_wave, "pixel_tiles": p.pixel_tiles,
             "workgroups": p.workgroups, "row_waves": p.row_waves, "load_bytes": lb.value}
+
+
+def prom_pw_batch_class(n: int, h: int, w: int, cin: int, cout: int) -> int:
+    """0: launched alone, 1: joins the launch of small layers, 2: the launch of large layers."""
+    rc = load_library().prom_pw_batch_class(n, h, w, cin, cout)
+    if rc < 0:
+        raise PromError(rc, "prom_pw_batch_class")
+    return rc
 
 
 def prom_pw_batchable(n: int, h: int, w: int, cin: int, cout: int) -> bool:

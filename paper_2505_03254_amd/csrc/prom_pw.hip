@@ -94,18 +94,11 @@ __global__ __launch_bounds__(256) void pw_generic_kernel(const PwArgs a)
 // Several independent layers in one launch: workgroups [start[i], start[i+1]) (both multiples
 // of 8) run layer i with the plan NT = 4, PT = 1 and 16-byte activation loads.  The launch,
 // prologue and write-back latencies of one layer overlap with the streaming of the others.
-constexpr int kMaxBatch = 32;
 constexpr int kBatchNT = 4;
 #ifndef PROM_BATCH_DEPTH
 #define PROM_BATCH_DEPTH 4
 #endif
 constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flight per wavefront
-struct PwBatchArgs {
-    int count;
-    int start[kMaxBatch + 1];
-    PwArgs layer[kMaxBatch];
-};
-
 // Tiles per wavefront of a batch member: kBatchNT, or half of it for a layer with many k
 // steps, whose decoded fragments would otherwise set the LDS size (and with it the number of
 // resident workgroups) of the whole launch.
@@ -186,9 +179,9 @@ static KernelFn select_kernel(int nt, int pt, int xmode, bool ks1, bool fullw, b
 
 // Workgroups of `fn` that fit on one CU with `lds` bytes of dynamic LDS; also raises the
 // kernel's dynamic-LDS limit once.  Cached per (kernel, LDS size); 0 on error.
-static int resident_workgroups(KernelFn fn, size_t lds)
+static int resident_workgroups(KernelFn fn, size_t lds, int threads = 256)
 {
-    struct Entry { KernelFn fn; size_t lds; int occ; };
+    struct Entry { KernelFn fn; size_t lds; int threads; int occ; };
     static std::mutex mu;
     static std::vector<Entry> cache;
     std::lock_guard<std::mutex> lock(mu);
@@ -196,7 +189,7 @@ static int resident_workgroups(KernelFn fn, size_t lds)
     for (const Entry &e : cache) {
         if (e.fn == fn) {
             seen_fn = true;
-            if (e.lds == lds) return e.occ;
+            if (e.lds == lds && e.threads == threads) return e.occ;
         }
     }
     if (!seen_fn) {
@@ -209,13 +202,13 @@ static int resident_workgroups(KernelFn fn, size_t lds)
     }
     int occ = 0;
     const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(fn),
-                                                                      256, lds);
+                                                                      threads, lds);
     if (e != hipSuccess || occ < 1) {
         last_hip_error() = e;
         (void)hipGetLastError();
         return 0;
     }
-    cache.push_back({fn, lds, occ});
+    cache.push_back({fn, lds, threads, occ});
     return occ;
 }
 
@@ -234,8 +227,8 @@ static int max_pt_for(int nt) { return nt <= 2 ? 4 : (nt <= 6 ? 2 : 1); }
 // does not fit the LDS budget.
 static bool plan_rows(int cin, int cout, int ks, int *cw_out, int *nt_out)
 {
-    if (cin % 16 != 0) return false;
-    for (int cw = 4; cw >= 2; cw -= 2) {
+    if (cin % 8 != 0) return false;
+    for (int cw = 4; cw >= 2; --cw) {
         if (cout % (16 * cw) != 0) continue;
         const int nt = cout / (16 * cw);
         if (nt < 1 || nt > kRowsMaxNT) continue;
@@ -251,9 +244,11 @@ struct PwLaunch {
     PwArgs a;
     KernelFn fn;
     int nt, pt, xmode, grid;
+    int threads;  // workgroup size: 256, or 64*cw*(4/cw) for the row-cooperative kernel
     size_t lds;
     bool fast;
     bool rows;  // row-cooperative kernel (a.cw != 0)
+    int big_body;  // body of pw_bigbatch_kernel that runs this plan, or -1
     int mode;
 };
 
@@ -351,14 +346,17 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     L.rows = false;
     if (plan && plan->row_waves) {
         const int cw = plan->row_waves, rnt = plan->tiles_per_wave;
-        if (!fast || (cw != 2 && cw != 4) || rnt < 1 || rnt > kRowsMaxNT || plan->pixel_tiles > 1) return PROM_EINVAL;
-        if (cin % 16 != 0 || cout % (16 * rnt * cw) != 0) return PROM_EINVAL;
+        if (!fast || cw < 2 || cw > 4 || rnt < 1 || rnt > kRowsMaxNT || plan->pixel_tiles > 1) return PROM_EINVAL;
+        if (cout % (16 * rnt * cw) != 0) return PROM_EINVAL;
         if (lds_bytes_rows(rnt, cw, a.KS) > (size_t)kLdsMax) return PROM_EINVAL;
         L.rows = true;
         a.cw = cw;
         nt = rnt;
         pt = 1;
-    } else if (fast && !(plan && (plan->tiles_per_wave || plan->pixel_tiles)) && (n_tiles + nt - 1) / nt > 1) {
+    } else if (fast && !(plan && (plan->tiles_per_wave || plan->pixel_tiles)) &&
+               ((n_tiles + nt - 1) / nt > 1 || nt >= 8)) {
+        // also instead of one chunk of 8 or more tiles, whose kernel needs so many registers that
+        // only one wavefront per SIMD is resident
         int cw = 0, rnt = 0;
         if (plan_rows(cin, cout, a.KS, &cw, &rnt)) {
             L.rows = true;
@@ -372,19 +370,21 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     L.fast = fast;
     L.mode = mode;
     L.xmode = !fast ? 1 : (cin % 16 == 0 ? 16 : 8);
+    L.threads = L.rows ? rows_threads(a.cw) : 256;
     if (L.rows) {
         L.lds = lds_bytes_rows(nt, a.cw, a.KS);
-        L.fn = pw_rows_select(nt, a.KS == 1);
+        L.fn = pw_rows_select(nt, a.KS == 1, L.xmode);
     } else {
         L.lds = fast ? lds_bytes_fast(nt, a.KS) : lds_bytes_generic(nt, a.KS);
         L.fn = select_kernel(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, fast, mode);
     }
     if (!L.fn) return PROM_EINVAL;
+    L.big_body = fast ? pw_big_body_id(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, a.cw) : -1;
 
     a.n_chunks = L.rows ? cout / (16 * nt * a.cw) : (n_tiles + nt - 1) / nt;
     a.units = (int)((M + 16 * pt - 1) / (16 * pt));
     // a workgroup's 4 wavefronts take 4 groups per round (4 / cw groups in the row-cooperative kernel)
-    const long long wg_units = L.rows ? (a.units + 4 / a.cw - 1) / (4 / a.cw) : (a.units + 3) / 4;
+    const long long wg_units = L.rows ? (a.units + rows_groups(a.cw) - 1) / rows_groups(a.cw) : (a.units + 3) / 4;
     long long wgs;
     if (plan && plan->workgroups) {
         if (plan->workgroups < 1) return PROM_EINVAL;
@@ -394,7 +394,7 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
         // One resident round of workgroups, every wavefront with the same number of groups.
         int occ = 2;
         if (!shape_only) {
-            occ = resident_workgroups(L.fn, L.lds);
+            occ = resident_workgroups(L.fn, L.lds, L.threads);
             if (occ < 1) return PROM_EHIP;
         }
         long long target = ((long long)kNumCU * occ) / a.n_chunks;
@@ -412,11 +412,11 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
 
 static int pw_launch(const PwLaunch &L, hipStream_t st)
 {
-    if (L.lds > 64 * 1024 && resident_workgroups(L.fn, L.lds) < 1) return PROM_EHIP;
+    if (L.lds > 64 * 1024 && resident_workgroups(L.fn, L.lds, L.threads) < 1) return PROM_EHIP;
     clear_hip_error();
     PwArgs args = L.a;
     void *kargs[] = {&args};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(L.fn), dim3(L.grid), dim3(256), kargs,
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(L.fn), dim3(L.grid), dim3(L.threads), kargs,
                                          L.lds, st);
     if (e != hipSuccess) {
         last_hip_error() = e;
@@ -557,11 +557,67 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         if (l > lds) lds = l;
     }
     b.start[count] = start;
-    if (resident_workgroups(reinterpret_cast<KernelFn>(&pw_batch_kernel), lds) < 1) return PROM_EHIP;
+    if (resident_workgroups(reinterpret_cast<KernelFn>(static_cast<PwBatchFn>(&pw_batch_kernel)), lds) < 1) return PROM_EHIP;
     clear_hip_error();
     void *kargs[] = {&b};
     const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&pw_batch_kernel), dim3(start), dim3(256),
                                          kargs, lds, st);
+    if (e != hipSuccess) {
+        last_hip_error() = e;
+        (void)hipGetLastError();
+        return PROM_EHIP;
+    }
+    return check_launch();
+}
+
+// A large layer can join the launch of large layers if pw_bigbatch_kernel carries the body of its plan.
+constexpr long long kBigBytesPerWg = 768LL << 10;  // measured best of 128 KB .. 2 MB on the MobileNetV2 head
+static bool big_batchable(const PwLaunch &L)
+{
+    return L.fast && L.mode == 0 && L.big_body >= 0 && !batchable(L) && L.lds <= (size_t)kLdsBudget;
+}
+
+static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
+{
+    static thread_local PwBatchArgs b;
+    b.count = count;
+    size_t lds = 0;
+    int start = 0;
+    long long total_work = 0, done_work = 0;
+    for (int i = 0; i < count; ++i) {
+        const PwLaunch &L = *members[i];
+        const int width = 16 * L.nt * (L.rows ? L.a.cw : 1);
+        total_work += (long long)L.a.M * (L.a.K + width) * L.a.n_chunks;
+    }
+    for (int i = 0; i < count; ++i) {
+        const PwLaunch &L = *members[i];
+        PwArgs a = L.a;  // keeps its own plan (tiles, pixel tiles, chunks); only the grid changes
+        const int width = 16 * L.nt * (L.rows ? a.cw : 1);
+        const long long work = (long long)a.M * (a.K + width);
+        const int per_step = L.rows ? rows_groups(a.cw) : 4;
+        const long long wg_units = (a.units + per_step - 1) / per_step;
+        const long long per_wg = done_work * 10 < total_work * 8   ? kBigBytesPerWg
+                                 : done_work * 20 < total_work * 19 ? kBigBytesPerWg / 2
+                                                                    : kBigBytesPerWg / 4;
+        done_work += work * a.n_chunks;
+        long long wgs = (work + per_wg - 1) / per_wg;
+        if (wgs < 1) wgs = 1;
+        if (wgs > wg_units) wgs = wg_units;
+        a.wg_per_chunk = (int)wgs;
+        const int nblk = (int)((wgs * a.n_chunks + 7) / 8 * 8);
+        b.layer[i] = a;
+        b.body[i] = (unsigned char)L.big_body;
+        b.start[i] = start;
+        start += nblk;
+        const size_t l = pw_big_body_lds(L.big_body, a);
+        if (l > lds) lds = l;
+    }
+    b.start[count] = start;
+    const PwBatchFn fn = pw_bigbatch_fn();
+    if (resident_workgroups(reinterpret_cast<KernelFn>(fn), lds) < 1) return PROM_EHIP;
+    clear_hip_error();
+    void *kargs[] = {&b};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(fn), dim3(start), dim3(256), kargs, lds, st);
     if (e != hipSuccess) {
         last_hip_error() = e;
         (void)hipGetLastError();
@@ -581,6 +637,15 @@ extern "C" int prom_pw_batchable(int n, int h, int w, int cin, int cout)
     return prom::batchable(L) ? 1 : 0;
 }
 
+extern "C" int prom_pw_batch_class(int n, int h, int w, int cin, int cout)
+{
+    prom::PwLaunch L;
+    const int rc = prom::pw_prepare(nullptr, n, h, w, cin, nullptr, cout, nullptr, nullptr, nullptr,
+                                    nullptr, nullptr, 0, true, L);
+    if (rc != PROM_OK) return rc;
+    return prom::batchable(L) ? 1 : (prom::big_batchable(L) ? 2 : 0);
+}
+
 extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, int *bad_layer, void *stream)
 {
     using namespace prom;
@@ -597,34 +662,48 @@ extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, i
             return rc;
         }
     }
-    // Results are those of running the layers one after the other.  Small layers that do not
-    // touch each other's data wait in a pending batch, which becomes one launch where its layers
-    // run concurrently.  A layer that conflicts with a pending one forces the batch out first; a
-    // larger layer that does not may overtake it.
+    // Results are those of running the layers one after the other.  Layers that do not touch each
+    // other's data wait in one of two pending batches -- small layers (pw_batch_kernel) and large
+    // layers whose plan pw_bigbatch_kernel carries -- and each batch becomes one launch where its
+    // layers run concurrently.  A layer that conflicts with a pending one forces both batches out
+    // first; any other layer that fits no batch is launched at once and may overtake them.
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const PwLaunch *pending[kMaxBatch];
-    int npending = 0;
-    int first_pending = 0;
-    auto flush = [&]() -> int {
+    const PwLaunch *pending[2][kMaxBatch];
+    int npending[2] = {0, 0};
+    int first_pending[2] = {0, 0};
+    auto flush_one = [&](int c) -> int {
         int rc = PROM_OK;
-        if (npending == 1)
-            rc = pw_launch(*pending[0], st);
-        else if (npending > 1)
-            rc = launch_batch(pending, npending, st);
-        npending = 0;
-        if (rc != PROM_OK && bad_layer) *bad_layer = first_pending;
+        if (npending[c] == 1)
+            rc = pw_launch(*pending[c][0], st);
+        else if (npending[c] > 1)
+            rc = c == 0 ? launch_batch(pending[c], npending[c], st) : launch_big(pending[c], npending[c], st);
+        npending[c] = 0;
+        if (rc != PROM_OK && bad_layer) *bad_layer = first_pending[c];
         return rc;
     };
+    auto flush_all = [&]() -> int {
+        // the large layers first: they were written first in the usual order of a network, and the
+        // small batch then fills the chip while they drain
+        const int rc = flush_one(1);
+        if (rc != PROM_OK) return rc;
+        return flush_one(0);
+    };
     for (int i = 0; i < count; ++i) {
-        bool clash = npending == kMaxBatch && batchable(plans[i]);
-        for (int k = 0; k < npending && !clash; ++k) clash = conflicts(pending[k]->a, plans[i].a);
+        const int cls = batchable(plans[i]) ? 0 : (big_batchable(plans[i]) ? 1 : -1);
+        bool clash = false;
+        for (int c = 0; c < 2 && !clash; ++c)
+            for (int k = 0; k < npending[c] && !clash; ++k) clash = conflicts(pending[c][k]->a, plans[i].a);
         if (clash) {
-            const int rc = flush();
+            const int rc = flush_all();
             if (rc != PROM_OK) return rc;
         }
-        if (batchable(plans[i])) {
-            if (npending == 0) first_pending = i;
-            pending[npending++] = &plans[i];
+        if (cls >= 0) {
+            if (npending[cls] == kMaxBatch) {
+                const int rc = flush_one(cls);
+                if (rc != PROM_OK) return rc;
+            }
+            if (npending[cls] == 0) first_pending[cls] = i;
+            pending[cls][npending[cls]++] = &plans[i];
         } else {
             const int rc = pw_launch(plans[i], st);
             if (rc != PROM_OK) {
@@ -633,7 +712,7 @@ extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, i
             }
         }
     }
-    return flush();
+    return flush_all();
 }
 
 extern "C" int prom_copy_bytes(const void *src, void *dst, size_t nbytes, void *stream)

@@ -7,10 +7,10 @@
 // traffic is the same, but a store instruction then touches twice as many 128-byte lines on its
 // way through the vector L1, and that path is what limits a write-heavy layer.
 //
-// Here the CW = 2 or 4 chunks of one pixel group sit on the wavefronts of ONE workgroup
-// (G = 4 / CW pixel groups per workgroup step).  Every wavefront computes its 16 pixels x 16*NT
+// Here the CW = 2, 3 or 4 chunks of one pixel group sit on the wavefronts of ONE workgroup
+// (G = 4 / CW pixel groups per workgroup step: 2, 1, 1; the workgroup has 64*CW*G threads).  Every wavefront computes its 16 pixels x 16*NT
 // channels as before and puts them into a shared LDS tile [16*G pixels][16*NT*CW bytes]; after a
-// workgroup barrier all 256 lanes write the tile as whole rows, in 16-byte pieces that follow each
+// workgroup barrier all lanes of the workgroup write the tile as whole rows, in 16-byte pieces that follow each
 // other in memory.  The tile is double buffered, so one barrier per step suffices: a wavefront
 // can reach the writes of step s+2 only through the barrier of step s+1, which every wavefront
 // passes after its reads of step s have returned.  The activations of a pixel group are loaded by
@@ -23,27 +23,31 @@
 
 namespace prom {
 
-// LDS bytes: fragments and parameters of the CW*NT tiles, two output tiles of 1024*NT bytes.
+// LDS bytes: fragments and parameters of the CW*NT tiles, two output tiles of
+// 16*G pixels x 16*NT*CW bytes.
+__host__ __device__ constexpr int rows_groups(int cw) { return 4 / cw; }
+__host__ __device__ constexpr int rows_threads(int cw) { return 64 * cw * rows_groups(cw); }
 __host__ __device__ constexpr size_t lds_bytes_rows(int nt, int cw, int ks)
 {
-    return (size_t)cw * nt * ks * 1024 + (size_t)cw * nt * 256 + (size_t)2 * 1024 * nt;
+    return (size_t)cw * nt * ks * 1024 + (size_t)cw * nt * 256 + (size_t)2 * 256 * nt * cw * rows_groups(cw);
 }
 
 // Fragments frag[CW*NT][KS][64] and parameters lpar[CW*NT][4 g][4 r] of a super-chunk; tile slot
 // cw*NT + t holds the channels base + 16*NT*cw + chan_of<NT>(t, ., .).  Ends with the barrier.
 template <int NT>
-__device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, int CW, v4i *frag, v4i *lpar)
+__device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, int CW, int nthr, v4i *frag,
+                                                   v4i *lpar)
 {
     const int tid = threadIdx.x;
     const int KS = a.KS, Nc = a.Nc;
     const int NTT = CW * NT;
     const int nfrag = NTT * KS * 64;
     constexpr int U = 8;  // words in flight per thread
-    for (int base = 0; base < nfrag; base += 256 * U) {
+    for (int base = 0; base < nfrag; base += nthr * U) {
         uint32_t word[U];
 #pragma unroll
         for (int q = 0; q < U; ++q) {
-            const int idx = base + q * 256 + tid;
+            const int idx = base + q * nthr + tid;
             const int tk = idx >> 6;
             const int ks = tk % KS;
             const int tt = tk / KS;
@@ -58,11 +62,11 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
         }
 #pragma unroll
         for (int q = 0; q < U; ++q) {
-            const int idx = base + q * 256 + tid;
+            const int idx = base + q * nthr + tid;
             if (idx < nfrag) frag[idx] = decode_word(word[q]);
         }
     }
-    for (int s = tid; s < NTT * 16; s += 256) {
+    for (int s = tid; s < NTT * 16; s += nthr) {
         const int tt = s >> 4;
         const int cw = tt / NT;
         const int t = tt - cw * NT;
@@ -79,12 +83,13 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
     __syncthreads();
 }
 
-// Requirements (checked by the host): cin % 16 == 0, cout % (16*NT*CW) == 0, 4-byte aligned
-// tensors below 2^31 bytes, CW in {2, 4} (a.cw), a.units counts groups of 16 pixels.
-template <int NT, bool KS1, int D = 4>
+// Requirements (checked by the host): cin % 16 == 0 (XMODE 16) or cin % 8 == 0 (XMODE 8, two
+// 8-byte loads per fragment), cout % (16*NT*CW) == 0, 4-byte aligned tensors below 2^31 bytes,
+// CW in {2, 3, 4} (a.cw), 64*CW*G threads per workgroup, a.units counts groups of 16 pixels.
+template <int NT, bool KS1, int XMODE = 16, int D = 4>
 __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
-    constexpr int NI = (NT + 3) / 4;  // 16-byte pieces per lane per step: 64*NT pieces, 256 lanes
+    constexpr int NI = (NT + 3) / 4;  // 16-byte pieces per lane per step: 16*G*CW*NT pieces, 64*G*CW lanes
     const int KS = KS1 ? 1 : a.KS;
     const int CW = a.cw, G = 4 / CW, NTT = CW * NT;
     v4i *frag = reinterpret_cast<v4i *>(lds_raw);
@@ -99,7 +104,11 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
     const int sc = lid % a.n_chunks;
     const int wg = lid / a.n_chunks;
     if (wg >= a.wg_per_chunk) return;  // the whole workgroup leaves: no barrier is missed
-    const int cwi = wave & (CW - 1);   // this wavefront's chunk within the super-chunk
+    // a workgroup launched with more wavefronts than CW*G (a batch of layers shares one workgroup
+    // size): the spare ones leave now; a finished wavefront no longer counts at the barriers
+    if (wave >= CW * G) return;
+    const int nthr = 64 * CW * G;
+    const int cwi = wave % CW;         // this wavefront's chunk within the super-chunk
     const int gsub = wave / CW;        // and its pixel group within the workgroup step
     const int cbase = sc * NTT * 16;
     const int RWs = NTT * 16;          // bytes of a tile row
@@ -119,7 +128,13 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
     unsigned xoff = min((unsigned)kOobOffset, (unsigned)((wg * G + gsub) * 16 + j) * (unsigned)K + 16u * g);
     const unsigned xstep = (unsigned)a.wg_per_chunk * (unsigned)(G * 16) * (unsigned)K;
     auto load_group = [&](v4i &b) {
-        b = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xoff, 64 * lk, 0);
+        if constexpr (XMODE == 16) {
+            b = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xoff, 64 * lk, 0);
+        } else {
+            const v2i lo2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)xoff, 64 * lk, 0);
+            const v2i hi2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(xoff + 8), 64 * lk, 0);
+            b = v4i{lo2[0], lo2[1], hi2[0], hi2[1]};
+        }
         if (KS1 || ++lk == KS) {
             lk = 0;
             xoff = min(xoff + xstep, (unsigned)kOobOffset);
@@ -129,7 +144,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
 
-    stage_weights_rows<NT>(a, cbase, CW, frag, lpar);
+    stage_weights_rows<NT>(a, cbase, CW, nthr, frag, lpar);
 
     v4i par[NT][4];
     const v4i *lpg = lpar + cwi * NT * 16 + g * 4;
@@ -155,13 +170,14 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
 
     // where this lane puts its outputs in the tile: row gsub*16 + j, this wavefront's columns
     const int wbase = (gsub * 16 + j) * RWs + cwi * NT * 16;
-    // the pieces this lane writes to memory: piece q = 256*i + tid of 64*NT, row-major in the tile
+    // the pieces this lane writes to memory: piece q = nthr*i + tid of 16*G*NTT, row-major in the tile
+    const int tile_bytes = 256 * G * NTT;
     int goff[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int q = i * 256 + tid;
+        const int q = i * nthr + tid;
         const int row = q / NTT;
-        goff[i] = q < 64 * NT ? row * Nc + 16 * (q - row * NTT) : kOobOffset;
+        goff[i] = q < 16 * G * NTT ? row * Nc + 16 * (q - row * NTT) : kOobOffset;
     }
     // byte offset of (first pixel of the workgroup step, super-chunk base)
     unsigned ytile = min((unsigned)kOobOffset, (unsigned)(wg * G * 16) * (unsigned)Nc + (unsigned)cbase);
@@ -198,7 +214,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
             if constexpr (REFILL) load_group(slot);
             if (KS1 || ++ck == KS) {
                 ck = 0;
-                unsigned char *tile = tiles + buf * (1024 * NT);
+                unsigned char *tile = tiles + buf * tile_bytes;
 #pragma unroll
                 for (int t0 = 0; t0 < NT; t0 += grp_size<NT>(t0)) {
                     const int S = grp_size<NT>(t0);
@@ -242,7 +258,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
                 __syncthreads();
 #pragma unroll
                 for (int i = 0; i < NI; ++i) {
-                    const v4i v = *reinterpret_cast<const v4i *>(tile + (i * 256 + tid) * 16);
+                    const v4i v = *reinterpret_cast<const v4i *>(tile + (i * nthr + tid) * 16);
                     // tile offset in the vector offset: see the store of the streaming kernel
                     __builtin_amdgcn_raw_buffer_store_b128(
                         v, ry, (int)min((unsigned)goff[i] + ytile, (unsigned)kOobOffset), 0, 0);
@@ -276,15 +292,33 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
     }
 }
 
-template <int NT, bool KS1>
+template <int NT, bool KS1, int XMODE>
 __global__ __launch_bounds__(256, (NT <= 7 ? 2 : 1)) void pw_rows_kernel(const PwArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    pw_rows_body<NT, KS1>(a, logical_block_id(), lds_raw);
+    pw_rows_body<NT, KS1, XMODE>(a, logical_block_id(), lds_raw);
 }
 
-// Defined in prom_pw_rows.hip: the instantiation for NT in 1..6, or nullptr.
-PwKernelFn pw_rows_select(int nt, bool ks1);
+// ---- several independent layers in one launch -------------------------------------------------
+// Workgroups [start[i], start[i+1]) (both multiples of 8) run layer i; body[i] selects the kernel
+// body (pw_bigbatch_kernel only).
+constexpr int kMaxBatch = 32;
+struct PwBatchArgs {
+    int count;
+    int start[kMaxBatch + 1];
+    unsigned char body[kMaxBatch];
+    PwArgs layer[kMaxBatch];
+};
+using PwBatchFn = void (*)(PwBatchArgs);
+
+// Bodies pw_bigbatch_kernel carries (the plans the library picks for the large layers at the head
+// of MobileNetV2); -1 if this plan is not among them.  Defined in prom_pw_big.hip.
+int pw_big_body_id(int nt, int pt, int xmode, bool ks1, bool fullw, int row_waves);
+PwBatchFn pw_bigbatch_fn();
+size_t pw_big_body_lds(int body, const PwArgs &a);
+
+// Defined in prom_pw_rows.hip: the instantiation for NT in 1..6 and load width 16 or 8, or nullptr.
+PwKernelFn pw_rows_select(int nt, bool ks1, int xmode);
 constexpr int kRowsMaxNT = 6;
 
 }  // namespace prom

@@ -103,14 +103,15 @@ def test_every_tile_plan(P, nt):
                 assert_same(run_pw(P, L, plan=plan), want, f"nt={nt} pt={pt} wgs={wgs} cin={cin}")
 
 
-@pytest.mark.parametrize("cw", [2, 4])
+@pytest.mark.parametrize("cw", [2, 3, 4])
 def test_row_cooperative_plans(P, cw):
     """The row-cooperative kernel (2 or 4 wavefronts of a workgroup share a pixel group and write
     whole rows): every tile count, one and several k steps, ragged pixel counts down to a single
     pixel, few and many workgroups, with and without the skip connection."""
     for nt in range(1, 7):
         cout = 16 * nt * cw
-        for (n, h, w, cin) in ((2, 9, 13, 32), (1, 7, 7, 160), (1, 1, 1, 64), (3, 5, 11, 16)):
+        for (n, h, w, cin) in ((2, 9, 13, 32), (1, 7, 7, 160), (1, 1, 1, 64), (3, 5, 11, 16), (2, 6, 9, 24),
+                               (1, 8, 5, 72)):
             L = make_pw_layer(5000 + 10 * nt + cw + cin, n, h, w, cin, cout, signed_x=True,
                               act_window=(-100, 100), with_residual=(cin == 32))
             want = oracle_pw(oracle, L)
@@ -123,11 +124,11 @@ def test_row_cooperative_plans(P, cw):
     assert_same(run_pw(P, L, plan=P.PwPlan(2, 1, 0, cw)), oracle_pw(oracle, L), f"rows cw={cw} two pieces")
     # plans that cannot be realised
     L = make_pw_layer(5950, 1, 4, 4, 32, 96)
-    for bad in (P.PwPlan(4, 0, 0, cw), P.PwPlan(7, 0, 0, cw), P.PwPlan(3, 2, 0, cw), P.PwPlan(3, 0, 0, 3)):
+    for bad in (P.PwPlan(5, 0, 0, cw), P.PwPlan(7, 0, 0, cw), P.PwPlan(1, 2, 0, cw), P.PwPlan(1, 0, 0, 5)):
         with pytest.raises(P.PromError) as e:
             run_pw(P, L, plan=bad)
         assert e.value.code == -1
-    L = make_pw_layer(5960, 1, 4, 4, 24, 16 * cw)  # cin % 16 != 0
+    L = make_pw_layer(5960, 1, 4, 4, 20, 16 * cw)  # cin % 8 != 0: not a fast-path shape
     with pytest.raises(P.PromError) as e:
         run_pw(P, L, plan=P.PwPlan(1, 0, 0, cw))
     assert e.value.code == -1
@@ -136,9 +137,9 @@ def test_row_cooperative_plans(P, cw):
 def test_library_picks_row_cooperative_kernel_for_wide_rows(P):
     """A 32->192 and a 64->384 layer (rows wider than one wavefront's chunk, whole row = 4
     wavefronts) take the row-cooperative kernel by default; results as the oracle's."""
-    for cin, cout in ((32, 192), (64, 384), (32, 256)):
+    for cin, cout in ((32, 192), (64, 384), (32, 256), (24, 288)):
         q = P.prom_pw_plan_query(2, 28, 28, cin, cout)
-        assert q["row_waves"] in (2, 4) and 16 * q["tiles_per_wave"] * q["row_waves"] == cout, q
+        assert q["row_waves"] in (2, 3, 4) and 16 * q["tiles_per_wave"] * q["row_waves"] == cout, q
         L = make_pw_layer(5980 + cin, 2, 28, 28, cin, cout)
         assert_same(run_pw(P, L), oracle_pw(oracle, L), f"default plan {cin}->{cout}")
     assert P.prom_pw_plan_query(2, 28, 28, 16, 96)["row_waves"] == 0  # one chunk: plain kernel
@@ -285,3 +286,40 @@ def test_pixel_tile_plans_agree_on_a_full_size_layer(P):
             torch.cuda.synchronize()
             bad = int((y != want).sum())
             assert bad == 0, f"plan {plan}, run {run}: {bad} outputs differ"
+
+
+def test_sequence_puts_large_layers_into_one_launch(P):
+    """Large independent layers whose plan the large-layer batch kernel carries (the head of
+    MobileNetV2 at batch 64: 32->16, 16->96, 24->144 and 96->24) go through prom_pw_conv_sequence
+    together with small ones; every output against the oracle, and a second call where the layers
+    depend on each other (the output of one is the input of the next), which must not be batched."""
+    torch = torch_cuda()
+    shapes = [(112, 32, 16), (112, 16, 96), (56, 24, 144), (56, 96, 24), (14, 64, 384), (7, 160, 960)]
+    n = 64
+    classes = [P.prom_pw_batch_class(n, hw, hw, cin, cout) for hw, cin, cout in shapes]
+    assert classes[:4] == [2, 2, 2, 2] and classes[4:] == [1, 1], classes
+    layers, wants = [], []
+    for i, (hw, cin, cout) in enumerate(shapes):
+        L = make_pw_layer(9100 + i, n, hw, hw, cin, cout, signed_x=True, act_window=(-128, 127))
+        y = torch.full((n, hw, hw, cout), -99, dtype=torch.int8, device="cuda")
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, requant_dev(P, L), None, y))
+        wants.append(dev(oracle_pw(oracle, L)))
+    for run in range(3):
+        for l in layers:
+            l[5].fill_(-99)
+        P.PwSequence(layers).run()
+        torch.cuda.synchronize()
+        for (hw, cin, cout), l, want in zip(shapes, layers, wants):
+            assert int((l[5] != want).sum()) == 0, f"run {run}: {cin}->{cout} @ {hw}"
+    # a chain 32 -> 16 -> 96 at 112x112: the second layer reads what the first writes
+    n = 48
+    A = make_pw_layer(9200, n, 112, 112, 32, 16, signed_x=True, act_window=(-128, 127), shift_range=(2, 3))
+    Bq = make_pw_layer(9201, n, 112, 112, 16, 96, act_window=(-128, 127), shift_range=(1, 2), make_x=False)
+    mid = torch.full((n, 112, 112, 16), -99, dtype=torch.int8, device="cuda")
+    out = torch.full((n, 112, 112, 96), -99, dtype=torch.int8, device="cuda")
+    P.PwSequence([(dev(A.x), dev(P.prom_pack_ternary(A.weight)), 16, requant_dev(P, A), None, mid),
+                  (mid, dev(P.prom_pack_ternary(Bq.weight)), 96, requant_dev(P, Bq), None, out)]).run()
+    torch.cuda.synchronize()
+    m = oracle.pw_conv(A.x, A.weight, A.bias, A.mult, A.shift, -128, 127)
+    want = oracle.pw_conv(m, Bq.weight, Bq.bias, Bq.mult, Bq.shift, -128, 127)
+    assert_same(out.cpu().numpy(), want, "dependent large layers")
