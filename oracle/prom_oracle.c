@@ -28,6 +28,19 @@
  * Preconditions: |bias| <= 2^30, 0 <= shift <= 31, 0 < mult < 2^31, so every
  * intermediate fits in int64.
  *
+ * PReLU variant (the *_prelu functions; the paper's MobileNetV2 and RegNetX models replace
+ * ReLU6 / ReLU by PReLU, Section 4 "Experimental Setup"; PReLU itself is
+ * f(z) = z for z >= 0 and a_c * z for z < 0 with one learned slope a_c per channel).  The
+ * real pre-activation is z = sigma_c * s with sigma_c > 0, so its sign is the sign of s, and
+ * the slope folds into a second multiplier mult_neg[c] ~ a_c * mult[c] (same shift, any
+ * int32 value, a slope may be negative):
+ *     s = acc + bias[c]
+ *     m = mult[c] if s >= 0 else mult_neg[c]
+ *     q = floor( (s*m + 2^(30+shift[c])) / 2^(31+shift[c]) )
+ *     y = clamp as above (+ residual as above)
+ * Integer form again this build's contract (parity unpinned by the paper; pinned in the tests
+ * against the plain requantisation where the two must agree, and against a float PReLU).
+ *
  * Loops are plain and in definition order.  The only parallelism is an OpenMP
  * "parallel for" over pixels (each pixel's outputs are independent).
  */
@@ -60,6 +73,30 @@ static int8_t finish(int64_t acc, int32_t bias, int32_t mult, int32_t shift,
 {
     int64_t s = acc + (int64_t)bias;
     int64_t q = oracle_requant(s, mult, shift);
+    if (q < act_min) q = act_min;
+    if (q > act_max) q = act_max;
+    if (has_res) {
+        q += (int64_t)res;
+        if (q < -128) q = -128;
+        if (q > 127) q = 127;
+    }
+    return (int8_t)q;
+}
+
+/* Requantise s with the multiplier chosen by its sign (PReLU). */
+int64_t oracle_requant_prelu(int64_t s, int32_t mult, int32_t mult_neg, int32_t shift)
+{
+    int64_t m = (s >= 0) ? (int64_t)mult : (int64_t)mult_neg;
+    int64_t num = s * m + ((int64_t)1 << (30 + shift));
+    int64_t den = (int64_t)1 << (31 + shift);
+    return floor_div_pos(num, den);
+}
+
+static int8_t finish_prelu(int64_t acc, int32_t bias, int32_t mult, int32_t mult_neg, int32_t shift,
+                           int32_t act_min, int32_t act_max, int has_res, int8_t res)
+{
+    int64_t s = acc + (int64_t)bias;
+    int64_t q = oracle_requant_prelu(s, mult, mult_neg, shift);
     if (q < act_min) q = act_min;
     if (q > act_max) q = act_max;
     if (has_res) {
@@ -138,6 +175,37 @@ int oracle_pw_conv(const int8_t *x, int n, int h, int wd, int cin,
     return 0;
 }
 
+/* Pointwise 1x1 conv with the PReLU requantisation. */
+int oracle_pw_conv_prelu(const int8_t *x, int n, int h, int wd, int cin,
+                         const int8_t *w /* [cout][cin], values in {-1,0,1} */, int cout,
+                         const int32_t *bias, const int32_t *mult, const int32_t *mult_neg,
+                         const int32_t *shift, int32_t act_min, int32_t act_max,
+                         const int8_t *residual /* [n][h][w][cout] or NULL */,
+                         int8_t *y /* [n][h][w][cout] */)
+{
+    if (!x || !w || !bias || !mult || !mult_neg || !shift || !y) return -1;
+    if (n <= 0 || h <= 0 || wd <= 0 || cin <= 0 || cout <= 0) return -1;
+    for (int64_t i = 0; i < (int64_t)cout * cin; ++i)
+        if (w[i] < -1 || w[i] > 1) return -2;
+    int64_t m_pixels = (int64_t)n * h * wd;
+    int64_t m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < m_pixels; ++m) {
+        for (int co = 0; co < cout; ++co) {
+            int64_t acc = 0;
+            for (int k = 0; k < cin; ++k) {
+                int8_t wk = w[(int64_t)co * cin + k];
+                if (wk == 1) acc += (int64_t)x[m * cin + k];
+                else if (wk == -1) acc -= (int64_t)x[m * cin + k];
+            }
+            y[m * cout + co] = finish_prelu(acc, bias[co], mult[co], mult_neg[co], shift[co],
+                                            act_min, act_max, residual != NULL,
+                                            residual ? residual[m * cout + co] : 0);
+        }
+    }
+    return 0;
+}
+
 /* Depthwise 3x3 conv, pad 1, stride 1 or 2, NHWC, weights [3][3][c]. */
 int oracle_dw_conv(const int8_t *x, int n, int h, int wd, int c,
                    const int8_t *w /* [3][3][c] */, int stride,
@@ -170,6 +238,45 @@ int oracle_dw_conv(const int8_t *x, int n, int h, int wd, int c,
                 }
                 y[(((int64_t)in_ * ho + oy) * wo + ox) * c + ch] =
                     finish(acc, bias[ch], mult[ch], shift[ch], act_min, act_max, 0, 0);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Depthwise 3x3 conv with the PReLU requantisation. */
+int oracle_dw_conv_prelu(const int8_t *x, int n, int h, int wd, int c,
+                         const int8_t *w /* [3][3][c] */, int stride,
+                         const int32_t *bias, const int32_t *mult, const int32_t *mult_neg,
+                         const int32_t *shift, int32_t act_min, int32_t act_max,
+                         int8_t *y /* [n][ho][wo][c] */)
+{
+    if (!x || !w || !bias || !mult || !mult_neg || !shift || !y) return -1;
+    if (n <= 0 || h <= 0 || wd <= 0 || c <= 0 || (stride != 1 && stride != 2)) return -1;
+    int ho = (h + 2 - 3) / stride + 1;
+    int wo = (wd + 2 - 3) / stride + 1;
+    int64_t rows = (int64_t)n * ho;
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < rows; ++row) {
+        int in_ = (int)(row / ho);
+        int oy = (int)(row % ho);
+        for (int ox = 0; ox < wo; ++ox) {
+            for (int ch = 0; ch < c; ++ch) {
+                int64_t acc = 0;
+                for (int i = 0; i < 3; ++i) {
+                    for (int j = 0; j < 3; ++j) {
+                        int iy = oy * stride + i - 1;
+                        int ix = ox * stride + j - 1;
+                        if (iy < 0 || iy >= h || ix < 0 || ix >= wd) continue; /* zero pad */
+                        int64_t xv = x[(((int64_t)in_ * h + iy) * wd + ix) * c + ch];
+                        int64_t wv = w[(i * 3 + j) * c + ch];
+                        acc += xv * wv;
+                    }
+                }
+                y[(((int64_t)in_ * ho + oy) * wo + ox) * c + ch] =
+                    finish_prelu(acc, bias[ch], mult[ch], mult_neg[ch], shift[ch],
+                                 act_min, act_max, 0, 0);
             }
         }
     }

@@ -50,6 +50,16 @@ def _load():
         lib.oracle_dw_conv.argtypes = [_i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        _i8p, ctypes.c_int, _i32p, _i32p, _i32p,
                                        ctypes.c_int32, ctypes.c_int32, _i8p]
+        lib.oracle_requant_prelu.restype = ctypes.c_int64
+        lib.oracle_requant_prelu.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.oracle_pw_conv_prelu.restype = ctypes.c_int
+        lib.oracle_pw_conv_prelu.argtypes = [_i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             _i8p, ctypes.c_int, _i32p, _i32p, _i32p, _i32p,
+                                             ctypes.c_int32, ctypes.c_int32, _i8p, _i8p]
+        lib.oracle_dw_conv_prelu.restype = ctypes.c_int
+        lib.oracle_dw_conv_prelu.argtypes = [_i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             _i8p, ctypes.c_int, _i32p, _i32p, _i32p, _i32p,
+                                             ctypes.c_int32, ctypes.c_int32, _i8p]
         lib.oracle_block.restype = ctypes.c_int
         lib.oracle_block.argtypes = ([_i8p] + [ctypes.c_int] * 7 +
                                      [_i8p, _i32p, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32] * 3 +
@@ -87,6 +97,10 @@ def requant(s: int, mult: int, shift: int) -> int:
     return int(_load().oracle_requant(int(s), int(mult), int(shift)))
 
 
+def requant_prelu(s: int, mult: int, mult_neg: int, shift: int) -> int:
+    return int(_load().oracle_requant_prelu(int(s), int(mult), int(mult_neg), int(shift)))
+
+
 def pw_accum(x: np.ndarray, weight: np.ndarray) -> np.ndarray:
     """x int8 [..., cin], weight int8 [cout, cin] -> int32 [..., cout]."""
     x = _i8(x)
@@ -101,8 +115,9 @@ def pw_accum(x: np.ndarray, weight: np.ndarray) -> np.ndarray:
 
 
 def pw_conv(x, weight, bias, mult, shift, act_min: int, act_max: int,
-            residual=None) -> np.ndarray:
-    """x int8 [n,h,w,cin]; weight int8 [cout,cin] ternary -> int8 [n,h,w,cout]."""
+            residual=None, mult_neg=None) -> np.ndarray:
+    """x int8 [n,h,w,cin]; weight int8 [cout,cin] ternary -> int8 [n,h,w,cout].
+    With mult_neg (int32 [cout]) the PReLU requantisation is used."""
     x = _i8(x)
     weight = _i8(weight)
     n, h, w, cin = x.shape
@@ -115,6 +130,15 @@ def pw_conv(x, weight, bias, mult, shift, act_min: int, act_max: int,
         res = _i8(residual)
         assert res.shape == (n, h, w, cout)
     y = np.empty((n, h, w, cout), dtype=np.int8)
+    if mult_neg is not None:
+        mult_neg = _i32(mult_neg)
+        assert mult_neg.shape == (cout,)
+        rc = _load().oracle_pw_conv_prelu(_p8(x), n, h, w, cin, _p8(weight), cout, _p32(bias),
+                                          _p32(mult), _p32(mult_neg), _p32(shift), act_min, act_max,
+                                          _p8(res), _p8(y))
+        if rc:
+            raise ValueError(f"oracle_pw_conv_prelu failed: {rc}")
+        return y
     rc = _load().oracle_pw_conv(_p8(x), n, h, w, cin, _p8(weight), cout, _p32(bias), _p32(mult),
                                 _p32(shift), act_min, act_max, _p8(res), _p8(y))
     if rc:
@@ -122,8 +146,10 @@ def pw_conv(x, weight, bias, mult, shift, act_min: int, act_max: int,
     return y
 
 
-def dw_conv(x, weight, stride: int, bias, mult, shift, act_min: int, act_max: int) -> np.ndarray:
-    """x int8 [n,h,w,c]; weight int8 [3,3,c] -> int8 [n,ho,wo,c] (pad 1)."""
+def dw_conv(x, weight, stride: int, bias, mult, shift, act_min: int, act_max: int,
+            mult_neg=None) -> np.ndarray:
+    """x int8 [n,h,w,c]; weight int8 [3,3,c] -> int8 [n,ho,wo,c] (pad 1).
+    With mult_neg (int32 [c]) the PReLU requantisation is used."""
     x = _i8(x)
     weight = _i8(weight)
     n, h, w, c = x.shape
@@ -132,6 +158,15 @@ def dw_conv(x, weight, stride: int, bias, mult, shift, act_min: int, act_max: in
     ho = (h + 2 - 3) // stride + 1
     wo = (w + 2 - 3) // stride + 1
     y = np.empty((n, ho, wo, c), dtype=np.int8)
+    if mult_neg is not None:
+        mult_neg = _i32(mult_neg)
+        assert mult_neg.shape == (c,)
+        rc = _load().oracle_dw_conv_prelu(_p8(x), n, h, w, c, _p8(weight), stride, _p32(bias),
+                                          _p32(mult), _p32(mult_neg), _p32(shift), act_min, act_max,
+                                          _p8(y))
+        if rc:
+            raise ValueError(f"oracle_dw_conv_prelu failed: {rc}")
+        return y
     rc = _load().oracle_dw_conv(_p8(x), n, h, w, c, _p8(weight), stride, _p32(bias), _p32(mult),
                                 _p32(shift), act_min, act_max, _p8(y))
     if rc:
@@ -165,4 +200,17 @@ def block(x, expand, dw, project, stride: int, add_residual: bool):
                               int(bool(add_residual)), _p8(t1), _p8(t2), _p8(y))
     if rc:
         raise ValueError(f"oracle_block failed: {rc}")
+    return y, t1, t2
+
+
+def block_prelu(x, expand, dw, project, stride: int, add_residual: bool):
+    """The block with PReLU after the expand and depthwise layers (the paper's MobileNetV2
+    variant, Section 4): the three layer functions chained.  expand and dw are tuples
+    (weight, bias, mult, shift, act_min, act_max, mult_neg); project as in block()."""
+    we, be, me, se, loe, hie, ne = expand
+    wd_, bd, md, sd, lod, hid, nd = dw
+    wp, bp, mp, sp, lop, hip_ = project
+    t1 = pw_conv(x, we, be, me, se, loe, hie, mult_neg=ne)
+    t2 = dw_conv(t1, wd_, stride, bd, md, sd, lod, hid, mult_neg=nd)
+    y = pw_conv(t2, wp, bp, mp, sp, lop, hip_, residual=_i8(x) if add_residual else None)
     return y, t1, t2

@@ -152,6 +152,15 @@ def _requant_params(stream: SplitMix64, c: int, shift_range: Tuple[int, int] = (
     return bias, mult, shift
 
 
+def prelu_mult_neg(seed: int, mult: np.ndarray) -> np.ndarray:
+    """Negative-side multipliers of a PReLU layer: slope a_c = k/256 with k uniform in
+    [-64, 255] (PReLU slopes start at 0.25 and are learned per channel; a few turn negative),
+    folded into the positive multiplier, mult_neg = floor(mult * k / 256).  Input recipe only:
+    the layer functions take mult_neg as given."""
+    k = SplitMix64(seed).substream(31).uniform_int(mult.size, -64, 255).astype(np.int64)
+    return ((mult.astype(np.int64) * k) >> 8).astype(np.int32)
+
+
 def make_pw_layer(seed: int, n: int, h: int, w: int, cin: int, cout: int, *,
                   act_window: Tuple[int, int] = (0, 127), with_residual: bool = False,
                   p_zero: float = 0.5, signed_x: bool = False,
