@@ -33,9 +33,10 @@ def log(*a):
 
 def kernel_name(variant):
     nt, pt, ld, ks1, fullw = variant[:5]
+    # last template argument: 0 = the plain epilogues (1 = PReLU, 2 = both)
     if len(variant) > 5 and variant[5]:  # row-cooperative kernel
-        return f"void prom::pw_rows_kernel<{nt}, {str(ks1).lower()}>(prom::PwArgs)"
-    return (f"void prom::pw_stream_kernel<{nt}, {pt}, {ld}, {str(ks1).lower()}, {str(fullw).lower()}>"
+        return f"void prom::pw_rows_kernel<{nt}, {str(ks1).lower()}, {ld}, 0>(prom::PwArgs)"
+    return (f"void prom::pw_stream_kernel<{nt}, {pt}, {ld}, {str(ks1).lower()}, {str(fullw).lower()}, 0>"
             f"(prom::PwArgs)")
 
 
@@ -131,7 +132,8 @@ def main():
     for l in layers:
         s_ = l["shape"]
         l["class"] = 0 if args.no_batching else P.prom_pw_batch_class(args.batch, s_.hw, s_.hw, s_.cin, s_.cout)
-    BATCH_NAME = {1: "prom::pw_batch_kernel(prom::PwBatchArgs)", 2: "prom::pw_bigbatch_kernel(prom::PwBatchArgs)"}
+    BATCH_NAME = {1: "void prom::pw_batch_kernel<0>(prom::PwBatchArgs)",
+                  2: "void prom::pw_bigbatch_kernel<0>(prom::PwBatchArgs)"}
     runs = []  # layers that go into one PwSequence call
     for cls in (2, 0, 1):
         members = [l for l in layers if l["class"] == cls]
@@ -335,7 +337,52 @@ def main():
         log(f"[bench] oracle: {ops / t_cpu / 1e9:.2f} Gop/s on {oracle.max_threads()} threads; "
             f"GPU outputs of the sample differ in {mismatches} elements")
 
+    # ---- extra leg: the same sweep as a PReLU network (the paper's MobileNetV2 variant: PReLU
+    # after every expand layer and the head, none after the project layers) -----------------------
+    if not args.no_extra:
+        result.setdefault("extra", {})["prelu_sweep"] = prelu_leg(P, torch, dev, layers, args, total_bytes,
+                                                                  not args.no_cpu_baseline, log)
+
     print(json.dumps(result), flush=True)
+
+
+def prelu_leg(P, torch, dev, layers, args, total_bytes, check, log):
+    import numpy as np
+    from workloads import prelu_mult_neg
+    seq_layers, prelu_layers = [], []
+    for i, l in enumerate(layers):
+        s, L = l["shape"], l["L"]
+        is_act = not s.name.endswith("project")
+        mneg = prelu_mult_neg(SEED + 500 + i, L.mult) if is_act else None
+        rq = P.Requant(l["rq"].bias, l["rq"].mult, l["rq"].shift, -128, 127,
+                       torch.from_numpy(mneg).to(dev) if is_act else None)
+        seq_layers.append((l["x"], l["wp"], s.cout, rq, None, l["y"]))
+        if is_act:
+            prelu_layers.append((l, mneg))
+    seq = P.PwSequence(seq_layers)
+    for _ in range(3):
+        seq.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        seq.run()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / args.steps
+    out = {"prelu_layers": len(prelu_layers), "us": round(us, 1),
+           "gbs": round(total_bytes / (us * 1e-6) / 1e9, 1),
+           "frac_hbm_roofline": round(total_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    if check:
+        import oracle
+        bad = 0
+        for l, mneg in prelu_layers:
+            L = l["L"]
+            want = oracle.pw_conv(np.ascontiguousarray(L.x[:2]), L.weight, L.bias, L.mult, L.shift, -128, 127,
+                                  mult_neg=mneg)
+            bad += int((l["y"][:2].cpu().numpy() != want).sum())
+        out["parity_mismatches_vs_oracle"] = bad
+    log(f"[bench] PReLU sweep ({len(prelu_layers)} of {len(layers)} layers with PReLU): {us:.1f} us/step, "
+        f"{out['gbs']:.0f} GB/s")
+    return out
 
 
 def ab_study(P, torch, dev, which, batch):

@@ -53,7 +53,16 @@ enum {
 };
 
 /* Per-output-channel requantisation and activation window.  The struct itself is read on
- * the host at call time; its three arrays are device memory of C int32 values each. */
+ * the host at call time; its arrays are device memory of C int32 values each.
+ *
+ * PReLU (the paper's MobileNetV2 and RegNetX models replace ReLU6 / ReLU by PReLU, Section 4,
+ * experimental setup): with mult_neg != NULL the multiplier of an output follows the sign of
+ * s = acc + bias[c] (which is the sign of the real pre-activation, the scales being positive):
+ *     m = s >= 0 ? mult[c] : mult_neg[c]
+ *     q = floor((s*m + 2^(30+shift[c])) / 2^(31+shift[c])),  then the window and the residual
+ * mult_neg[c] is the slope a_c folded into the multiplier (a_c * mult[c], same shift); any int32
+ * value is computed exactly (a slope may be negative or, with a smaller mult, above 1).  The
+ * window is then usually the full [-128, 127].  mult_neg == NULL gives the plain form above. */
 typedef struct {
     const int32_t *bias;     /* dev [C]                                                       */
     const int32_t *mult;     /* dev [C]  Q31 multiplier, 2^30 <= mult < 2^31 for a normalised
@@ -61,6 +70,7 @@ typedef struct {
     const int32_t *shift;    /* dev [C]  extra right shift, 0..31                             */
     int32_t act_min;         /* -128 <= act_min <= act_max <= 127; [0,127] is ReLU6 when the  */
     int32_t act_max;         /*  output scale maps 6.0 to 127                                 */
+    const int32_t *mult_neg; /* dev [C] or NULL: PReLU multiplier for acc + bias < 0          */
 } prom_requant_t;
 
 /* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default".
@@ -196,7 +206,8 @@ int prom_pw_batch_class(int n, int h, int w, int cin, int cout);
  * accumulation on the vector ALU (sums of the input bytes whose weight is +1 / -1, paper
  * Section 2), one lane per pixel.  Bit-identical results; kept for the A/B measurement against
  * the MFMA kernel, not for production use.  Limits: cin <= 256, cin % 4 == 0, cout % 4 == 0,
- * 4-byte aligned pointers, tensors below 2 GiB (PROM_EUNSUPPORTED otherwise). */
+ * 4-byte aligned pointers, tensors below 2 GiB, no PReLU multipliers (PROM_EUNSUPPORTED
+ * otherwise). */
 int prom_pw_conv_addsub(const int8_t *x, int n, int h, int w, int cin,
                         const void *w_packed, int cout, const prom_requant_t *rq,
                         const int8_t *residual, int8_t *y, void *stream);

@@ -26,7 +26,8 @@ class PromError(RuntimeError):
 
 class _RequantC(ctypes.Structure):
     _fields_ = [("bias", ctypes.c_void_p), ("mult", ctypes.c_void_p), ("shift", ctypes.c_void_p),
-                ("act_min", ctypes.c_int32), ("act_max", ctypes.c_int32)]
+                ("act_min", ctypes.c_int32), ("act_max", ctypes.c_int32),
+                ("mult_neg", ctypes.c_void_p)]
 
 
 class _PwLayerC(ctypes.Structure):
@@ -120,19 +121,24 @@ def _check(rc: int, where: str) -> None:
 
 @dataclass
 class Requant:
-    """Device int32 tensors bias/mult/shift of one layer plus its activation window."""
+    """Device int32 tensors bias/mult/shift of one layer plus its activation window;
+    mult_neg (optional) makes it a PReLU layer."""
     bias: "torch.Tensor"
     mult: "torch.Tensor"
     shift: "torch.Tensor"
     act_min: int
     act_max: int
+    mult_neg: "Optional[torch.Tensor]" = None
 
     def _c(self) -> _RequantC:
         import torch
-        for t in (self.bias, self.mult, self.shift):
+        for t in (self.bias, self.mult, self.shift) + (() if self.mult_neg is None else (self.mult_neg,)):
             assert t.dtype == torch.int32 and t.is_contiguous() and t.is_cuda
+        if self.mult_neg is not None:
+            assert self.mult_neg.numel() == self.mult.numel()
         return _RequantC(self.bias.data_ptr(), self.mult.data_ptr(), self.shift.data_ptr(),
-                         int(self.act_min), int(self.act_max))
+                         int(self.act_min), int(self.act_max),
+                         None if self.mult_neg is None else self.mult_neg.data_ptr())
 
 
 @dataclass

@@ -31,6 +31,7 @@ struct BlockArgs {
     const int32_t *be, *me, *se;  // expand bias / mult / shift [chid]
     const int32_t *bd, *md, *sd;  // depthwise [chid]
     const int32_t *bp, *mp, *sp;  // project [cout]
+    const int32_t *ne, *nd, *np;  // PReLU negative-side multipliers of the three layers, or nullptr
     int N, H, W, Ho, Wo, cin, chid, cout, stride;
     int R;        // output rows per band
     int bands;    // bands per image
@@ -43,10 +44,17 @@ struct BlockArgs {
 
 constexpr int kCH = 64;  // hidden channels per chunk = one k step of the projection
 
-__device__ __forceinline__ v4i make_par(int b, int m, int s)
+// Parameters of channel c of a layer in the form its epilogue takes (mneg == nullptr: plain).
+__device__ __forceinline__ v4i make_par(const int32_t *b, const int32_t *m, const int32_t *mneg,
+                                        const int32_t *s, int c)
 {
-    const long long C = (long long)b * m + (1LL << (30 + s));
-    return v4i{(int)(uint32_t)C, (int)(C >> 32), m, s};
+    return requant_params(b[c], m[c], mneg ? mneg[c] : 0, s[c], mneg != nullptr);
+}
+
+// prelu is uniform over the launch.
+__device__ __forceinline__ int requant_sel(bool prelu, int accv, const v4i &pr, int lo, int hi)
+{
+    return prelu ? requant_prelu_i64(accv, pr, lo, hi) : requant_i64<true>(accv, pr, lo, hi);
 }
 
 // COT: 16-channel output tiles (cout <= 16*COT); TPW: projection pixel tiles per wavefront.
@@ -98,7 +106,7 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
         // project parameters (used after the last chunk)
         if (tid < 16 * COT) {
             v4i p = {0, 0, 0, 1};
-            if (tid < cout) p = make_par(a.bp[tid], a.mp[tid], a.sp[tid]);
+            if (tid < cout) p = make_par(a.bp, a.mp, a.np, a.sp, tid);
             pp[tid] = p;
         }
     }
@@ -137,8 +145,8 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
         if (tid < kCH) {
             v4i e = {0, 0, 0, 1}, d = {0, 0, 0, 1};
             if (tid < chc) {
-                e = make_par(a.be[c0 + tid], a.me[c0 + tid], a.se[c0 + tid]);
-                d = make_par(a.bd[c0 + tid], a.md[c0 + tid], a.sd[c0 + tid]);
+                e = make_par(a.be, a.me, a.ne, a.se, c0 + tid);
+                d = make_par(a.bd, a.md, a.nd, a.sd, c0 + tid);
             }
             pe[tid] = e;
             pd[tid] = d;
@@ -176,7 +184,7 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
                     if (ri >= 0 && ri < a.H) {
                         int v[4];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = requant_i64<true>(d4[r], par[r], lo_e, hi_e);
+                        for (int r = 0; r < 4; ++r) v[r] = requant_sel(a.ne != nullptr, d4[r], par[r], lo_e, hi_e);
                         o = pack4_low_bytes(v[0], v[1], v[2], v[3]);
                     }
                     *reinterpret_cast<uint32_t *>(t1 + (row * W2 + col + 1) * kCH + 16 * t + 4 * g) = o;
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
                         }
                     int v[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) v[q] = requant_i64<true>(sum[q], par[q], lo_d, hi_d);
+                    for (int q = 0; q < 4; ++q) v[q] = requant_sel(a.nd != nullptr, sum[q], par[q], lo_d, hi_d);
                     *reinterpret_cast<uint32_t *>(t2 + item * kCH + 4 * cg) = pack4_low_bytes(v[0], v[1], v[2], v[3]);
                 }
             }
@@ -252,7 +260,7 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
             if (c < cout) {
                 int v[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = requant_i64<true>(acc[q][t][r], pp[c + r], lo_p, hi_p);
+                for (int r = 0; r < 4; ++r) v[r] = requant_sel(a.np != nullptr, acc[q][t][r], pp[c + r], lo_p, hi_p);
                 if (a.add_res) {
                     // stride 1 and cin == cout: the block input at the same pixel and channels
                     const uint32_t res = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(
@@ -388,6 +396,7 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
     a.be = rq_expand->bias; a.me = rq_expand->mult; a.se = rq_expand->shift;
     a.bd = rq_dw->bias; a.md = rq_dw->mult; a.sd = rq_dw->shift;
     a.bp = rq_project->bias; a.mp = rq_project->mult; a.sp = rq_project->shift;
+    a.ne = rq_expand->mult_neg; a.nd = rq_dw->mult_neg; a.np = rq_project->mult_neg;
     a.N = n; a.H = h; a.W = w; a.Ho = ho; a.Wo = wo;
     a.cin = cin; a.chid = chid; a.cout = cout; a.stride = stride;
     a.add_res = add_residual;

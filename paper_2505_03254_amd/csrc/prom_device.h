@@ -65,6 +65,60 @@ __device__ __forceinline__ int requant_to_biased(int s, double scale, int lo_b, 
     return clamp_i32(qe, lo_b, hi_b);
 }
 
+// ---- integer requantisation ------------------------------------------------------------------
+
+// The four per-channel values the epilogue keeps in registers.
+__device__ __forceinline__ v4i requant_params(int bias, int mult, int mult_neg, int shift, bool prelu)
+{
+    if (prelu) return v4i{bias, mult, mult_neg, shift};
+    const long long C = (long long)bias * mult + (1LL << (30 + shift));
+    return v4i{(int)(uint32_t)C, (int)(C >> 32), mult, shift};
+}
+
+// t = acc*mult + C; q = t >> (31 + shift); clamp to [lo, hi].  pr = (C lo, C hi, mult, s) with
+// s = shift-1 when !GENERAL (the caller guarantees shift >= 1) and s = shift when GENERAL.
+template <bool GENERAL>
+__device__ __forceinline__ int requant_i64(int accv, const v4i &pr, int lo, int hi)
+{
+    const long long C = (long long)(((unsigned long long)(uint32_t)pr[1] << 32) | (uint32_t)pr[0]);
+    const long long t = (long long)accv * (long long)pr[2] + C;
+    int q;
+    if constexpr (GENERAL)
+        q = (int)(t >> 31) >> pr[3];
+    else
+        q = (int)(t >> 32) >> pr[3];
+    return med3_i32(q, lo, hi);
+}
+
+// PReLU form: pr = (bias, mult, mult_neg, shift); the multiplier follows the sign of
+// s = acc + bias, then q = floor((s*m + 2^(30+shift)) / 2^(31+shift)), clamp.  Computed as
+// floor((floor(s*m / 2^shift) + 2^30) / 2^31), which is the same number (2^30 is an integer and
+// nested floors of divisions by positive integers collapse) and needs no per-channel rounding
+// constant: such constants are loop invariants the compiler would keep in registers, two more
+// per channel.
+__device__ __forceinline__ int requant_prelu_s(int s, int mult, int mult_neg, int shift, int lo, int hi)
+{
+    const int m = s < 0 ? mult_neg : mult;
+    const long long u = ((long long)s * (long long)m) >> shift;
+    const int q = (int)((u + (1LL << 30)) >> 31);
+    return med3_i32(q, lo, hi);
+}
+__device__ __forceinline__ int requant_prelu_i64(int accv, const v4i &pr, int lo, int hi)
+{
+    return requant_prelu_s(accv + pr[0], pr[1], pr[2], pr[3], lo, hi);
+}
+
+// Epilogue forms: 0 = every shift of the wavefront's channels >= 1 (pr.w holds shift-1),
+// 1 = any shift, 2 = PReLU.
+template <int MODE>
+__device__ __forceinline__ int requant_mode(int accv, const v4i &pr, int lo, int hi)
+{
+    if constexpr (MODE == 2)
+        return requant_prelu_i64(accv, pr, lo, hi);
+    else
+        return requant_i64<MODE == 1>(accv, pr, lo, hi);
+}
+
 // Low bytes of four ints -> one dword (a in bits 0..7).
 __device__ __forceinline__ uint32_t pack4_low_bytes(int a, int b, int c, int d)
 {

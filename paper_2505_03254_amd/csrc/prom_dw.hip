@@ -25,6 +25,7 @@ struct DwArgs {
     const int8_t *w;  // [3][3][C]
     const int32_t *bias;
     const int32_t *mult;
+    const int32_t *mult_neg;  // PReLU: multiplier for acc + bias < 0, or nullptr
     const int32_t *shift;
     int8_t *y;
     int N, H, W, C, Ho, Wo, stride;
@@ -138,6 +139,19 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     }
     const int yoff = ox * a.C + c;
     const int yrow = a.Wo * a.C;
+    if (a.mult_neg) {  // PReLU layer (uniform over the launch)
+        const v4i pn = *reinterpret_cast<const v4i *>(a.mult_neg + c);
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            int out[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                out[q] = requant_prelu_i64(acc[o][q], v4i{pb[q], pm[q], pn[q], ps[q]}, lo, hi);
+            __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(out[0], out[1], out[2], out[3]), ry, yoff,
+                                                  (oy0 + o) * yrow, 0);
+        }
+        return;
+    }
 #pragma unroll
     for (int o = 0; o < 4; ++o) {
         int out[4];
@@ -175,7 +189,8 @@ __global__ __launch_bounds__(256) void dw_kernel_generic(const DwArgs a)
                    (int)a.w[(i * 3 + jx) * a.C + c];
         }
     }
-    const int v = requant_to_biased(acc, make_scale(a.mult[c], a.shift[c]), a.lo_b, a.hi_b);
+    const int m = (a.mult_neg && acc < 0) ? a.mult_neg[c] : a.mult[c];
+    const int v = requant_to_biased(acc, make_scale(m, a.shift[c]), a.lo_b, a.hi_b);
     a.y[tid] = (int8_t)(v - kQBias);
 }
 
@@ -195,7 +210,7 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
     if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || (stride != 1 && stride != 2)) return PROM_EINVAL;
     if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
     DwArgs a;
-    a.x = x; a.w = w_dw; a.bias = rq->bias; a.mult = rq->mult; a.shift = rq->shift; a.y = y;
+    a.x = x; a.w = w_dw; a.bias = rq->bias; a.mult = rq->mult; a.mult_neg = rq->mult_neg; a.shift = rq->shift; a.y = y;
     a.N = n; a.H = h; a.W = w; a.C = c; a.stride = stride;
     a.Ho = (h - 1) / stride + 1;
     a.Wo = (w - 1) / stride + 1;
@@ -208,7 +223,7 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
     clear_hip_error();
     // the fast kernel addresses one image with 32-bit offsets and reads the parameters 16 bytes at a time
     const bool fast = (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 3) == 0) &&
-                      ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->shift) & 15) == 0) &&
+                      ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg | (uintptr_t)rq->shift) & 15) == 0) &&
                       (long long)h * w * c < (1LL << 31) - (1LL << 24) && n <= 65535;
     if (fast) {
         a.strip_rows = 4;

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void pw_generic_kernel(const PwArgs a)
     const int Wv = a.wg_per_chunk * 4;
     const int K = a.K, M = a.M, Nc = a.Nc;
 
-    stage_weights<NT, !RAW>(a, cbase, frag, lpar);
+    stage_weights<NT, !RAW>(a, cbase, frag, lpar, !RAW && a.mult_neg != nullptr);
 
     v4i par[NT][4];
 #pragma unroll
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256) void pw_generic_kernel(const PwArgs a)
                     if constexpr (RAW) {
                         a.acc_out[rowoff + cl] = acc[t][r];
                     } else {
-                        int v = requant_i64<true>(acc[t][r], par[t][r], lo, hi);
+                        int v = a.mult_neg ? requant_prelu_i64(acc[t][r], par[t][r], lo, hi)
+                                           : requant_i64<true>(acc[t][r], par[t][r], lo, hi);
                         if (a.residual) v = med3_i32(v + (int)a.residual[rowoff + cl], m128, p127);
                         a.y[rowoff + cl] = (int8_t)v;
                     }
@@ -106,6 +107,7 @@ constexpr int kBatchNTDeep = 2;
 constexpr int kBatchDeepKS = 10;
 __host__ __device__ constexpr int batch_nt(int ks) { return ks >= kBatchDeepKS ? kBatchNTDeep : kBatchNT; }
 
+template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -121,16 +123,16 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     // ring are exact (a store in a conditional epilogue makes them conservative)
     if (a.KS >= kBatchDeepKS) {
         if (a.Nc % (16 * kBatchNTDeep) == 0)
-            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth>(a, lid, lds_raw);
+            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, EPI>(a, lid, lds_raw);
         else
-            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth>(a, lid, lds_raw);
+            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, EPI>(a, lid, lds_raw);
     } else if (a.Nc % (16 * kBatchNT) == 0) {
         if (a.KS == 1)
-            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth>(a, lid, lds_raw);
+            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, EPI>(a, lid, lds_raw);
         else
-            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth>(a, lid, lds_raw);
+            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, EPI>(a, lid, lds_raw);
     } else {
-        pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth>(a, lid, lds_raw);
+        pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, EPI>(a, lid, lds_raw);
     }
 }
 
@@ -151,7 +153,7 @@ constexpr long long kStreamBytes = (1LL << 31) - (1LL << 16);  // 32-bit buffer 
 using KernelFn = PwKernelFn;
 
 // mode 0: requantised output; mode 1: raw accumulators.  fast: streaming kernel applies.
-static KernelFn select_kernel(int nt, int pt, int xmode, bool ks1, bool fullw, bool fast, int mode)
+static KernelFn select_kernel(int nt, int pt, int xmode, bool ks1, bool fullw, bool fast, int mode, bool prelu)
 {
     if (!fast) {
         const bool raw = mode == 1;
@@ -163,16 +165,16 @@ static KernelFn select_kernel(int nt, int pt, int xmode, bool ks1, bool fullw, b
         }
     }
     switch (nt) {
-    case 1: return pw_stream_select<1>(pt, xmode, ks1, fullw);
-    case 2: return pw_stream_select<2>(pt, xmode, ks1, fullw);
-    case 3: return pw_stream_select<3>(pt, xmode, ks1, fullw);
-    case 4: return pw_stream_select<4>(pt, xmode, ks1, fullw);
-    case 5: return pw_stream_select<5>(pt, xmode, ks1, fullw);
-    case 6: return pw_stream_select<6>(pt, xmode, ks1, fullw);
-    case 7: return pw_stream_select<7>(pt, xmode, ks1, fullw);
-    case 8: return pw_stream_select<8>(pt, xmode, ks1, fullw);
-    case 9: return pw_stream_select<9>(pt, xmode, ks1, fullw);
-    case 10: return pw_stream_select<10>(pt, xmode, ks1, fullw);
+    case 1: return pw_stream_select<1>(pt, xmode, ks1, fullw, prelu);
+    case 2: return pw_stream_select<2>(pt, xmode, ks1, fullw, prelu);
+    case 3: return pw_stream_select<3>(pt, xmode, ks1, fullw, prelu);
+    case 4: return pw_stream_select<4>(pt, xmode, ks1, fullw, prelu);
+    case 5: return pw_stream_select<5>(pt, xmode, ks1, fullw, prelu);
+    case 6: return pw_stream_select<6>(pt, xmode, ks1, fullw, prelu);
+    case 7: return pw_stream_select<7>(pt, xmode, ks1, fullw, prelu);
+    case 8: return pw_stream_select<8>(pt, xmode, ks1, fullw, prelu);
+    case 9: return pw_stream_select<9>(pt, xmode, ks1, fullw, prelu);
+    case 10: return pw_stream_select<10>(pt, xmode, ks1, fullw, prelu);
     default: return nullptr;
     }
 }
@@ -291,6 +293,7 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     a.wq = static_cast<const uint32_t *>(w_packed);
     a.bias = rq ? rq->bias : nullptr;
     a.mult = rq ? rq->mult : nullptr;
+    a.mult_neg = rq ? rq->mult_neg : nullptr;
     a.shift = rq ? rq->shift : nullptr;
     a.residual = mode == 0 ? residual : nullptr;
     a.y = y;
@@ -373,10 +376,10 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     L.threads = L.rows ? rows_threads(a.cw) : 256;
     if (L.rows) {
         L.lds = lds_bytes_rows(nt, a.cw, a.KS);
-        L.fn = pw_rows_select(nt, a.KS == 1, L.xmode);
+        L.fn = pw_rows_select(nt, a.KS == 1, L.xmode, a.mult_neg != nullptr);
     } else {
         L.lds = fast ? lds_bytes_fast(nt, a.KS) : lds_bytes_generic(nt, a.KS);
-        L.fn = select_kernel(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, fast, mode);
+        L.fn = select_kernel(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, fast, mode, a.mult_neg != nullptr);
     }
     if (!L.fn) return PROM_EINVAL;
     L.big_body = fast ? pw_big_body_id(nt, pt, L.xmode, a.KS == 1, cout % (16 * nt) == 0, a.cw) : -1;
@@ -557,11 +560,13 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         if (l > lds) lds = l;
     }
     b.start[count] = start;
-    if (resident_workgroups(reinterpret_cast<KernelFn>(static_cast<PwBatchFn>(&pw_batch_kernel)), lds) < 1) return PROM_EHIP;
+    bool any_prelu = false;
+    for (int i = 0; i < count; ++i) any_prelu |= members[i]->a.mult_neg != nullptr;
+    const PwBatchFn fn = any_prelu ? &pw_batch_kernel<kEpiBoth> : &pw_batch_kernel<kEpiPlain>;
+    if (resident_workgroups(reinterpret_cast<KernelFn>(fn), lds) < 1) return PROM_EHIP;
     clear_hip_error();
     void *kargs[] = {&b};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&pw_batch_kernel), dim3(start), dim3(256),
-                                         kargs, lds, st);
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(fn), dim3(start), dim3(256), kargs, lds, st);
     if (e != hipSuccess) {
         last_hip_error() = e;
         (void)hipGetLastError();
@@ -613,7 +618,9 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         if (l > lds) lds = l;
     }
     b.start[count] = start;
-    const PwBatchFn fn = pw_bigbatch_fn();
+    bool any_prelu = false;
+    for (int i = 0; i < count; ++i) any_prelu |= members[i]->a.mult_neg != nullptr;
+    const PwBatchFn fn = pw_bigbatch_fn(any_prelu);
     if (resident_workgroups(reinterpret_cast<KernelFn>(fn), lds) < 1) return PROM_EHIP;
     clear_hip_error();
     void *kargs[] = {&b};

@@ -173,6 +173,7 @@ extern "C" int prom_pw_conv_addsub(const int8_t *x, int n, int h, int w, int cin
     const long long M = (long long)n * h * w;
     if ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)residual | (uintptr_t)w_packed) & 3) != 0) return PROM_EINVAL;
     if (cin > 256 || cin % 4 != 0 || cout % 4 != 0) return PROM_EUNSUPPORTED;
+    if (rq->mult_neg) return PROM_EUNSUPPORTED;  // the comparison kernel has the plain epilogue only
     if ((M + 64) * (long long)(cin > cout ? cin : cout) >= (1LL << 31) - (1LL << 20)) return PROM_EUNSUPPORTED;
     {
         const uintptr_t ya = (uintptr_t)y, xa = (uintptr_t)x;

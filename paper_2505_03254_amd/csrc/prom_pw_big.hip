@@ -40,6 +40,7 @@ size_t pw_big_body_lds(int body, const PwArgs &a)
     }
 }
 
+template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -49,16 +50,20 @@ __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b
     const int lid = logical_block_id(bid - b.start[i], b.start[i + 1] - b.start[i]);
     const PwArgs &a = b.layer[i];
     switch (b.body[i]) {
-    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true>(a, lid, lds_raw); break;
-    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true>(a, lid, lds_raw); break;
-    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false>(a, lid, lds_raw); break;
-    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false>(a, lid, lds_raw); break;
-    case kBodyR3x8: pw_rows_body<3, true, 8>(a, lid, lds_raw); break;
-    case kBodyR3: pw_rows_body<3, true, 16>(a, lid, lds_raw); break;
-    default: pw_rows_body<6, true, 16>(a, lid, lds_raw); break;
+    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true, ring_depth<4>(), EPI>(a, lid, lds_raw); break;
+    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true, ring_depth<1>(), EPI>(a, lid, lds_raw); break;
+    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false, ring_depth<2>(), EPI>(a, lid, lds_raw); break;
+    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), EPI>(a, lid, lds_raw); break;
+    case kBodyR3x8: pw_rows_body<3, true, 8, 4, EPI>(a, lid, lds_raw); break;
+    case kBodyR3: pw_rows_body<3, true, 16, 4, EPI>(a, lid, lds_raw); break;
+    default: pw_rows_body<6, true, 16, 4, EPI>(a, lid, lds_raw); break;
     }
 }
 
-PwBatchFn pw_bigbatch_fn() { return &pw_bigbatch_kernel; }
+// any_prelu: a member of the launch is a PReLU layer.
+PwBatchFn pw_bigbatch_fn(bool any_prelu)
+{
+    return any_prelu ? &pw_bigbatch_kernel<kEpiBoth> : &pw_bigbatch_kernel<kEpiPlain>;
+}
 
 }  // namespace prom

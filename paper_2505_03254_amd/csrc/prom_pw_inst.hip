@@ -8,28 +8,30 @@
 
 namespace prom {
 
-template <int NT, int PT, int XMODE>
+template <int NT, int PT, int XMODE, int EPI>
 static PwKernelFn pick(bool ks1, bool fullw)
 {
-    if (ks1) return fullw ? &pw_stream_kernel<NT, PT, XMODE, true, true> : &pw_stream_kernel<NT, PT, XMODE, true, false>;
-    return fullw ? &pw_stream_kernel<NT, PT, XMODE, false, true> : &pw_stream_kernel<NT, PT, XMODE, false, false>;
+    if (ks1)
+        return fullw ? &pw_stream_kernel<NT, PT, XMODE, true, true, EPI> : &pw_stream_kernel<NT, PT, XMODE, true, false, EPI>;
+    return fullw ? &pw_stream_kernel<NT, PT, XMODE, false, true, EPI> : &pw_stream_kernel<NT, PT, XMODE, false, false, EPI>;
 }
 
 template <int NT, int PT>
-static PwKernelFn pick_x(int xmode, bool ks1, bool fullw)
+static PwKernelFn pick_x(int xmode, bool ks1, bool fullw, bool prelu)
 {
-    return xmode == 16 ? pick<NT, PT, 16>(ks1, fullw) : pick<NT, PT, 8>(ks1, fullw);
+    if (prelu) return xmode == 16 ? pick<NT, PT, 16, kEpiPrelu>(ks1, fullw) : pick<NT, PT, 8, kEpiPrelu>(ks1, fullw);
+    return xmode == 16 ? pick<NT, PT, 16, kEpiPlain>(ks1, fullw) : pick<NT, PT, 8, kEpiPlain>(ks1, fullw);
 }
 
-template <> PwKernelFn pw_stream_select<PROM_PW_NT>(int pt, int xmode, bool ks1, bool fullw)
+template <> PwKernelFn pw_stream_select<PROM_PW_NT>(int pt, int xmode, bool ks1, bool fullw, bool prelu)
 {
     constexpr int NT = PROM_PW_NT;
-    if (pt == 1) return pick_x<NT, 1>(xmode, ks1, fullw);
+    if (pt == 1) return pick_x<NT, 1>(xmode, ks1, fullw, prelu);
     if constexpr (NT <= 6) {
-        if (pt == 2) return pick_x<NT, 2>(xmode, ks1, fullw);
+        if (pt == 2) return pick_x<NT, 2>(xmode, ks1, fullw, prelu);
     }
     if constexpr (NT <= 2) {
-        if (pt == 4) return pick_x<NT, 4>(xmode, ks1, fullw);
+        if (pt == 4) return pick_x<NT, 4>(xmode, ks1, fullw, prelu);
     }
     return nullptr;
 }

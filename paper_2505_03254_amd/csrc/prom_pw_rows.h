@@ -35,7 +35,7 @@ __host__ __device__ constexpr size_t lds_bytes_rows(int nt, int cw, int ks)
 // Fragments frag[CW*NT][KS][64] and parameters lpar[CW*NT][4 g][4 r] of a super-chunk; tile slot
 // cw*NT + t holds the channels base + 16*NT*cw + chan_of<NT>(t, ., .).  Ends with the barrier.
 template <int NT>
-__device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, int CW, int nthr, v4i *frag,
+__device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, int CW, int nthr, bool prelu, v4i *frag,
                                                    v4i *lpar)
 {
     const int tid = threadIdx.x;
@@ -71,14 +71,14 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
         const int cw = tt / NT;
         const int t = tt - cw * NT;
         const int c = cbase + cw * NT * 16 + chan_of<NT>(t, (s >> 2) & 3, s & 3);
-        int pb = 0, pm = 0, ps = 1;
+        int pb = 0, pm = 0, pn = 0, ps = 1;
         if (c < Nc) {
             pb = a.bias[c];
             pm = a.mult[c];
             ps = a.shift[c];
+            if (prelu) pn = a.mult_neg[c];
         }
-        const long long C = (long long)pb * pm + (1LL << (30 + ps));
-        lpar[s] = v4i{(int)(uint32_t)C, (int)(C >> 32), pm, ps};
+        lpar[s] = requant_params(pb, pm, pn, ps, prelu);
     }
     __syncthreads();
 }
@@ -86,9 +86,10 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
 // Requirements (checked by the host): cin % 16 == 0 (XMODE 16) or cin % 8 == 0 (XMODE 8, two
 // 8-byte loads per fragment), cout % (16*NT*CW) == 0, 4-byte aligned tensors below 2^31 bytes,
 // CW in {2, 3, 4} (a.cw), 64*CW*G threads per workgroup, a.units counts groups of 16 pixels.
-template <int NT, bool KS1, int XMODE = 16, int D = 4>
+template <int NT, bool KS1, int XMODE = 16, int D = 4, int EPI = kEpiPlain>
 __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
+    const bool prelu = EPI == kEpiPrelu || (EPI == kEpiBoth && a.mult_neg != nullptr);
     constexpr int NI = (NT + 3) / 4;  // 16-byte pieces per lane per step: 16*G*CW*NT pieces, 64*G*CW lanes
     const int KS = KS1 ? 1 : a.KS;
     const int CW = a.cw, G = 4 / CW, NTT = CW * NT;
@@ -144,7 +145,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
 
-    stage_weights_rows<NT>(a, cbase, CW, nthr, frag, lpar);
+    stage_weights_rows<NT>(a, cbase, CW, nthr, prelu, frag, lpar);
 
     v4i par[NT][4];
     const v4i *lpg = lpar + cwi * NT * 16 + g * 4;
@@ -158,7 +159,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
         }
     // per wavefront: the wavefronts of a workgroup may take different forms of the loop; they
     // still meet at the same number of barriers
-    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+    const bool general_shift = prelu || __builtin_amdgcn_ballot_w64(sh0) != 0;
     if (!general_shift) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
@@ -189,11 +190,27 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
     const int tail_steps = total_steps - full_rounds * D;
     const v4i *fl = frag + cwi * NT * KS * 64 + lane;
 
-    auto run = [&](auto has_res_tag, auto general_tag) {
+    auto run = [&](auto has_res_tag, auto mode_tag) {
         constexpr bool HAS_RES = decltype(has_res_tag)::value;
-        constexpr bool GENERAL = decltype(general_tag)::value;
+        constexpr int MODE = decltype(mode_tag)::value;
         v4i acc[NT];
         const v4i zero4 = {0, 0, 0, 0};
+        // PReLU: the parameters per tile as four vectors over the lane's 4 channels.  The biases
+        // are the accumulators' start value (a register quad the first MFMA of a group reads
+        // as its C operand), so that the sign of the accumulator is the sign that selects the
+        // multiplier.
+        v4i cinit[NT], pmul[NT], pneg[NT], pshift[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if constexpr (MODE == 2) {
+                cinit[t] = v4i{par[t][0][0], par[t][1][0], par[t][2][0], par[t][3][0]};
+                pmul[t] = v4i{par[t][0][1], par[t][1][1], par[t][2][1], par[t][3][1]};
+                pneg[t] = v4i{par[t][0][2], par[t][1][2], par[t][2][2], par[t][3][2]};
+                pshift[t] = v4i{par[t][0][3], par[t][1][3], par[t][2][3], par[t][3][3]};
+            } else {
+                cinit[t] = zero4;
+            }
+        }
         int ck = 0;
         int buf = 0;
         auto step = [&](v4i &slot, auto refill_tag) {
@@ -205,7 +222,7 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
             if (KS1 || ck == 0) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KS * 64], slot, zero4, 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KS * 64], slot, cinit[t], 0, 0, 0);
             } else {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
@@ -239,7 +256,13 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
                             int v[4];
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                v[r] = requant_i64<GENERAL>(acc[t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                {
+                                    if constexpr (MODE == 2)
+                                        v[r] = requant_prelu_s(acc[t0 + tt][r], pmul[t0 + tt][r], pneg[t0 + tt][r],
+                                                               pshift[t0 + tt][r], lo, hi);
+                                    else
+                                        v[r] = requant_mode<MODE>(acc[t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                }
                             if constexpr (HAS_RES) {
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) v[r] = med3_i32(v[r] + sbyte(res[tt], r), m128, p127);
@@ -279,24 +302,38 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
         }
     };
 
-    if (a.residual) {
-        if (general_shift)
-            run(std::true_type{}, std::true_type{});
-        else
-            run(std::true_type{}, std::false_type{});
-    } else {
-        if (general_shift)
-            run(std::false_type{}, std::true_type{});
-        else
-            run(std::false_type{}, std::false_type{});
+    using Fast = std::integral_constant<int, 0>;
+    using General = std::integral_constant<int, 1>;
+    using Prelu = std::integral_constant<int, 2>;
+    if constexpr (EPI != kEpiPlain) {
+        if (prelu) {
+            if (a.residual)
+                run(std::true_type{}, Prelu{});
+            else
+                run(std::false_type{}, Prelu{});
+            return;
+        }
+    }
+    if constexpr (EPI != kEpiPrelu) {
+        if (a.residual) {
+            if (general_shift)
+                run(std::true_type{}, General{});
+            else
+                run(std::true_type{}, Fast{});
+        } else {
+            if (general_shift)
+                run(std::false_type{}, General{});
+            else
+                run(std::false_type{}, Fast{});
+        }
     }
 }
 
-template <int NT, bool KS1, int XMODE>
+template <int NT, bool KS1, int XMODE, int EPI>
 __global__ __launch_bounds__(256, (NT <= 7 ? 2 : 1)) void pw_rows_kernel(const PwArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    pw_rows_body<NT, KS1, XMODE>(a, logical_block_id(), lds_raw);
+    pw_rows_body<NT, KS1, XMODE, 4, EPI>(a, logical_block_id(), lds_raw);
 }
 
 // ---- several independent layers in one launch -------------------------------------------------
@@ -314,11 +351,11 @@ using PwBatchFn = void (*)(PwBatchArgs);
 // Bodies pw_bigbatch_kernel carries (the plans the library picks for the large layers at the head
 // of MobileNetV2); -1 if this plan is not among them.  Defined in prom_pw_big.hip.
 int pw_big_body_id(int nt, int pt, int xmode, bool ks1, bool fullw, int row_waves);
-PwBatchFn pw_bigbatch_fn();
+PwBatchFn pw_bigbatch_fn(bool any_prelu);
 size_t pw_big_body_lds(int body, const PwArgs &a);
 
 // Defined in prom_pw_rows.hip: the instantiation for NT in 1..6 and load width 16 or 8, or nullptr.
-PwKernelFn pw_rows_select(int nt, bool ks1, int xmode);
+PwKernelFn pw_rows_select(int nt, bool ks1, int xmode, bool prelu);
 constexpr int kRowsMaxNT = 6;
 
 }  // namespace prom

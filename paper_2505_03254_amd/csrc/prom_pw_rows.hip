@@ -3,21 +3,21 @@
 
 namespace prom {
 
-template <int NT> static PwKernelFn rows_pick(bool ks1, int xmode)
+template <int NT, int EPI> static PwKernelFn rows_pick_e(bool ks1, int xmode)
 {
-    if (xmode == 16) return ks1 ? &pw_rows_kernel<NT, true, 16> : &pw_rows_kernel<NT, false, 16>;
-    return ks1 ? &pw_rows_kernel<NT, true, 8> : &pw_rows_kernel<NT, false, 8>;
+    if (xmode == 16) return ks1 ? &pw_rows_kernel<NT, true, 16, EPI> : &pw_rows_kernel<NT, false, 16, EPI>;
+    return ks1 ? &pw_rows_kernel<NT, true, 8, EPI> : &pw_rows_kernel<NT, false, 8, EPI>;
 }
 
-PwKernelFn pw_rows_select(int nt, bool ks1, int xmode)
+PwKernelFn pw_rows_select(int nt, bool ks1, int xmode, bool prelu)
 {
     switch (nt) {
-    case 1: return rows_pick<1>(ks1, xmode);
-    case 2: return rows_pick<2>(ks1, xmode);
-    case 3: return rows_pick<3>(ks1, xmode);
-    case 4: return rows_pick<4>(ks1, xmode);
-    case 5: return rows_pick<5>(ks1, xmode);
-    case 6: return rows_pick<6>(ks1, xmode);
+    case 1: return prelu ? rows_pick_e<1, kEpiPrelu>(ks1, xmode) : rows_pick_e<1, kEpiPlain>(ks1, xmode);
+    case 2: return prelu ? rows_pick_e<2, kEpiPrelu>(ks1, xmode) : rows_pick_e<2, kEpiPlain>(ks1, xmode);
+    case 3: return prelu ? rows_pick_e<3, kEpiPrelu>(ks1, xmode) : rows_pick_e<3, kEpiPlain>(ks1, xmode);
+    case 4: return prelu ? rows_pick_e<4, kEpiPrelu>(ks1, xmode) : rows_pick_e<4, kEpiPlain>(ks1, xmode);
+    case 5: return prelu ? rows_pick_e<5, kEpiPrelu>(ks1, xmode) : rows_pick_e<5, kEpiPlain>(ks1, xmode);
+    case 6: return prelu ? rows_pick_e<6, kEpiPrelu>(ks1, xmode) : rows_pick_e<6, kEpiPlain>(ks1, xmode);
     default: return nullptr;
     }
 }

@@ -34,11 +34,17 @@
 
 namespace prom {
 
+// Which epilogues a kernel body carries: the plain forms, the PReLU form, or both (shared launches
+// that hold layers of both kinds).  A body is compiled per kind because the registers of a kernel
+// are those of its hungriest path.
+constexpr int kEpiPlain = 0, kEpiPrelu = 1, kEpiBoth = 2;
+
 struct PwArgs {
     const int8_t *x;
     const uint32_t *wq;
     const int32_t *bias;
     const int32_t *mult;
+    const int32_t *mult_neg;  // PReLU: multiplier for acc + bias < 0, or nullptr
     const int32_t *shift;
     const int8_t *residual;
     int8_t *y;
@@ -87,15 +93,16 @@ __device__ __forceinline__ v4i decode_word(uint32_t word)
 }
 
 // Decode the chunk's weights into LDS fragments frag[NT][KS][64 lanes] and the chunk's
-// requantisation parameters into lpar[NT][4 g][4 r] = (C lo, C hi, mult, shift).  Ends with
-// the workgroup barrier that publishes both.
+// requantisation parameters into lpar[NT][4 g][4 r] = (C lo, C hi, mult, shift), or
+// (bias, mult, mult_neg, shift) for a PReLU layer.  Ends with the workgroup barrier that
+// publishes both.
 template <int NT, bool WITH_PARAMS>
-__device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar)
+__device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar, bool prelu)
 {
     const int tid = threadIdx.x;
     const int KS = a.KS, Nc = a.Nc;
     const int nfrag = NT * KS * 64;
-    int pb = 0, pm = 0, ps = 1;
+    int pb = 0, pm = 0, pn = 0, ps = 1;
     const bool ptid = WITH_PARAMS && tid < NT * 16;
     if (ptid) {
         const int c = cbase + chan_of<NT>(tid >> 4, (tid >> 2) & 3, tid & 3);
@@ -103,6 +110,7 @@ __device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *f
             pb = a.bias[c];
             pm = a.mult[c];
             ps = a.shift[c];
+            if (prelu) pn = a.mult_neg[c];
         }
     }
     constexpr int U = 16;  // words in flight per thread
@@ -128,26 +136,8 @@ __device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *f
             if (idx < nfrag) frag[idx] = decode_word(word[q]);
         }
     }
-    if (ptid) {
-        const long long C = (long long)pb * pm + (1LL << (30 + ps));
-        lpar[tid] = v4i{(int)(uint32_t)C, (int)(C >> 32), pm, ps};
-    }
+    if (ptid) lpar[tid] = requant_params(pb, pm, pn, ps, prelu);
     __syncthreads();
-}
-
-// t = acc*mult + C; q = t >> (31 + shift); clamp to [lo, hi].  pr = (C lo, C hi, mult, s) with
-// s = shift-1 when !GENERAL (the caller guarantees shift >= 1) and s = shift when GENERAL.
-template <bool GENERAL>
-__device__ __forceinline__ int requant_i64(int accv, const v4i &pr, int lo, int hi)
-{
-    const long long C = (long long)(((unsigned long long)(uint32_t)pr[1] << 32) | (uint32_t)pr[0]);
-    const long long t = (long long)accv * (long long)pr[2] + C;
-    int q;
-    if constexpr (GENERAL)
-        q = (int)(t >> 31) >> pr[3];
-    else
-        q = (int)(t >> 32) >> pr[3];
-    return med3_i32(q, lo, hi);
 }
 
 // XCD-aware logical workgroup id: consecutive hardware ids go round-robin over the 8 XCDs;
@@ -184,9 +174,11 @@ constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled
 //          conditions, compile-time staging geometry).
 // ============================================================================================
 // `lid` is the workgroup's logical id within this layer's grid (see logical_block_id).
-template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>()>
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>(), int EPI = kEpiPlain>
 __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
+    // PReLU layer?  Known at compile time unless the body carries both kinds of epilogue.
+    const bool prelu = EPI == kEpiPrelu || (EPI == kEpiBoth && a.mult_neg != nullptr);
     constexpr int NI = (NT + 3) / 4;  // 16-byte store instructions per staged tile
     const int KS = KS1 ? 1 : a.KS;
     v4i *frag = reinterpret_cast<v4i *>(lds_raw);  // [NT][KS][64 lanes] decoded A operands
@@ -241,7 +233,7 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
     v4i ring[D][PT];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
-    stage_weights<NT, true>(a, cbase, frag, lpar);
+    stage_weights<NT, true>(a, cbase, frag, lpar, prelu);
 
     // per-lane parameters: 4 channels per tile slot.  The lanes of a wavefront hold every channel
     // of the chunk between them, so a wavefront can see by itself whether any shift is 0 and
@@ -256,7 +248,7 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
             par[t][r] = lpg[t * 16 + r];
             sh0 |= par[t][r][3] == 0;
         }
-    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+    const bool general_shift = prelu || __builtin_amdgcn_ballot_w64(sh0) != 0;
     if (!general_shift) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
@@ -302,13 +294,29 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
     // ---- main loop: D ring slots per round, straight-line.  Refills past the end of this
     // wavefront's work read zeros (their offsets are beyond the tensor) and are never used.
     // The last total_steps % D steps run one at a time on slot 0 with the ring rotated down.
-    // The loop is instantiated per (residual, general shift) so that its body has no branch on
+    // The loop is instantiated per (residual, epilogue form) so that its body has no branch on
     // either. ------------------------------------------------------------------------------------
-    auto run = [&](auto has_res_tag, auto general_tag) {
+    auto run = [&](auto has_res_tag, auto mode_tag) {
         constexpr bool HAS_RES = decltype(has_res_tag)::value;
-        constexpr bool GENERAL = decltype(general_tag)::value;
+        constexpr int MODE = decltype(mode_tag)::value;
         v4i acc[PT][NT];
         const v4i zero4 = {0, 0, 0, 0};
+        // PReLU: the parameters per tile as four vectors over the lane's 4 channels.  The biases
+        // are the accumulators' start value (a register quad the first MFMA of a group reads
+        // as its C operand), so that the sign of the accumulator is the sign that selects the
+        // multiplier.
+        v4i cinit[NT], pmul[NT], pneg[NT], pshift[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if constexpr (MODE == 2) {
+                cinit[t] = v4i{par[t][0][0], par[t][1][0], par[t][2][0], par[t][3][0]};
+                pmul[t] = v4i{par[t][0][1], par[t][1][1], par[t][2][1], par[t][3][1]};
+                pneg[t] = v4i{par[t][0][2], par[t][1][2], par[t][2][2], par[t][3][2]};
+                pshift[t] = v4i{par[t][0][3], par[t][1][3], par[t][2][3], par[t][3][3]};
+            } else {
+                cinit[t] = zero4;
+            }
+        }
         int ck = 0;
         auto step = [&](v4i(&slot)[PT], auto refill_tag) {
             constexpr bool REFILL = decltype(refill_tag)::value;
@@ -323,7 +331,7 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
                     const v4i wfrag = fk[t * KS * 64];
 #pragma unroll
                     for (int p = 0; p < PT; ++p)
-                        acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, slot[p], zero4, 0, 0, 0);
+                        acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag, slot[p], cinit[t], 0, 0, 0);
                 }
             } else {
 #pragma unroll
@@ -364,7 +372,13 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
                                 int v[4];
 #pragma unroll
                                 for (int r = 0; r < 4; ++r)
-                                    v[r] = requant_i64<GENERAL>(acc[p][t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                    {
+                                    if constexpr (MODE == 2)
+                                        v[r] = requant_prelu_s(acc[p][t0 + tt][r], pmul[t0 + tt][r], pneg[t0 + tt][r],
+                                                               pshift[t0 + tt][r], lo, hi);
+                                    else
+                                        v[r] = requant_mode<MODE>(acc[p][t0 + tt][r], par[t0 + tt][r], lo, hi);
+                                }
                                 if constexpr (HAS_RES) {
 #pragma unroll
                                     for (int r = 0; r < 4; ++r)
@@ -416,31 +430,45 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
         }
     };
 
-    if (a.residual) {
-        if (general_shift)
-            run(std::true_type{}, std::true_type{});
-        else
-            run(std::true_type{}, std::false_type{});
-    } else {
-        if (general_shift)
-            run(std::false_type{}, std::true_type{});
-        else
-            run(std::false_type{}, std::false_type{});
+    using Fast = std::integral_constant<int, 0>;
+    using General = std::integral_constant<int, 1>;
+    using Prelu = std::integral_constant<int, 2>;
+    if constexpr (EPI != kEpiPlain) {
+        if (prelu) {
+            if (a.residual)
+                run(std::true_type{}, Prelu{});
+            else
+                run(std::false_type{}, Prelu{});
+            return;
+        }
+    }
+    if constexpr (EPI != kEpiPrelu) {
+        if (a.residual) {
+            if (general_shift)
+                run(std::true_type{}, General{});
+            else
+                run(std::true_type{}, Fast{});
+        } else {
+            if (general_shift)
+                run(std::false_type{}, General{});
+            else
+                run(std::false_type{}, Fast{});
+        }
     }
 }
 
-template <int NT, int PT, int XMODE, bool KS1, bool FULLW>
-__global__ __launch_bounds__(256, (NT * PT <= 7 ? 2 : 1)) void pw_stream_kernel(const PwArgs a)
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int EPI>
+__global__ __launch_bounds__(256, (NT * PT <= (EPI == kEpiPlain ? 7 : 6) ? 2 : 1)) void pw_stream_kernel(const PwArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    pw_stream_body<NT, PT, XMODE, KS1, FULLW>(a, logical_block_id(), lds_raw);
+    pw_stream_body<NT, PT, XMODE, KS1, FULLW, ring_depth<PT>(), EPI>(a, logical_block_id(), lds_raw);
 }
 
 using PwKernelFn = void (*)(const PwArgs);
 
 // One translation unit per NT instantiates the streaming kernel (prom_pw_inst.hip) and exports
 // its selector; returns nullptr for a combination that is not compiled.
-template <int NT> PwKernelFn pw_stream_select(int pt, int xmode, bool ks1, bool fullw);
+template <int NT> PwKernelFn pw_stream_select(int pt, int xmode, bool ks1, bool fullw, bool prelu);
 
 constexpr int kMaxNT = 10;
 
