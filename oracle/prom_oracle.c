@@ -283,6 +283,60 @@ int oracle_dw_conv_prelu(const int8_t *x, int n, int h, int wd, int c,
     return 0;
 }
 
+/* Grouped 3x3 conv, pad 1, stride 1 or 2, NHWC, as many output as input channels, groups of
+ * `gs` channels (RegNet / ResNeXt use group sizes above one where MobileNetV2 has the depthwise
+ * conv: paper, Section 2; its weights W[cout][cin per group][K][K] are 8-bit with one scale per
+ * output channel, Section 3.1 "Depthwise Convolutions", Eq. 4-5).  Output channel ch belongs to
+ * group ch / gs and sees input channels (ch / gs) * gs + 0 .. gs-1.  Weights [3][3][c][gs]:
+ * w[(i*3 + j)*c + ch][k] multiplies input channel (ch / gs) * gs + k at tap (i, j).
+ * acc_out (optional) receives the raw sums; y (optional) the requantised bytes, with the PReLU
+ * form when mult_neg is given. */
+int oracle_gconv3x3(const int8_t *x, int n, int h, int wd, int c,
+                    const int8_t *w /* [3][3][c][gs] */, int gs, int stride,
+                    const int32_t *bias, const int32_t *mult, const int32_t *mult_neg /* or NULL */,
+                    const int32_t *shift, int32_t act_min, int32_t act_max,
+                    int32_t *acc_out /* [n][ho][wo][c] or NULL */, int8_t *y /* [n][ho][wo][c] or NULL */)
+{
+    if (!x || !w || (!y && !acc_out)) return -1;
+    if (y && (!bias || !mult || !shift)) return -1;
+    if (n <= 0 || h <= 0 || wd <= 0 || c <= 0 || gs <= 0 || c % gs != 0) return -1;
+    if (stride != 1 && stride != 2) return -1;
+    int ho = (h + 2 - 3) / stride + 1;
+    int wo = (wd + 2 - 3) / stride + 1;
+    int64_t rows = (int64_t)n * ho;
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < rows; ++row) {
+        int in_ = (int)(row / ho);
+        int oy = (int)(row % ho);
+        for (int ox = 0; ox < wo; ++ox) {
+            for (int ch = 0; ch < c; ++ch) {
+                int first = (ch / gs) * gs; /* first input channel of the group */
+                int64_t acc = 0;
+                for (int i = 0; i < 3; ++i) {
+                    for (int j = 0; j < 3; ++j) {
+                        int iy = oy * stride + i - 1;
+                        int ix = ox * stride + j - 1;
+                        if (iy < 0 || iy >= h || ix < 0 || ix >= wd) continue; /* zero pad */
+                        for (int k = 0; k < gs; ++k) {
+                            int64_t xv = x[(((int64_t)in_ * h + iy) * wd + ix) * c + first + k];
+                            int64_t wv = w[((int64_t)(i * 3 + j) * c + ch) * gs + k];
+                            acc += xv * wv;
+                        }
+                    }
+                }
+                int64_t o = (((int64_t)in_ * ho + oy) * wo + ox) * c + ch;
+                if (acc_out) acc_out[o] = (int32_t)acc;
+                if (y)
+                    y[o] = mult_neg ? finish_prelu(acc, bias[ch], mult[ch], mult_neg[ch], shift[ch],
+                                                   act_min, act_max, 0, 0)
+                                    : finish(acc, bias[ch], mult[ch], shift[ch], act_min, act_max, 0, 0);
+            }
+        }
+    }
+    return 0;
+}
+
 /* Inverted-residual block: pointwise expand -> depthwise 3x3 -> pointwise project
  * (+ saturating add of the block input when add_residual).  It is the three functions
  * above chained through caller-provided intermediates t1 [n][h][w][chid] and

@@ -60,6 +60,10 @@ def _load():
         lib.oracle_dw_conv_prelu.argtypes = [_i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                              _i8p, ctypes.c_int, _i32p, _i32p, _i32p, _i32p,
                                              ctypes.c_int32, ctypes.c_int32, _i8p]
+        lib.oracle_gconv3x3.restype = ctypes.c_int
+        lib.oracle_gconv3x3.argtypes = [_i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                        _i8p, ctypes.c_int, ctypes.c_int, _i32p, _i32p, _i32p, _i32p,
+                                        ctypes.c_int32, ctypes.c_int32, _i32p, _i8p]
         lib.oracle_block.restype = ctypes.c_int
         lib.oracle_block.argtypes = ([_i8p] + [ctypes.c_int] * 7 +
                                      [_i8p, _i32p, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32] * 3 +
@@ -172,6 +176,48 @@ def dw_conv(x, weight, stride: int, bias, mult, shift, act_min: int, act_max: in
     if rc:
         raise ValueError(f"oracle_dw_conv failed: {rc}")
     return y
+
+
+def _gconv(x, weight, stride, bias, mult, mult_neg, shift, act_min, act_max, raw):
+    x = _i8(x)
+    weight = _i8(weight)
+    n, h, w, c = x.shape
+    assert weight.ndim == 4 and weight.shape[:3] == (3, 3, c), weight.shape
+    gs = weight.shape[3]
+    ho = (h + 2 - 3) // stride + 1
+    wo = (w + 2 - 3) // stride + 1
+    null32 = ctypes.cast(None, _i32p)
+    if raw:
+        acc = np.empty((n, ho, wo, c), dtype=np.int32)
+        rc = _load().oracle_gconv3x3(_p8(x), n, h, w, c, _p8(weight), gs, stride, null32, null32, null32,
+                                     null32, 0, 0, _p32(acc), None)
+        out = acc
+    else:
+        bias, mult, shift = _i32(bias), _i32(mult), _i32(shift)
+        assert bias.shape == mult.shape == shift.shape == (c,)
+        mn = null32
+        if mult_neg is not None:
+            mult_neg = _i32(mult_neg)
+            assert mult_neg.shape == (c,)
+            mn = _p32(mult_neg)
+        y = np.empty((n, ho, wo, c), dtype=np.int8)
+        rc = _load().oracle_gconv3x3(_p8(x), n, h, w, c, _p8(weight), gs, stride, _p32(bias), _p32(mult), mn,
+                                     _p32(shift), act_min, act_max, null32, _p8(y))
+        out = y
+    if rc:
+        raise ValueError(f"oracle_gconv3x3 failed: {rc}")
+    return out
+
+
+def gconv3x3(x, weight, stride: int, bias, mult, shift, act_min: int, act_max: int,
+             mult_neg=None) -> np.ndarray:
+    """Grouped 3x3 conv: x int8 [n,h,w,c]; weight int8 [3,3,c,gs] -> int8 [n,ho,wo,c] (pad 1)."""
+    return _gconv(x, weight, stride, bias, mult, mult_neg, shift, act_min, act_max, False)
+
+
+def gconv3x3_accum(x, weight, stride: int) -> np.ndarray:
+    """Raw int32 sums of the grouped 3x3 conv."""
+    return _gconv(x, weight, stride, None, None, None, None, 0, 0, True)
 
 
 def block(x, expand, dw, project, stride: int, add_residual: bool):

@@ -7,7 +7,7 @@ tests and the HIP path's tests/bench take their inputs from here.
 """
 from .generators import (  # noqa: F401
     SplitMix64, PwLayerInputs, DwLayerInputs, BlockInputs,
-    make_pw_layer, make_dw_layer, make_block, float_conv_weights, prelu_mult_neg, CONFIG_SEED_BASE,
+    make_pw_layer, make_dw_layer, make_block, make_gconv_layer, GconvLayerInputs, float_conv_weights, prelu_mult_neg, CONFIG_SEED_BASE,
 )
 from .mobilenetv2 import (  # noqa: F401
     PwShape, DwShape, BlockShape, mobilenetv2_pointwise_layers, mobilenetv2_depthwise_layers,

@@ -201,6 +201,40 @@ def make_dw_layer(seed: int, n: int, h: int, w: int, c: int, stride: int = 1, *,
                          act_window[0], act_window[1])
 
 
+@dataclass
+class GconvLayerInputs:
+    n: int
+    h: int
+    w: int
+    c: int
+    gs: int
+    stride: int
+    x: np.ndarray            # int8 [n,h,w,c]
+    weight: np.ndarray       # int8 [3,3,c,gs]
+    bias: np.ndarray
+    mult: np.ndarray
+    shift: np.ndarray
+    act_min: int
+    act_max: int
+
+
+def make_gconv_layer(seed: int, n: int, h: int, w: int, c: int, gs: int, stride: int = 1, *,
+                     act_window: Tuple[int, int] = (0, 127), signed_x: bool = False,
+                     shift_range: Tuple[int, int] = (10, 16), make_x: bool = True) -> GconvLayerInputs:
+    """A grouped 3x3 layer (groups of gs channels, as many outputs as inputs): 8-bit weights
+    uniform in [-127, 127] like the depthwise layers."""
+    root = SplitMix64(seed)
+    if make_x:
+        mask = 0xFF if signed_x else 0x7F
+        x = root.substream(1).bytes_masked(n * h * w * c, mask).view(np.int8).reshape(n, h, w, c)
+    else:
+        x = np.empty((0,), dtype=np.int8)
+    weight = root.substream(2).uniform_int(9 * c * gs, -127, 127).astype(np.int8).reshape(3, 3, c, gs)
+    bias, mult, shift = _requant_params(root.substream(3), c, shift_range)
+    return GconvLayerInputs(n, h, w, c, gs, stride, x, weight, bias, mult, shift,
+                            act_window[0], act_window[1])
+
+
 def make_block(seed: int, n: int, h: int, w: int, cin: int, t: int, cout: Optional[int] = None,
                stride: int = 1, *, signed_x: bool = False, p_zero: float = 0.5,
                expand_shift: Tuple[int, int] = (8, 14), dw_shift: Tuple[int, int] = (8, 14),
