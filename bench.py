@@ -592,6 +592,40 @@ def extra_legs(P, torch, dev, batch, log):
                           "gbs_incl_intermediates": round((io_bytes + mid_bytes) / dt / 1e9, 1)}
     log(f"[bench] 17-block chain: {dt * 1e6:.1f} us per pass, fused: {', '.join(fused)}; "
         f"{io_bytes / 1e6:.0f} MB block inputs+outputs, {mid_bytes / 1e6:.0f} MB intermediates of unfused blocks")
+
+    # grouped 3x3 convolutions of RegNetX-400MF and ResNeXt-50 32x4d at the same batch
+    from workloads import make_gconv_layer, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers
+    for key, shapes in (("gconv_regnetx_400mf", regnetx_400mf_grouped_layers()),
+                        ("gconv_resnext50_32x4d", resnext50_32x4d_grouped_layers())):
+        gl = []
+        for i, g in enumerate(shapes):
+            G = make_gconv_layer(SEED + 3000 + i, 1, 4, 4, g.c, g.gs, g.stride)
+            x = torch.randint(0, 128, (batch, g.hw_in, g.hw_in, g.c), dtype=torch.int8, device=dev)
+            w = torch.from_numpy(G.weight).to(dev)
+            wf = torch.from_numpy(P.prom_gconv_pack(G.weight)).to(dev)  # weights prepared once per layer
+            rq = P.Requant(torch.from_numpy(G.bias).to(dev), torch.from_numpy(G.mult).to(dev),
+                           torch.from_numpy(G.shift).to(dev), 0, 127)
+            ho = (g.hw_in - 1) // g.stride + 1
+            y = torch.empty((batch, ho, ho, g.c), dtype=torch.int8, device=dev)
+            gl.append((g, x, (w, wf), rq, y, batch * g.c * (g.hw_in ** 2 + ho ** 2), batch * ho * ho * g.c * 9 * g.gs))
+        for _ in range(2):
+            for g, x, (w, wf), rq, y, _b, _m in gl:
+                P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(5):
+            for g, x, (w, wf), rq, y, _b, _m in gl:
+                P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
+        torch.cuda.synchronize()
+        dg = (time.perf_counter() - tg0) / 5
+        gbytes = sum(b for *_, b, _m in gl)
+        gmacs = sum(m for *_, m in gl)
+        out[key] = {"layers": len(gl), "us": round(dg * 1e6, 1), "gbs": round(gbytes / dg / 1e9, 1),
+                    "frac_hbm_roofline": round(gbytes / dg / 1e9 / HBM_PEAK_GBS, 4),
+                    "useful_gmac_per_s": round(gmacs / dg / 1e9, 1)}
+        log(f"[bench] {key}: {len(gl)} layers, {dg * 1e6:.1f} us, {gbytes / dg / 1e9:.0f} GB/s, "
+            f"{gmacs / dg / 1e12:.1f} Tmac/s useful")
+        del gl
     return out
 
 

@@ -227,6 +227,41 @@ int prom_dw_conv(const int8_t *x, int n, int h, int w, int c,
                  const int8_t *w_dw, int stride, const prom_requant_t *rq,
                  int8_t *y, void *stream);
 
+/* ---- grouped 3x3 convolution, pad 1, stride 1 or 2 --------------------------------------
+ * RegNet and ResNeXt have group sizes above one where MobileNetV2 has the depthwise convolution
+ * (paper Section 2); the weights are 8-bit with one scale per output channel like the depthwise
+ * ones (Section 3.1, Eq. 4-5).  As many output as input channels; output channel ch belongs to
+ * group ch / group_size and sees that group's input channels:
+ *   acc[n][oy][ox][ch] = sum_{i,j in 0..2} sum_{k < group_size}
+ *         x[n][oy*stride+i-1][ox*stride+j-1][(ch / group_size) * group_size + k] * w_g[i][j][ch][k]
+ * with x = 0 outside the image, then the requantisation above (plain or PReLU).
+ *   x dev int8 [n][h][w][c];  w_g dev int8 [3][3][c][group_size];  y dev int8 [n][ho][wo][c];
+ *   c % group_size == 0 (PROM_EINVAL otherwise); group_size <= 4096; y must not overlap x or w_g.
+ * group_size 4, 8, 16, 32 or 64 (c % 4 == 0, 4-byte aligned tensors below 2 GiB, 16-byte aligned
+ * parameter arrays, w <= 190) runs on the matrix cores; any other multiple of 4 on a tiled
+ * vector-ALU kernel, group_size 1 is prom_dw_conv, anything else a slow one-thread-per-output
+ * kernel.
+ *   w_frag (optional, may be NULL): the same weights in the operand order of the matrix-core
+ *   kernel, prepared once per layer with prom_gconv_pack (weights are fixed at inference, paper
+ *   Figure 12) and copied to the device, 16-byte aligned; with it a workgroup starts with a plain
+ *   copy instead of decoding w_g.  It must describe the same weights as w_g (not checked); it is
+ *   ignored by the kernels that do not use it, and PROM_EINVAL if prom_gconv_frag_size(c,
+ *   group_size) is 0. */
+int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c,
+                  const int8_t *w_g, const void *w_frag, int group_size, int stride,
+                  const prom_requant_t *rq, int8_t *y, void *stream);
+
+/* Bytes of the prepared form of prom_gconv_pack; 0 if the matrix-core kernel does not take this
+ * layer (group_size not 4, 8, 16, 32 or 64, c % 4 != 0 or c % group_size != 0). */
+size_t prom_gconv_frag_size(int c, int group_size);
+
+/* Host to host: w_host[3][3][c][group_size] -> frag_host, laid out
+ * [block of 64 channels][tile t: 4][tap: 9][lane: 64][16 bytes]: lane (i = lane & 15, kg = lane >> 4)
+ * of tile t holds, for output channel oc = 64*block + 16*(i >> 2) + 4*t + (i & 3), the weights on
+ * input channels 64*block + 16*kg + 0..15 (those of oc's group, zero elsewhere).
+ * PROM_EUNSUPPORTED if prom_gconv_frag_size is 0, PROM_EWORKSPACE if frag_bytes is too small. */
+int prom_gconv_pack(const int8_t *w_host, int c, int group_size, void *frag_host, size_t frag_bytes);
+
 /* ---- inverted-residual block ------------------------------------------------------------
  * pointwise expand (cin -> chid, rq_expand) -> depthwise 3x3 (stride, rq_dw) ->
  * pointwise project (chid -> cout, rq_project); if add_residual (requires stride == 1 and

@@ -78,6 +78,12 @@ def load_library():
     lib.prom_pw_accum_i32.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp]
     lib.prom_dw_conv.restype = ci
     lib.prom_dw_conv.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, vp]
+    lib.prom_gconv3x3.restype = ci
+    lib.prom_gconv3x3.argtypes = [vp, ci, ci, ci, ci, vp, vp, ci, ci, ctypes.POINTER(_RequantC), vp, vp]
+    lib.prom_gconv_frag_size.restype = sz
+    lib.prom_gconv_frag_size.argtypes = [ci, ci]
+    lib.prom_gconv_pack.restype = ci
+    lib.prom_gconv_pack.argtypes = [vp, ci, ci, vp, sz]
     lib.prom_block.restype = ci
     lib.prom_block.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
                                vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
@@ -277,6 +283,42 @@ def prom_dw_conv(x, w_dw, stride: int, rq: Requant, y=None, stream=None):
 
 def prom_block_workspace_size(n, h, w, cin, chid, cout, stride) -> int:
     return int(load_library().prom_block_workspace_size(n, h, w, cin, chid, cout, stride))
+
+
+def prom_gconv_frag_size(c: int, group_size: int) -> int:
+    return int(load_library().prom_gconv_frag_size(int(c), int(group_size)))
+
+
+def prom_gconv_pack(w: np.ndarray) -> np.ndarray:
+    """w: int8 [3,3,c,group_size] host array -> the prepared form for the matrix-core kernel
+    (uint8 host array).  Raises PromError(-2) when that kernel does not take the layer."""
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    assert w.ndim == 4 and w.shape[:2] == (3, 3)
+    c, gs = int(w.shape[2]), int(w.shape[3])
+    out = np.zeros(max(prom_gconv_frag_size(c, gs), 1), dtype=np.uint8)
+    _check(load_library().prom_gconv_pack(w.ctypes.data, c, gs, out.ctypes.data, out.size), "prom_gconv_pack")
+    return out
+
+
+def prom_gconv3x3(x, w_g, stride: int, rq: Requant, y=None, stream=None, w_frag=None):
+    """Grouped 3x3 conv: x int8 [n,h,w,c] device; w_g int8 [3,3,c,group_size] device;
+    w_frag: optional device copy of prom_gconv_pack(w_g)."""
+    import torch
+    _dev_i8(x, "x")
+    _dev_i8(w_g, "w_g")
+    n, h, w, c = x.shape
+    if w_g.dim() != 4 or tuple(w_g.shape[:3]) != (3, 3, c):
+        raise ValueError("w_g must have the shape [3, 3, c, group_size]")
+    gs = int(w_g.shape[3])
+    ho, wo = (h - 1) // stride + 1, (w - 1) // stride + 1
+    if y is None:
+        y = torch.empty((n, ho, wo, c), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    rqc = rq._c()
+    _check(load_library().prom_gconv3x3(x.data_ptr(), n, h, w, c, w_g.data_ptr(),
+                                        None if w_frag is None else w_frag.data_ptr(), gs, int(stride),
+                                        ctypes.byref(rqc), y.data_ptr(), _stream_ptr(stream)), "prom_gconv3x3")
+    return y
 
 
 def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand: Requant,

@@ -1,0 +1,543 @@
+// int8 grouped 3x3 convolution (pad 1, stride 1 or 2), NHWC, as many output as input channels,
+// groups of gs channels, with the integer requantisation epilogue (plain or PReLU).  RegNet and
+// ResNeXt have this layer where MobileNetV2 has the depthwise convolution (paper Section 2); its
+// weights are 8-bit with one scale per output channel (Section 3.1, Eq. 4-5).
+//
+// gconv_kernel_v4: a thread owns 4 consecutive output channels (they lie in one group, gs being
+// a multiple of 4) of one output column and 4 consecutive output rows; lanes run over channels,
+// then columns.  For each of the 3 kernel columns it loads the gs input bytes of its group (in
+// chunks of up to 16) for the 6 (stride 1) or 9 (stride 2) input rows that feed its outputs -- lanes of one group read
+// the same bytes, lanes of neighbouring groups the bytes next to them, so a wavefront's load
+// covers one contiguous run -- and, per kernel row, the 4*gs weight bytes of its 4 channels,
+// which are reused for the 4 output rows.  The input channels of a group are contiguous in both
+// operands, so 4 of them are one v_dot4_i32_i8 with no unpacking: 9*gs/4 instructions per
+// output byte.  From gs = 16 on that is more vector ALU time than the HBM needs for the bytes
+// (36 instructions per output byte at gs = 16), i.e. the kernel is ALU bound there.
+#include "prom.h"
+#include "prom_device.h"
+#include "prom_launch.h"
+
+#include <mutex>
+#include <type_traits>
+
+namespace prom {
+
+struct GconvArgs {
+    const int8_t *x;
+    const int8_t *w;  // [3][3][C][gs]
+    const v4i *wfrag;  // the same weights in MFMA operand order (prom_gconv_pack), or nullptr
+    const int32_t *bias;
+    const int32_t *mult;
+    const int32_t *mult_neg;  // or nullptr
+    const int32_t *shift;
+    int8_t *y;
+    int N, H, W, C, Ho, Wo, stride, gs;
+    int lo, hi;
+    long long total;  // outputs (generic kernel)
+};
+
+// n consecutive dwords at byte offset voff (+ scalar offset soff) of a buffer, with the widest
+// loads n allows.  Out-of-range dwords read as zero.
+template <int N>
+__device__ __forceinline__ void load_dwords(const __amdgpu_buffer_rsrc_t r, int voff, int soff, uint32_t (&out)[N])
+{
+    constexpr int kOob = 0x7ffff000;
+    if constexpr (N % 4 == 0) {
+#pragma unroll
+        for (int k = 0; k < N; k += 4) {
+            const v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, min((unsigned)voff + 4u * k, (unsigned)kOob), soff, 0);
+            out[k] = v[0]; out[k + 1] = v[1]; out[k + 2] = v[2]; out[k + 3] = v[3];
+        }
+    } else if constexpr (N % 2 == 0) {
+#pragma unroll
+        for (int k = 0; k < N; k += 2) {
+            const v2i v = __builtin_amdgcn_raw_buffer_load_b64(r, min((unsigned)voff + 4u * k, (unsigned)kOob), soff, 0);
+            out[k] = v[0]; out[k + 1] = v[1];
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+            out[k] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, min((unsigned)voff + 4u * k, (unsigned)kOob), soff, 0);
+    }
+}
+
+// C % 4 == 0, gs % 4 == 0, 4-byte aligned x / y / w, 16-byte aligned parameters, one image and
+// the weights below 2^31 bytes.  The input channels of a group are taken in chunks of 4*KC
+// (KC dwords per load); ONE: the group is a single chunk (gs == 4*KC), and the weights of the
+// lane's 4 channels are then one contiguous run.  The loops over the kernel columns and the
+// chunks stay loops: unrolled, the compiler issues every load of the thread up front and needs
+// several hundred registers.
+// Grid: x over Wo * C/4 (channels fastest, then output columns), y = group of 4 output rows,
+// z = image.  Row and image indices are uniform per workgroup; the image is addressed through a
+// buffer resource of its own, so rows above and below it read as zero and output rows below it
+// are dropped, and a column outside the image gets an offset beyond the resource.
+template <int S, int KC, bool ONE>
+__global__ __launch_bounds__(256, (KC == 4 ? 3 : 4)) void gconv_kernel_v4(const GconvArgs a)
+{
+    constexpr int NPIX = S == 1 ? 6 : 9;  // input rows feeding 4 output rows
+    constexpr int kFlags = 0x00020000;
+    constexpr int kOob = 0x7ffff000;
+    const int GS = ONE ? 4 * KC : a.gs;
+    const int nchunk = ONE ? 1 : GS / (4 * KC);
+    const int C4 = a.C >> 2;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.Wo * C4) return;
+    const int ox = t / C4;
+    const int c = (t - ox * C4) * 4;  // the lane's first output channel
+    const int first = (c / GS) * GS;  // first input channel of its group
+    const int oy0 = blockIdx.y * 4;
+    const int n = blockIdx.z;
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.x) + (long long)n * a.H * a.W * a.C, 0, a.H * a.W * a.C, kFlags);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(a.y + (long long)n * a.Ho * a.Wo * a.C, 0, a.Ho * a.Wo * a.C, kFlags);
+    const __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.w), 0, 9 * a.C * GS, kFlags);
+
+    const int rowbytes = a.W * a.C;
+    const int iy0 = oy0 * S - 1;
+    int acc[4][4];  // [output row][channel]
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[o][r] = 0;
+
+#pragma nounroll
+    for (int jx = 0; jx < 3; ++jx) {
+        const int ix = ox * S + jx - 1;
+        const int coff0 = (ix >= 0 && ix < a.W) ? ix * a.C + first : kOob;
+#pragma nounroll
+        for (int kc = 0; kc < nchunk; ++kc) {
+            const int coff = (int)min((unsigned)coff0 + (unsigned)(kc * 4 * KC), (unsigned)kOob);
+            uint32_t v[NPIX][KC];
+#pragma unroll
+            for (int p = 0; p < NPIX; ++p) load_dwords<KC>(rx, coff, (iy0 + p) * rowbytes, v[p]);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                uint32_t wr[4][KC];  // [channel r][k]
+                const int wrow = (i * 3 + jx) * a.C * GS;  // uniform
+                if constexpr (ONE) {
+                    uint32_t flat[4 * KC];
+                    load_dwords<4 * KC>(rw, c * GS, wrow, flat);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int k = 0; k < KC; ++k) wr[r][k] = flat[r * KC + k];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) load_dwords<KC>(rw, (c + r) * GS + kc * 4 * KC, wrow, wr[r]);
+                }
+#pragma unroll
+                for (int o = 0; o < 4; ++o)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int k = 0; k < KC; ++k)
+                            acc[o][r] = __builtin_amdgcn_sdot4((int)v[S * o + i][k], (int)wr[r][k], acc[o][r], false);
+            }
+        }
+    }
+
+    const v4i pb = *reinterpret_cast<const v4i *>(a.bias + c);
+    const v4i pm = *reinterpret_cast<const v4i *>(a.mult + c);
+    const v4i ps = *reinterpret_cast<const v4i *>(a.shift + c);
+    v4i pn = {0, 0, 0, 0};
+    const bool prelu = a.mult_neg != nullptr;  // uniform over the launch
+    if (prelu) pn = *reinterpret_cast<const v4i *>(a.mult_neg + c);
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int yoff = ox * a.C + c;
+    const int yrow = a.Wo * a.C;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        int out[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const v4i pr = requant_params(pb[r], pm[r], pn[r], ps[r], prelu);
+            out[r] = prelu ? requant_prelu_i64(acc[o][r], pr, lo, hi) : requant_i64<true>(acc[o][r], pr, lo, hi);
+        }
+        // an output row below the image is beyond the resource and is dropped
+        __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(out[0], out[1], out[2], out[3]), ry, yoff,
+                                              (oy0 + o) * yrow, 0);
+    }
+}
+
+// ---- gconv_mfma_kernel: group sizes 4, 8, 16, 32, 64 on the matrix cores -------------------------
+// A block of 64 output channels only sees the same 64 input channels (the groups divide 64), so
+// per kernel tap the layer is a [64 x 64] block-diagonal int8 matrix applied to the 64 input bytes
+// of the pixel under that tap: 9 k steps of v_mfma_i32_16x16x64_i8, one per tap.  The matrix cores
+// do 64/gs times the necessary multiply-adds and are still far from being the limit; what has to
+// be kept small is the number of times an input byte is fetched, 9 if every tap loads from
+// global memory (measured: the texture addresser, which takes a 16-byte-per-lane load lane by
+// lane, was then 70 % busy and set the time).  So a workgroup stages the input rows of a band of
+// output rows once in LDS (64 channels per pixel, a zero column left and right, zero rows above
+// and below the image), and the B operands of all 9 taps are 16-byte LDS reads at the lane's
+// pixel plus the tap's offset; the block's weights are decoded once per workgroup into LDS
+// fragments (zeros outside the groups) and serve every band the workgroup takes.
+// Tile rows are permuted as in the pointwise kernels: row 4g + r of tile t is channel
+// 16g + 4t + r of the block, so that a lane's 16 outputs of a pixel are 16 contiguous bytes.
+// A wavefront iteration covers PT tiles of 16 consecutive output pixels of the band (in row-major
+// order, so ragged widths waste nothing), a fragment read serving PT MFMAs.
+// Requirements (host): gs in {4, 8, 16, 32, 64}, C % 4 == 0, x and y below 2^31 - 2^24 bytes,
+// 4-byte aligned x / y / w, the band geometry of GconvBand.
+struct GconvBand {
+    int ncb;         // blocks of 64 channels
+    int wgs_per_cb;  // workgroups per channel block
+    int R;           // output rows per band
+    int RI;          // input rows per band = (R-1)*stride + 3
+    int bands;       // bands per image
+    int G;           // images per unit of work (above 1 only when a band is the whole image)
+    int units;       // units of work per channel block
+};
+
+constexpr int kGconvFragBytes = 4 * 9 * 64 * 16;
+constexpr int kGconvParBytes = 64 * 16;
+constexpr int kGconvPieces = 9;  // 16-byte pieces of a staged band per thread
+
+__global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, const GconvBand bd)
+{
+    constexpr int kFlags = 0x00020000;
+    constexpr int kOob = 0x7ffff000;
+    constexpr int PT = 2;
+    constexpr int NK = kGconvPieces;
+    extern __shared__ __align__(16) unsigned char lds[];
+    v4i *frag = reinterpret_cast<v4i *>(lds);                                    // [tile t][tap s][lane]
+    v4i *lpar = reinterpret_cast<v4i *>(lds + kGconvFragBytes);                  // [64] parameters
+    unsigned char *xt = lds + kGconvFragBytes + kGconvParBytes;                  // [G][RI][W+2][64] input band(s)
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15, g = lane >> 4;
+    const int cb = blockIdx.x % bd.ncb;
+    const int wg = blockIdx.x / bd.ncb;
+    const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
+    const int W2 = W + 2;
+    const int cbase = cb * 64;
+    const bool prelu = a.mult_neg != nullptr;
+    const int row_items = W2 * 4;              // 16-byte pieces per staged input row
+    const int img_items = bd.RI * row_items;   // pieces per staged image band
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.N * a.H * W * C, kFlags);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.N * a.Ho * Wo * C, kFlags);
+
+    // Unit of work u: one band of one image, or (small images) the whole of up to G images.
+    struct Unit { int img0, count, ro0, rows_out; };
+    auto unit_of = [&](int u) {
+        Unit q;
+        if (bd.G > 1) {
+            q.img0 = u * bd.G;
+            q.count = min(bd.G, a.N - q.img0);
+            q.ro0 = 0;
+        } else {
+            q.img0 = u / bd.bands;
+            q.count = 1;
+            q.ro0 = (u - q.img0 * bd.bands) * bd.R;
+        }
+        q.rows_out = min(bd.R, a.Ho - q.ro0);
+        return q;
+    };
+    // The band of a unit is fetched into registers, all 16-byte pieces of a thread back to back
+    // (one memory latency per band, not one per row), and written to LDS later: the fetch of the
+    // next unit is in flight while the current one is computed, and the first fetch while the
+    // weights are staged.  Pixels outside the image and channels beyond C are zeros.
+    v4i piece[NK];
+    auto fetch_band = [&](int u) {
+        const Unit q = unit_of(u);
+        const int ri0 = q.ro0 * S - 1;  // first input row (may be -1)
+        const int npiece = q.count * img_items;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+            const int pc = k * 256 + tid;
+            const int gi = pc / img_items;
+            const int rem = pc - gi * img_items;
+            const int row = rem / row_items;
+            const int it = rem - row * row_items;
+            const int col = it >> 2, qd = it & 3;  // staged column 0 is image column -1
+            const int iy = ri0 + row;
+            const bool ok = pc < npiece && iy >= 0 && iy < a.H && col >= 1 && col <= W && cbase + 16 * qd < C;
+            const int off = (((q.img0 + gi) * a.H + iy) * W + col - 1) * C + cbase + 16 * qd;
+            piece[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off : kOob, 0, 0);
+        }
+    };
+    // ---- weights of the block -> MFMA A fragments: a plain copy when the caller has prepared them,
+    // else decoded here ----------------------------------------------------------------------------
+    if (a.wfrag) {
+        const v4i *src = a.wfrag + (long long)cb * (4 * 9 * 64);
+        v4i tmp[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) tmp[k] = src[k * 256 + tid];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) frag[k * 256 + tid] = tmp[k];
+    } else
+    for (int idx = tid; idx < 4 * 9 * 64; idx += 256) {
+        const int l = idx & 63, ts = idx >> 6, s = ts % 9, t = ts / 9;
+        const int i = l & 15, kg = l >> 4;
+        const int oc = cbase + 16 * (i >> 2) + 4 * t + (i & 3);
+        const int gfirst = (oc / GS) * GS;  // first input channel of the output channel's group
+        v4i e = {0, 0, 0, 0};
+        if (oc < C) {
+            const int8_t *wrow = a.w + ((long long)s * C + oc) * GS;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int ic = cbase + 16 * kg + 4 * d;  // 4 input channels; GS % 4 == 0: all in or all out
+                if (ic >= gfirst && ic < gfirst + GS) e[d] = *reinterpret_cast<const int *>(wrow + (ic - gfirst));
+            }
+        }
+        frag[idx] = e;
+    }
+    if (tid < 64) {
+        const int c = cbase + tid;
+        v4i p = {0, 0, 0, 1};
+        if (c < C) p = requant_params(a.bias[c], a.mult[c], prelu ? a.mult_neg[c] : 0, a.shift[c], prelu);
+        lpar[tid] = p;
+    }
+    if (wg < bd.units) fetch_band(wg);
+    __syncthreads();
+
+    v4i par[4][4];  // [tile t][r]: channel 16g + 4t + r
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) par[t][r] = lpar[16 * g + 4 * t + r];
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int cl = cbase + 16 * g;  // the lane's first output channel
+
+    // one instance of the loop per epilogue form: no branch per output
+    auto run = [&](auto prelu_tag) {
+        constexpr bool PRELU = decltype(prelu_tag)::value;
+        for (int u = wg; u < bd.units; u += bd.wgs_per_cb) {
+            const Unit q = unit_of(u);
+            const int npiece = q.count * img_items;
+            __syncthreads();  // the readers of the previous band are done
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int pc = k * 256 + tid;
+                if (pc < npiece) *reinterpret_cast<v4i *>(xt + pc * 16) = piece[k];
+            }
+            __syncthreads();
+            if (u + bd.wgs_per_cb < bd.units) fetch_band(u + bd.wgs_per_cb);
+            // ---- the unit's output pixels in tiles of 16, PT tiles per wavefront iteration ---------
+            const int img_pix = q.rows_out * Wo;
+            const int npix = q.count * img_pix;
+            const int ngrp = (npix + 16 * PT - 1) / (16 * PT);
+            for (int grp = wave; grp < ngrp; grp += 4) {
+                int lbase[PT], yo[PT];
+                bool valid[PT];
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    const int idx = (grp * PT + p) * 16 + j;
+                    valid[p] = idx < npix;
+                    const int ii = valid[p] ? idx : 0;
+                    const int gi = ii / img_pix;
+                    const int rem = ii - gi * img_pix;
+                    const int r = rem / Wo;
+                    const int ox = rem - r * Wo;
+                    lbase[p] = ((gi * bd.RI + r * S) * W2 + ox * S) * 64 + 16 * g;  // tap (0, 0) of the pixel
+                    yo[p] = (((q.img0 + gi) * a.Ho + q.ro0 + r) * Wo + ox) * C + cl;
+                }
+                v4i acc[PT][4];
+#pragma unroll
+                for (int p = 0; p < PT; ++p)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[p][t] = v4i{0, 0, 0, 0};
+                // opaque offset: the fragment reads stay inside the loop (4 registers in flight
+                // each) instead of being hoisted out of it into 144 registers
+                int fo = lane;
+                asm volatile("" : "+v"(fo));
+                const v4i *fl = frag + fo;
+#pragma unroll
+                for (int s = 0; s < 9; ++s) {
+                    v4i b[PT];
+#pragma unroll
+                    for (int p = 0; p < PT; ++p)
+                        b[p] = *reinterpret_cast<const v4i *>(xt + lbase[p] + ((s / 3) * W2 + s % 3) * 64);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const v4i wf = fl[(t * 9 + s) * 64];
+#pragma unroll
+                        for (int p = 0; p < PT; ++p)
+                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, b[p], acc[p][t], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    uint32_t out[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        int v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            v[r] = PRELU ? requant_prelu_i64(acc[p][t][r], par[t][r], lo, hi)
+                                         : requant_i64<true>(acc[p][t][r], par[t][r], lo, hi);
+                        out[t] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                    }
+                    // the lane's channels cl .. cl+15 of its pixel (C % 4 == 0: whole dwords are in or out)
+                    if (valid[p] && cl + 16 <= C) {
+                        __builtin_amdgcn_raw_buffer_store_b128(v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]},
+                                                               ry, yo[p], 0, 0);
+                    } else if (valid[p]) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (cl + 4 * t < C)
+                                __builtin_amdgcn_raw_buffer_store_b32((int)out[t], ry, yo[p] + 4 * t, 0, 0);
+                    }
+                }
+            }
+        }
+    };
+    if (prelu)
+        run(std::true_type{});
+    else
+        run(std::false_type{});
+}
+
+// Any C, group size and alignment: one thread per output element.
+__global__ __launch_bounds__(256) void gconv_kernel_generic(const GconvArgs a)
+{
+    set_f64_round_down();
+    const long long tid = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (tid >= a.total) return;
+    const int c = (int)(tid % a.C);
+    long long r = tid / a.C;
+    const int ox = (int)(r % a.Wo);
+    r /= a.Wo;
+    const int oy = (int)(r % a.Ho);
+    const int n = (int)(r / a.Ho);
+    const int first = (c / a.gs) * a.gs;
+    int acc = a.bias[c];
+    for (int i = 0; i < 3; ++i) {
+        const int iy = oy * a.stride + i - 1;
+        if (iy < 0 || iy >= a.H) continue;
+        for (int jx = 0; jx < 3; ++jx) {
+            const int ix = ox * a.stride + jx - 1;
+            if (ix < 0 || ix >= a.W) continue;
+            const int8_t *xp = a.x + (((long long)n * a.H + iy) * a.W + ix) * a.C + first;
+            const int8_t *wp = a.w + ((long long)(i * 3 + jx) * a.C + c) * a.gs;
+            for (int k = 0; k < a.gs; ++k) acc += (int)xp[k] * (int)wp[k];
+        }
+    }
+    const int m = (a.mult_neg && acc < 0) ? a.mult_neg[c] : a.mult[c];
+    const int v = requant_to_biased(acc, make_scale(m, a.shift[c]), a.lo + kQBias, a.hi + kQBias);
+    a.y[tid] = (int8_t)(v - kQBias);
+}
+
+using GconvFn = void (*)(const GconvArgs);
+
+// gs % 4 == 0: the widest chunk that divides the group.
+template <int S> static GconvFn pick_gconv(int gs)
+{
+    if (gs == 4) return &gconv_kernel_v4<S, 1, true>;
+    if (gs == 8) return &gconv_kernel_v4<S, 2, true>;
+    if (gs == 16) return &gconv_kernel_v4<S, 4, true>;
+    if (gs % 16 == 0) return &gconv_kernel_v4<S, 4, false>;
+    if (gs % 8 == 0) return &gconv_kernel_v4<S, 2, false>;
+    return &gconv_kernel_v4<S, 1, false>;
+}
+
+static bool ranges_overlap(const void *p, size_t pn, const void *q, size_t qn)
+{
+    const uintptr_t a = (uintptr_t)p, b = (uintptr_t)q;
+    return a < b + qn && b < a + pn;
+}
+
+}  // namespace prom
+
+extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const int8_t *w_g, const void *w_frag,
+                             int group_size, int stride, const prom_requant_t *rq, int8_t *y, void *stream)
+{
+    using namespace prom;
+    if (!x || !w_g || !rq || !rq->bias || !rq->mult || !rq->shift || !y) return PROM_EINVAL;
+    if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || (stride != 1 && stride != 2)) return PROM_EINVAL;
+    if (group_size <= 0 || c % group_size != 0) return PROM_EINVAL;
+    if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
+    // |acc| <= 9 * gs * 128 * 128 must stay well inside the int32 accumulator and the
+    // precondition |acc + bias| < 2^30 of the requantisation
+    if (group_size > 4096) return PROM_EUNSUPPORTED;
+    if (group_size == 1) return prom_dw_conv(x, n, h, w, c, w_g, stride, rq, y, stream);  // same weight layout
+    GconvArgs a;
+    a.x = x; a.w = w_g; a.wfrag = nullptr; a.bias = rq->bias; a.mult = rq->mult; a.mult_neg = rq->mult_neg; a.shift = rq->shift;
+    a.y = y;
+    a.N = n; a.H = h; a.W = w; a.C = c; a.stride = stride; a.gs = group_size;
+    a.Ho = (h - 1) / stride + 1;
+    a.Wo = (w - 1) / stride + 1;
+    a.lo = rq->act_min;
+    a.hi = rq->act_max;
+    const size_t xbytes = (size_t)n * h * w * c, ybytes = (size_t)n * a.Ho * a.Wo * c;
+    const size_t wbytes = (size_t)9 * c * group_size;
+    if (xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
+    if (ranges_overlap(y, ybytes, x, xbytes) || ranges_overlap(y, ybytes, w_g, wbytes)) return PROM_EALIAS;
+    a.total = (long long)ybytes;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    clear_hip_error();
+    const bool fast = (group_size % 4 == 0) && (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_g) & 3) == 0) &&
+                      ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg |
+                         (uintptr_t)rq->shift) & 15) == 0) &&
+                      (long long)h * w * c < (1LL << 31) - (1LL << 24) && wbytes < ((size_t)1 << 30) && n <= 65535;
+    bool mfma = fast && (group_size == 4 || group_size == 8 || group_size == 16 || group_size == 32 ||
+                               group_size == 64) &&
+                      xbytes < ((size_t)1 << 31) - ((size_t)1 << 24) && ybytes < ((size_t)1 << 31) - ((size_t)1 << 24);
+    if (w_frag && (((uintptr_t)w_frag & 15) != 0 || prom_gconv_frag_size(c, group_size) == 0)) return PROM_EINVAL;
+    if (w_frag && ranges_overlap(y, ybytes, w_frag, prom_gconv_frag_size(c, group_size))) return PROM_EALIAS;
+    if (mfma) {
+        a.wfrag = static_cast<const v4i *>(w_frag);
+        // band height: as many output rows as keep the staged input rows within kBandBytes
+        constexpr int kBandBytes = kGconvPieces * 256 * 16;
+        const int row_bytes = (w + 2) * 64;
+        int ri = kBandBytes / row_bytes;
+        if (ri < 3) {
+            mfma = false;  // an image row too wide for the staged band: the dot4 kernel takes it
+        } else {
+            GconvBand bd;
+            bd.ncb = (c + 63) / 64;
+            bd.R = (ri - 3) / stride + 1;
+            if (bd.R > a.Ho) bd.R = a.Ho;
+            bd.RI = (bd.R - 1) * stride + 3;
+            bd.bands = (a.Ho + bd.R - 1) / bd.R;
+            bd.G = 1;
+            if (bd.bands == 1) {
+                // small images: several per unit (a workgroup copies 36 KB of weights whatever it
+                // computes), as far as they fit, but no more than leaves a workgroup for every
+                // compute unit
+                bd.G = kBandBytes / (bd.RI * row_bytes);
+                const long long spare = (long long)n * bd.ncb / 256;
+                if (bd.G > spare) bd.G = (int)spare;
+                if (bd.G > 16) bd.G = 16;
+                if (bd.G < 1) bd.G = 1;
+            }
+            const long long units = bd.G > 1 ? ((long long)n + bd.G - 1) / bd.G : (long long)n * bd.bands;
+            bd.units = (int)units;
+            long long per_cb = (2 * 256 + bd.ncb - 1) / bd.ncb;  // two workgroups per compute unit
+            if (per_cb > units) per_cb = units;
+            if (per_cb < 1) per_cb = 1;
+            bd.wgs_per_cb = (int)per_cb;
+            const size_t lds = (size_t)kGconvFragBytes + kGconvParBytes + (size_t)bd.G * bd.RI * row_bytes;
+            static std::once_flag once;
+            static hipError_t attr_err = hipSuccess;
+            std::call_once(once, [] {
+                attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gconv_mfma_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            });
+            if (attr_err != hipSuccess) {
+                last_hip_error() = attr_err;
+                (void)hipGetLastError();
+                return PROM_EHIP;
+            }
+            clear_hip_error();
+            hipLaunchKernelGGL(gconv_mfma_kernel, dim3((unsigned)(per_cb * bd.ncb)), dim3(256), lds, st, a, bd);
+            return check_launch();
+        }
+    }
+    if (fast) {
+        const GconvFn fn = stride == 1 ? pick_gconv<1>(group_size) : pick_gconv<2>(group_size);
+        const long long xblocks = ((long long)a.Wo * (c / 4) + 255) / 256;
+        const int strips = (a.Ho + 3) / 4;
+        if (xblocks > (1LL << 31) - 1 || strips > 65535) return PROM_EUNSUPPORTED;
+        hipLaunchKernelGGL(fn, dim3((unsigned)xblocks, (unsigned)strips, (unsigned)n), dim3(256), 0, st, a);
+    } else {
+        const long long blocks = (a.total + 255) / 256;
+        if (blocks > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
+        hipLaunchKernelGGL(gconv_kernel_generic, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    }
+    return check_launch();
+}

@@ -63,6 +63,46 @@ extern "C" int prom_unpack_ternary(const void *packed_host, size_t packed_bytes,
     return PROM_OK;
 }
 
+// ---- grouped 3x3 convolution: weights in the operand order of the matrix-core kernel ------------
+// [block of 64 channels][tile t: 4][tap s: 9][lane: 64] entries of 16 bytes.  Lane (i = lane & 15,
+// kg = lane >> 4) of tile t holds, for output channel oc = 64*block + 16*(i >> 2) + 4*t + (i & 3)
+// and tap s, the weights that multiply input channels 64*block + 16*kg + 0..15: w[s][oc][...] where
+// the input channel belongs to oc's group, zero elsewhere.
+extern "C" size_t prom_gconv_frag_size(int c, int group_size)
+{
+    if (c <= 0 || c % 4 != 0) return 0;
+    if (group_size != 4 && group_size != 8 && group_size != 16 && group_size != 32 && group_size != 64) return 0;
+    if (c % group_size != 0) return 0;
+    return (size_t)((c + 63) / 64) * 4 * 9 * 64 * 16;
+}
+
+extern "C" int prom_gconv_pack(const int8_t *w_host, int c, int group_size, void *frag_host, size_t frag_bytes)
+{
+    if (!w_host || !frag_host) return PROM_EINVAL;
+    const size_t need = prom_gconv_frag_size(c, group_size);
+    if (need == 0) return PROM_EUNSUPPORTED;
+    if (frag_bytes < need) return PROM_EWORKSPACE;
+    int8_t *out = static_cast<int8_t *>(frag_host);
+    std::memset(out, 0, need);
+    const int ncb = (c + 63) / 64;
+    for (int cb = 0; cb < ncb; ++cb)
+        for (int t = 0; t < 4; ++t)
+            for (int s = 0; s < 9; ++s)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int i = lane & 15, kg = lane >> 4;
+                    const int oc = 64 * cb + 16 * (i >> 2) + 4 * t + (i & 3);
+                    if (oc >= c) continue;
+                    const int gfirst = (oc / group_size) * group_size;
+                    int8_t *e = out + ((((size_t)cb * 4 + t) * 9 + s) * 64 + lane) * 16;
+                    for (int b = 0; b < 16; ++b) {
+                        const int ic = 64 * cb + 16 * kg + b;
+                        if (ic >= gfirst && ic < gfirst + group_size)
+                            e[b] = w_host[((size_t)s * c + oc) * group_size + (ic - gfirst)];
+                    }
+                }
+    return PROM_OK;
+}
+
 hipError_t &prom::last_hip_error()
 {
     static thread_local hipError_t e = hipSuccess;

@@ -1,0 +1,124 @@
+"""Parity of prom_gconv3x3 (grouped 3x3 convolution, int8) against the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_gconv_layer, prelu_mult_neg
+from gpu_util import assert_same, dev, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2505_03254_amd as P
+    P.load_library()
+    return P
+
+
+def _run(P, G, window=None, mneg=None, offset_params=False, use_frag=False):
+    torch = torch_cuda()
+    lo, hi = window if window is not None else (G.act_min, G.act_max)
+    if offset_params:  # parameter arrays that are not 16-byte aligned
+        pad = lambda a: dev(np.concatenate([np.zeros(1, a.dtype), a]))[1:]
+    else:
+        pad = dev
+    rq = P.Requant(pad(G.bias), pad(G.mult), pad(G.shift), lo, hi, None if mneg is None else pad(mneg))
+    frag = dev(P.prom_gconv_pack(G.weight)) if use_frag else None
+    y = P.prom_gconv3x3(dev(G.x), dev(G.weight), G.stride, rq, w_frag=frag)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def _want(G, window=None, mneg=None):
+    lo, hi = window if window is not None else (G.act_min, G.act_max)
+    return oracle.gconv3x3(G.x, G.weight, G.stride, G.bias, G.mult, G.shift, lo, hi, mult_neg=mneg)
+
+
+SHAPES = [
+    # n, h, w, c, gs, stride: every chunking of the tiled kernel (gs 4, 8, 16 in one chunk; 12, 24,
+    # 32, 40, 48, 64 in several), one group = dense conv, odd sizes, 1..3 rows left over in the
+    # row groups of 4, one pixel, group sizes and channel counts of the one-thread-per-output kernel
+    (2, 9, 11, 16, 4, 1), (2, 9, 11, 16, 4, 2), (1, 14, 14, 64, 8, 1), (2, 7, 7, 64, 8, 2),
+    (2, 13, 10, 64, 16, 1), (1, 28, 28, 128, 16, 2), (1, 6, 5, 24, 12, 1), (1, 7, 9, 48, 24, 1),
+    (2, 5, 6, 48, 24, 2), (1, 9, 9, 64, 32, 1), (1, 10, 7, 80, 40, 2), (1, 8, 8, 96, 48, 1),
+    (1, 5, 5, 128, 64, 2), (1, 6, 6, 32, 32, 1), (1, 1, 1, 16, 8, 1), (3, 2, 2, 8, 4, 2),
+    (2, 5, 4, 6, 3, 1), (1, 7, 3, 10, 5, 2), (2, 4, 4, 6, 2, 1), (1, 5, 5, 12, 1, 1), (1, 4, 6, 7, 7, 2),
+    (4, 56, 56, 96, 16, 1), (4, 56, 56, 96, 16, 2), (2, 28, 28, 192, 48, 1),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_gconv_shapes(P, shape):
+    n, h, w, c, gs, stride = shape
+    G = make_gconv_layer(15000 + h * 31 + c + gs + stride, n, h, w, c, gs, stride, signed_x=True,
+                         act_window=(-128, 127), shift_range=(8, 17))
+    G.x.reshape(-1)[::37] = -128
+    want = _want(G)
+    assert_same(_run(P, G), want, f"gconv {shape}")
+    if P.prom_gconv_frag_size(c, gs):  # the matrix-core kernel with weights prepared by prom_gconv_pack
+        assert_same(_run(P, G, use_frag=True), want, f"gconv {shape} prepared weights")
+
+
+@pytest.mark.parametrize("shape", [(2, 9, 11, 32, 8, 1), (2, 9, 11, 48, 24, 2), (1, 6, 6, 10, 5, 1)])
+def test_gconv_prelu_windows_shifts_and_unaligned_parameters(P, shape):
+    n, h, w, c, gs, stride = shape
+    G = make_gconv_layer(15500 + c + gs, n, h, w, c, gs, stride, signed_x=True, shift_range=(0, 31))
+    mneg = prelu_mult_neg(15500 + c, G.mult)
+    mneg[::3] = -(1 << 31)
+    for window in ((-128, 127), (0, 127), (-5, 9)):
+        assert_same(_run(P, G, window), _want(G, window), f"plain {shape} {window}")
+        assert_same(_run(P, G, window, mneg), _want(G, window, mneg), f"prelu {shape} {window}")
+        if P.prom_gconv_frag_size(c, gs):
+            assert_same(_run(P, G, window, mneg, use_frag=True), _want(G, window, mneg), f"prelu frag {shape}")
+    assert_same(_run(P, G, None, mneg, offset_params=True), _want(G, None, mneg), f"unaligned {shape}")
+
+
+def test_gconv_group_size_one_is_the_depthwise_layer(P):
+    torch = torch_cuda()
+    G = make_gconv_layer(15600, 2, 14, 14, 96, 1, 2, signed_x=True, act_window=(-128, 127))
+    rq = P.Requant(dev(G.bias), dev(G.mult), dev(G.shift), -128, 127)
+    a = P.prom_gconv3x3(dev(G.x), dev(G.weight), 2, rq)
+    b = P.prom_dw_conv(dev(G.x), dev(G.weight.reshape(3, 3, 96)), 2, rq)
+    torch.cuda.synchronize()
+    assert_same(a.cpu().numpy(), b.cpu().numpy(), "group size 1")
+    assert_same(a.cpu().numpy(), _want(G), "group size 1 vs oracle")
+
+
+def test_gconv_argument_errors(P):
+    G = make_gconv_layer(15700, 1, 4, 4, 16, 4)
+    rq = P.Requant(dev(G.bias), dev(G.mult), dev(G.shift), 0, 127)
+    x, w = dev(G.x), dev(G.weight)
+    with pytest.raises(P.PromError) as e:
+        P.prom_gconv3x3(x, dev(np.zeros((3, 3, 16, 3), np.int8)), 1, rq)   # 16 % 3 != 0
+    assert e.value.code == -1
+    with pytest.raises(P.PromError) as e:
+        P.prom_gconv3x3(x, w, 3, rq)
+    assert e.value.code == -1
+    with pytest.raises(P.PromError) as e:
+        P.prom_gconv3x3(x, w, 1, rq, y=x)                                    # output over input
+    assert e.value.code == -3
+    G5 = make_gconv_layer(15701, 1, 4, 4, 10, 5)                             # no prepared form for gs = 5
+    with pytest.raises(P.PromError) as e:
+        P.prom_gconv_pack(G5.weight)
+    assert e.value.code == -2
+    with pytest.raises(P.PromError) as e:
+        P.prom_gconv3x3(dev(G5.x), dev(G5.weight), 1,
+                        P.Requant(dev(G5.bias), dev(G5.mult), dev(G5.shift), 0, 127), w_frag=w)
+    assert e.value.code == -1
+
+
+def test_gconv_full_size_layer_every_output(P):
+    """A layer of RegNetX-400MF's size at batch 32 (28x28, 160 channels in groups of 16), both
+    strides, every output, three runs."""
+    torch = torch_cuda()
+    for stride in (1, 2):
+        G = make_gconv_layer(15800 + stride, 32, 28, 28, 160, 16, stride)
+        want = dev(_want(G))
+        x, w, frag = dev(G.x), dev(G.weight), dev(P.prom_gconv_pack(G.weight))
+        rq = P.Requant(dev(G.bias), dev(G.mult), dev(G.shift), G.act_min, G.act_max)
+        for run in range(3):
+            y = P.prom_gconv3x3(x, w, stride, rq, w_frag=frag if run else None)
+            torch.cuda.synchronize()
+            bad = int((y != want).sum())
+            assert bad == 0, f"stride {stride}, run {run}: {bad} outputs differ"
