@@ -8,4 +8,5 @@ from .prom_oracle import (  # noqa: F401
     max_threads,
     set_threads,
 )
-from .quant_oracle import quantize_pw_absmean, quantize_dw_absmax, quantize_activation_absmax  # noqa: F401,E402
+from .quant_oracle import (quantize_pw_absmean, quantize_dw_absmax, quantize_gconv_absmax,
+                           quantize_activation_absmax)  # noqa: F401,E402

@@ -51,6 +51,21 @@ def quantize_dw_absmax(w: np.ndarray, eps: float = 1e-5):
     return np.ascontiguousarray(np.transpose(q, (1, 2, 0))), scale
 
 
+def quantize_gconv_absmax(w: np.ndarray, eps: float = 1e-5):
+    """The same absmax scheme (Section 3.1, Eq. 4-5 with the factor 127 and the eps clamp of the
+    pseudocode) for a grouped 3x3 layer: one scale per output channel over its group's input
+    channels and the 9 taps.  w: float32 [c][gs][3][3] (the paper's [c_out][c_in per group][k][k]).
+    Returns (q int8 [3][3][c][gs], the layout prom_gconv3x3 takes, scale float32 [c])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    c, gs = w.shape[0], w.shape[1]
+    assert w.shape[2:] == (3, 3)
+    amax = np.max(np.abs(w.reshape(c, -1)), axis=1).astype(np.float32)
+    scale = (np.float32(127.0) / np.maximum(amax, np.float32(eps))).astype(np.float32)
+    q = np.rint((w.reshape(c, -1) * scale[:, None]).astype(np.float32))
+    q = np.clip(q, -128, 127).astype(np.int8).reshape(c, gs, 3, 3)
+    return np.ascontiguousarray(np.transpose(q, (2, 3, 0, 1))), scale
+
+
 def quantize_activation_absmax(x: np.ndarray, eps: float = 1e-5):
     """The paper's activation quantiser (Section 3.1, Eq. 6-7, with the factor 127 and the eps
     clamp of its pseudocode): one scale per batch element over all its channels and pixels.

@@ -128,3 +128,31 @@ def test_activation_absmax_against_the_papers_pseudocode_in_torch():
     want = (t.flatten(start_dim=1) * scale).round().clamp_(-128, 127).numpy().astype(np.int8).reshape(x.shape)
     q, s = oracle.quantize_activation_absmax(x)
     assert (q != want).mean() < 1e-3 and np.allclose(s, scale.numpy().ravel(), rtol=3e-7)
+
+
+def test_gconv_absmax_pins():
+    """Grouped 3x3 weights: one absmax scale per output channel over its group's input channels
+    and the 9 taps (Section 3.1: W[c_out][c_in][K][K], Eq. 4-5).  Group size 1 is the (pinned)
+    depthwise quantiser; the extreme of every channel maps to +-127; each code is within half a
+    step of w * scale; torch's statement of the pseudocode agrees up to its extra rounding."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(6)
+    d = rng.standard_normal((24, 1, 3, 3)).astype(np.float32)
+    q1, s1 = oracle.quantize_gconv_absmax(d)
+    q0, s0 = oracle.quantize_dw_absmax(d.reshape(24, 3, 3))
+    assert np.array_equal(q1.reshape(3, 3, 24), q0) and np.array_equal(s1, s0)
+    w = (rng.standard_normal((32, 8, 3, 3)) * rng.uniform(0.01, 3.0, (32, 1, 1, 1))).astype(np.float32)
+    q, s = oracle.quantize_gconv_absmax(w)
+    assert q.shape == (3, 3, 32, 8) and s.shape == (32,)
+    for c in range(32):
+        k = np.unravel_index(np.argmax(np.abs(w[c])), (8, 3, 3))
+        assert abs(int(q[k[1], k[2], c, k[0]])) == 127 and np.sign(q[k[1], k[2], c, k[0]]) == np.sign(w[c][k])
+        assert s[c] == np.float32(127.0) / np.abs(w[c]).max()
+    back = np.transpose(q, (2, 3, 0, 1)).astype(np.float64)          # [c][gs][3][3]
+    assert np.all(np.abs(back - w.astype(np.float64) * s[:, None, None, None].astype(np.float64)) <= 0.5 + 1e-4)
+    t = torch.from_numpy(w)
+    st = 127.0 / t.abs().flatten(start_dim=1).max(dim=-1, keepdim=True).values.clamp_(min=1e-5)
+    want = (t.flatten(start_dim=1) * st).round().clamp_(-128, 127).numpy().astype(np.int8).reshape(32, 8, 3, 3)
+    assert (np.transpose(q, (2, 3, 0, 1)) != want).mean() < 1e-3
+    z, sz = oracle.quantize_gconv_absmax(np.zeros((4, 4, 3, 3), np.float32))
+    assert not z.any() and np.all(sz == np.float32(127.0) / np.float32(1e-5))
