@@ -133,6 +133,14 @@ int prom_quantize_pw_absmean(const float *w, int cout, int cin, float eps, void 
  *   wq  dev int8 [3][3][c], the layout prom_dw_conv takes;  scale dev float32 [c] */
 int prom_quantize_dw_absmax(const float *w, int c, float eps, int8_t *wq, float *scale, void *stream);
 
+/* The same for a grouped 3x3 layer (Section 3.1: W[c_out][c_in per group][K][K], Eq. 4-5): one
+ * scale per output channel over its group's input channels and the 9 taps.
+ *   w   dev float32 [c][group_size][3][3]
+ *   wq  dev int8 [3][3][c][group_size], the layout prom_gconv3x3 takes;  scale dev float32 [c]
+ * PROM_EINVAL if c % group_size != 0. */
+int prom_quantize_gconv_absmax(const float *w, int c, int group_size, float eps, int8_t *wq,
+                               float *scale, void *stream);
+
 /* Activation quantisation with one dynamic scale per batch element (paper Section 3.1, Eq. 6-7;
  * factor 127 and eps clamp as in its pseudocode), on the device:
  *   scale[i] = 127 / max(max over the image |x[i][...]|, eps),

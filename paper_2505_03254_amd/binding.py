@@ -100,6 +100,8 @@ def load_library():
     lib.prom_quantize_activation_absmax.argtypes = [vp, ci, ctypes.c_longlong, ctypes.c_float, vp, vp, vp]
     lib.prom_quantize_dw_absmax.restype = ci
     lib.prom_quantize_dw_absmax.argtypes = [vp, ci, ctypes.c_float, vp, vp, vp]
+    lib.prom_quantize_gconv_absmax.restype = ci
+    lib.prom_quantize_gconv_absmax.argtypes = [vp, ci, ci, ctypes.c_float, vp, vp, vp]
     lib.prom_block_is_fused.restype = ci
     lib.prom_block_is_fused.argtypes = [ci] * 7
     lib.prom_pw_batch_class.restype = ci
@@ -388,6 +390,21 @@ def prom_quantize_dw_absmax(w, eps: float = 1e-5, stream=None):
     scale = torch.empty(c, dtype=torch.float32, device=w.device)
     _check(load_library().prom_quantize_dw_absmax(w.data_ptr(), c, float(eps), wq.data_ptr(), scale.data_ptr(),
                                                   _stream_ptr(stream)), "prom_quantize_dw_absmax")
+    return wq, scale
+
+
+def prom_quantize_gconv_absmax(w, eps: float = 1e-5, stream=None):
+    """w: float32 [c, group_size, 3, 3] device.  Returns (int8 [3, 3, c, group_size], scale float32 [c])."""
+    import torch
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 4
+            and tuple(w.shape[2:]) == (3, 3)):
+        raise TypeError("w must be a contiguous float32 [c, group_size, 3, 3] device tensor")
+    c, gs = int(w.shape[0]), int(w.shape[1])
+    wq = torch.empty((3, 3, c, gs), dtype=torch.int8, device=w.device)
+    scale = torch.empty(c, dtype=torch.float32, device=w.device)
+    _check(load_library().prom_quantize_gconv_absmax(w.data_ptr(), c, gs, float(eps), wq.data_ptr(),
+                                                     scale.data_ptr(), _stream_ptr(stream)),
+           "prom_quantize_gconv_absmax")
     return wq, scale
 
 

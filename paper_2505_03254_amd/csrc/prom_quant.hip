@@ -81,6 +81,30 @@ __global__ __launch_bounds__(256) void quant_dw_kernel(const float *__restrict__
     }
 }
 
+// Grouped 3x3 weights [c][gs][3][3]: one wavefront per output channel over its 9*gs weights
+// (butterfly maximum, then the codes in the layout prom_gconv3x3 takes, [3][3][c][gs]).
+__global__ __launch_bounds__(256) void quant_gconv_kernel(const float *__restrict__ w, int c, int gs, float eps,
+                                                          int8_t *__restrict__ wq, float *__restrict__ scale_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (ch >= c) return;  // whole wavefronts leave together
+    const int n = 9 * gs;
+    const float *wc = w + (size_t)ch * n;
+    float amax = 0.0f;
+    for (int i = lane; i < n; i += 64) amax = fmaxf(amax, fabsf(wc[i]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    const float scale = __fdiv_rn(127.0f, fmaxf(amax, eps));
+    if (lane == 0) scale_out[ch] = scale;
+    for (int i = lane; i < n; i += 64) {
+        const int k = i / 9, t = i - 9 * k;  // input channel of the group, tap
+        float q = rintf(__fmul_rn(wc[i], scale));
+        q = fminf(fmaxf(q, -128.0f), 127.0f);
+        wq[((size_t)t * c + ch) * gs + k] = (int8_t)(int)q;
+    }
+}
+
 // ---- activations: one absmax scale per batch element (paper Section 3.1, Eq. 6-7) -------------
 // Pass 1: absmax per image.  |x| >= 0, so the float bits order like unsigned integers and the
 // per-image maximum is an atomic max on the bit pattern (the target is cleared by a fill kernel).
@@ -203,5 +227,17 @@ extern "C" int prom_quantize_dw_absmax(const float *w, int c, float eps, int8_t 
     prom::clear_hip_error();
     hipLaunchKernelGGL(prom::quant_dw_kernel, dim3((unsigned)((c + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), w, c, eps, wq, scale);
+    return prom::check_launch();
+}
+
+extern "C" int prom_quantize_gconv_absmax(const float *w, int c, int group_size, float eps, int8_t *wq,
+                                          float *scale, void *stream)
+{
+    if (!w || !wq || !scale || c <= 0 || group_size <= 0 || c % group_size != 0 || !(eps > 0.0f)) return PROM_EINVAL;
+    if ((((uintptr_t)w | (uintptr_t)scale) & 3) != 0) return PROM_EINVAL;
+    if (group_size > 4096) return PROM_EUNSUPPORTED;
+    prom::clear_hip_error();
+    hipLaunchKernelGGL(prom::quant_gconv_kernel, dim3((unsigned)((c + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), w, c, group_size, eps, wq, scale);
     return prom::check_launch();
 }

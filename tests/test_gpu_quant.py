@@ -59,6 +59,27 @@ def test_absmax_every_mobilenetv2_depthwise_shape(P, kind):
         assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind", ["kaiming", "trained"])
+def test_absmax_grouped_layers(P, kind):
+    """Grouped 3x3 weights of the RegNetX / ResNeXt shapes (and ragged ones): codes and scales
+    bit for bit, and the quantised layer runs through prom_gconv3x3."""
+    torch = torch_cuda()
+    for c, gs in ((32, 16), (160, 16), (128, 4), (256, 8), (1024, 32), (48, 24), (10, 5), (64, 64), (7, 1)):
+        w = float_conv_weights(8300 + c + gs, c, 9 * gs, kind=kind).reshape(c, gs, 3, 3)
+        wq, scale = P.prom_quantize_gconv_absmax(dev(w))
+        torch.cuda.synchronize()
+        q, s = oracle.quantize_gconv_absmax(w)
+        assert_same(wq.cpu().numpy(), q, f"{kind} grouped c={c} gs={gs}")
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    z, sz = P.prom_quantize_gconv_absmax(dev(np.zeros((8, 4, 3, 3), np.float32)))
+    torch.cuda.synchronize()
+    assert not z.cpu().numpy().any() and np.all(sz.cpu().numpy() == np.float32(127.0) / np.float32(1e-5))
+    lib = P.load_library()
+    st = torch.cuda.current_stream().cuda_stream
+    w = dev(np.zeros((8, 3, 3, 3), np.float32))
+    assert lib.prom_quantize_gconv_absmax(w.data_ptr(), 8, 3, 1e-5, z.data_ptr(), sz.data_ptr(), st) == -1
+
+
 def test_quantised_weights_feed_the_convolutions(P):
     """float32 weights -> device quantisers -> prom_pw_conv / prom_dw_conv, against the oracle's
     quantisers followed by the oracle's convolutions."""
