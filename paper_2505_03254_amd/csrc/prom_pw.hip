@@ -103,7 +103,7 @@ constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flig
 // Tiles per wavefront of a batch member: kBatchNT, or half of it for a layer with many k
 // steps, whose decoded fragments would otherwise set the LDS size (and with it the number of
 // resident workgroups) of the whole launch.
-constexpr int kBatchNTDeep = 2;
+constexpr int kBatchNTDeep = 3;
 constexpr int kBatchDeepKS = 10;
 __host__ __device__ constexpr int batch_nt(int ks) { return ks >= kBatchDeepKS ? kBatchNTDeep : kBatchNT; }
 
