@@ -8,6 +8,10 @@
       HBM bytes per launch of every kernel from the FETCH_SIZE and WRITE_SIZE counters (KiB per
       dispatch), each scaled by what the same counter reads for prom::copy_kernel, which moves a
       known number of bytes in each direction.
+
+  python -m paper_2505_03254_amd.rocprof_summary counters <a>_counter_collection.csv [<b>_... ...]
+      average per launch of every counter in the given files, per kernel (optionally only
+      kernels whose name contains --match)
 """
 from __future__ import annotations
 
@@ -63,6 +67,21 @@ def traffic(fetch_csv: str, write_csv: str, copy_bytes: int) -> None:
             print(f"traffic_bytes_per_launch[{k}] = {int(rd + wr)}")
 
 
+def counters(paths, match: str) -> None:
+    agg = collections.OrderedDict()
+    for path in paths:
+        for r in csv.DictReader(open(path)):
+            k = r["Kernel_Name"]
+            if not _is_ours(k) or (match and match not in k):
+                continue
+            agg.setdefault(k, collections.OrderedDict()).setdefault(r["Counter_Name"], []).append(
+                float(r["Counter_Value"]))
+    for k, cs in agg.items():
+        print(k[:100])
+        for c, v in cs.items():
+            print(f"    {c:<34}{sum(v) / len(v):>16.0f}   (launches: {len(v)})")
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -72,9 +91,14 @@ def main(argv=None) -> int:
     t.add_argument("fetch_csv")
     t.add_argument("write_csv")
     t.add_argument("--copy-bytes", type=int, required=True)
+    c = sub.add_parser("counters")
+    c.add_argument("csv", nargs="+")
+    c.add_argument("--match", default="")
     a = ap.parse_args(argv)
     if a.cmd == "stats":
         stats(a.csv)
+    elif a.cmd == "counters":
+        counters(a.csv, a.match)
     else:
         traffic(a.fetch_csv, a.write_csv, a.copy_bytes)
     return 0
