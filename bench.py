@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--batch", type=int, default=BATCH, help="images per layer (metric is quoted at 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
-    ap.add_argument("--cpu-sample-images", type=int, default=16)
+    ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--zero-fraction", type=float, default=0.5,
                     help="P(weight == 0) of the synthetic ternary weights (the paper reports about 0.31 at "
                          "initialisation and 0.5-0.55 after training); the kernels are dense, so the "
