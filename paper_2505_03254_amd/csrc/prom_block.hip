@@ -7,11 +7,15 @@
 // channels in chunks of 64:
 //   stage 1  expand the band's input rows (R*stride + 2 with the halo) for 64 hidden channels
 //            with int8 MFMA, requantise, store as int8 into an LDS tile with a zero border;
-//   stage 2  depthwise 3x3 on that tile on the vector ALU (v_dot4_i32_i8 against one-hot weight
-//            dwords: one instruction per tap and channel, no unpacking), requantise into a
-//            second LDS tile laid out [pixel][channel];
-//   stage 3  that tile is the B operand of the projection MFMA: one 64-deep k step per chunk,
-//            accumulators live in registers across chunks.
+//   stage 2  depthwise 3x3 on that tile, also on the matrix cores: for 16 channels the 64-deep k
+//            dimension holds 4 taps x 16 channels (the B operand of lane (pixel, g) is the 16
+//            channel bytes of the pixel under tap 4q + g, one LDS read; the A operand is zero
+//            except the one weight of the lane's channel and tap), so 3 MFMAs cover the 9 taps
+//            of 16 pixels x 16 channels, against 144 vector-ALU multiply-adds per lane;
+//   stage 3  the requantised depthwise outputs of a lane (its pixel, 16 of the 64 hidden
+//            channels) are, packed, exactly a B operand of the projection MFMA: one 64-deep k
+//            step per chunk with the projection weights decoded in the matching channel order;
+//            nothing goes back to LDS, the accumulators live in registers across chunks.
 // After the last chunk the projection is requantised, the block input is added (skip) and the
 // band is written.  HBM traffic is the block input (rows of the halo are read twice) and output.
 // Shapes the fused kernel does not take run as three launches through the caller's workspace.
@@ -19,6 +23,7 @@
 #include "prom_launch.h"
 
 #include <mutex>
+#include <vector>
 
 namespace prom {
 
@@ -57,20 +62,24 @@ __device__ __forceinline__ int requant_sel(bool prelu, int accv, const v4i &pr, 
     return prelu ? requant_prelu_i64(accv, pr, lo, hi) : requant_i64<true>(accv, pr, lo, hi);
 }
 
-// COT: 16-channel output tiles (cout <= 16*COT); TPW: projection pixel tiles per wavefront.
-template <int COT, int TPW>
-__global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
+// COT: 16-channel output tiles (cout <= 16*COT); TPW: projection pixel tiles per wavefront;
+// PRELU: the expand and depthwise epilogues take the PReLU form (a layer of the two without
+// negative-side multipliers then runs it with mult_neg = mult, which is the plain form), so that
+// neither hot loop has a branch per output.
+template <int COT, int TPW, bool PRELU>
+__global__ __launch_bounds__(256, 2) void block_fused_kernel(const BlockArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds[];
-    int8_t *xs = reinterpret_cast<int8_t *>(lds);                      // [RI][W][cin] (+64 pad)
-    int8_t *t1 = reinterpret_cast<int8_t *>(lds + a.off_t1);           // [RI][W+2][64]
-    int8_t *t2 = reinterpret_cast<int8_t *>(lds + a.off_t2);           // [P2][64]
-    v4i *fe = reinterpret_cast<v4i *>(lds + a.off_fe);                 // [4 tiles][KSe][64 lanes]
-    v4i *fp = reinterpret_cast<v4i *>(lds + a.off_fp);                 // [COT][64 lanes]
-    v4i *pe = reinterpret_cast<v4i *>(lds + a.off_pe);                 // [64] expand parameters
-    v4i *pd = reinterpret_cast<v4i *>(lds + a.off_pd);                 // [64] depthwise parameters
+    int8_t *xs = reinterpret_cast<int8_t *>(lds);                      // [RI][W][cin padded to 16] (+64 pad)
+    // the expanded band as 4 planes of 16 channels, [4][RI][W+2][16]: a wavefront's 16-byte reads
+    // of one plane (consecutive pixels) then fall into different banks
+    int8_t *t1 = reinterpret_cast<int8_t *>(lds + a.off_t1);
+    v4i *fe = reinterpret_cast<v4i *>(lds + a.off_fe);                 // [chunk][4 tiles][KSe][64 lanes]
+    v4i *fp = reinterpret_cast<v4i *>(lds + a.off_fp);                 // [chunk][COT][64 lanes]
+    v4i *pe = reinterpret_cast<v4i *>(lds + a.off_pe);                 // [chunk][64] expand parameters
+    v4i *pd = reinterpret_cast<v4i *>(lds + a.off_pd);                 // [chunk][64] depthwise parameters
     v4i *pp = reinterpret_cast<v4i *>(lds + a.off_pp);                 // [16*COT] project parameters
-    int8_t *wdl = reinterpret_cast<int8_t *>(lds + a.off_wd);          // [9][64] depthwise weights
+    int8_t *wdl = reinterpret_cast<int8_t *>(lds + a.off_wd);          // [chunk][9][64] depthwise weights
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -85,23 +94,29 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
     const int W = a.W, Wo = a.Wo, cin = a.cin, chid = a.chid, cout = a.cout, s = a.stride;
     const int KSe = (cin + 63) >> 6, KWe = (cin + 15) >> 4, KWp = (chid + 15) >> 4;
     const int W2 = W + 2;
+    const int plane = a.RI * W2 * 16;  // bytes of one 16-channel plane of t1
     const int npix1 = a.RI * W;                       // pixels expanded per chunk
     const int npix2 = rows_out * Wo;                  // output pixels of the band
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(a.x), 0, a.N * a.H * W * cin, kBufFlags);
 
-    // ---- stage 0: the band's input rows into LDS (rows outside the image read as zero or as a
-    // neighbouring image; the expanded rows are forced to zero below, so either is fine) -------
+    // ---- stage 0: the band's input rows into LDS, pixels padded to a multiple of 16 bytes (rows
+    // outside the image read as zero or as a neighbouring image; the expanded rows are forced to
+    // zero below, so either is fine; the padding bytes meet zero weights) ------------------------
+    const int cinp = (cin + 15) & ~15;
     {
         const int row_bytes = W * cin;
         const int total = a.RI * row_bytes;  // multiple of 8
         const long long base = ((long long)img * a.H + ri0) * row_bytes;
+        const int pieces = cin >> 3;  // 8-byte pieces per pixel
         for (int o = tid * 8; o < total; o += 256 * 8) {
             const long long go = base + o;
             const int off = (go >= 0 && go < (long long)kOobOffset) ? (int)go : kOobOffset;
             const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rx, off, 0, 0);
-            *reinterpret_cast<v2i *>(xs + o) = v;
+            const int pc = o >> 3;
+            const int px = pc / pieces;
+            *reinterpret_cast<v2i *>(xs + px * cinp + 8 * (pc - px * pieces)) = v;
         }
         // project parameters (used after the last chunk)
         if (tid < 16 * COT) {
@@ -120,126 +135,168 @@ __global__ __launch_bounds__(256) void block_fused_kernel(const BlockArgs a)
     const int lo_e = in_vgpr(a.lo_e), hi_e = in_vgpr(a.hi_e);
     const int lo_d = in_vgpr(a.lo_d), hi_d = in_vgpr(a.hi_d);
 
+    // ---- weights and parameters of all chunks (one memory latency for the whole block) ----------
     const int nchunks = (chid + kCH - 1) / kCH;
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const int c0 = ch * kCH;
-        const int chc = min(kCH, chid - c0);  // channels of this chunk (multiple of 4)
-        __syncthreads();                      // previous chunk's readers are done with the LDS tiles
-        // ---- weights and parameters of the chunk --------------------------------------------
-        for (int idx = tid; idx < 4 * KSe * 64; idx += 256) {       // expand fragments
-            const int l = idx & 63, tk = idx >> 6, ks = tk % KSe, t = tk / KSe;
-            const int c = c0 + 16 * t + (l & 15);
-            const int kw = 4 * ks + (l >> 4);
-            const bool ok = c < chid && kw < KWe;
-            const uint32_t wv = a.we[ok ? (long long)c * KWe + kw : 0];
-            fe[idx] = decode_word(ok ? wv : 0u);
-        }
-        for (int idx = tid; idx < COT * 64; idx += 256) {           // project fragments, k step = chunk
-            const int l = idx & 63, t = idx >> 6;
-            const int c = 16 * t + (l & 15);
-            const int kw = 4 * ch + (l >> 4);
-            const bool ok = c < cout && kw < KWp;
-            const uint32_t wv = a.wp[ok ? (long long)c * KWp + kw : 0];
-            fp[idx] = decode_word(ok ? wv : 0u);
-        }
-        if (tid < kCH) {
-            v4i e = {0, 0, 0, 1}, d = {0, 0, 0, 1};
-            if (tid < chc) {
-                e = make_par(a.be, a.me, a.ne, a.se, c0 + tid);
-                d = make_par(a.bd, a.md, a.nd, a.sd, c0 + tid);
-            }
-            pe[tid] = e;
-            pd[tid] = d;
-        }
-        for (int idx = tid; idx < 9 * kCH; idx += 256) {
-            const int tap = idx >> 6, c = idx & 63;
-            wdl[idx] = c < chc ? a.wd[tap * chid + c0 + c] : (int8_t)0;
-        }
-        // zero border columns of t1 (col -1 and col W of every row)
-        for (int idx = tid; idx < a.RI * 2 * (kCH / 4); idx += 256) {
-            const int q = idx % (kCH / 4), rc = idx / (kCH / 4);
-            const int row = rc >> 1, col = (rc & 1) ? W + 1 : 0;
-            *reinterpret_cast<uint32_t *>(t1 + (row * W2 + col) * kCH + 4 * q) = 0u;
-        }
-        __syncthreads();
-
-        // ---- stage 1: expand 64 hidden channels for every pixel of the band's input rows ------
-        for (int t = 0; t < 4; ++t) {
-            if (16 * t >= chc) break;
-            v4i par[4];
+    const int fe_chunk = 4 * KSe * 64;  // expand fragments per chunk
+    for (int idx = tid; idx < nchunks * fe_chunk; idx += 256) {
+        const int ch = idx / fe_chunk, rem = idx - ch * fe_chunk;
+        const int l = rem & 63, tk = rem >> 6, ks = tk % KSe, t = tk / KSe;
+        const int c = ch * kCH + 16 * t + (l & 15);
+        const int kw = 4 * ks + (l >> 4);
+        const bool ok = c < chid && kw < KWe;
+        const uint32_t wv = a.we[ok ? (long long)c * KWe + kw : 0];
+        fe[idx] = decode_word(ok ? wv : 0u);
+    }
+    for (int idx = tid; idx < nchunks * COT * 64; idx += 256) {
+        // project fragments, one k step per chunk.  k order of the step: lane kg, byte 4t + b  <->
+        // hidden channel c0 + 16t + 4kg + b, which is where stage 2 leaves the depthwise outputs
+        const int ch = idx / (COT * 64), rem = idx - ch * (COT * 64);
+        const int l = rem & 63, t = rem >> 6;
+        const int c = 16 * t + (l & 15);
+        const int kg = l >> 4;
+        v4i e = {0, 0, 0, 0};
+        if (c < cout) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) par[r] = pe[16 * t + 4 * g + r];
+            for (int tt = 0; tt < 4; ++tt) {
+                const int kw = 4 * ch + tt;
+                if (kw < KWp) {
+                    const uint32_t wv = a.wp[(long long)c * KWp + kw];
+                    const uint32_t sel = ((wv >> (2 * kg)) & 0x03030303u) << 1;
+                    e[tt] = (int)__builtin_amdgcn_perm(0x00FF0000u, 0x00010000u, sel);
+                }
+            }
+        }
+        fp[idx] = e;
+    }
+    for (int idx = tid; idx < nchunks * kCH; idx += 256) {
+        v4i e = {0, 0, 0, 1}, d = {0, 0, 0, 1};
+        if (idx < chid) {
+            e = requant_params(a.be[idx], a.me[idx], a.ne ? a.ne[idx] : a.me[idx], a.se[idx], PRELU);
+            d = requant_params(a.bd[idx], a.md[idx], a.nd ? a.nd[idx] : a.md[idx], a.sd[idx], PRELU);
+        }
+        pe[idx] = e;
+        pd[idx] = d;
+    }
+    for (int idx = tid; idx < nchunks * 9 * kCH; idx += 256) {
+        const int ch = idx / (9 * kCH), rem = idx - ch * (9 * kCH);
+        const int tap = rem >> 6, c = ch * kCH + (rem & 63);
+        wdl[idx] = c < chid ? a.wd[tap * chid + c] : (int8_t)0;
+    }
+    // zero border columns of t1 (col -1 and col W of every row, in each of the 4 planes); stage 1
+    // never writes them
+    for (int idx = tid; idx < a.RI * 2 * (kCH / 4); idx += 256) {
+        const int q = idx % (kCH / 4), rc = idx / (kCH / 4);
+        const int row = rc >> 1, col = (rc & 1) ? W + 1 : 0;
+        *reinterpret_cast<uint32_t *>(t1 + (q >> 2) * plane + (row * W2 + col) * 16 + 4 * (q & 3)) = 0u;
+    }
+    __syncthreads();
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const v4i *fe_c = fe + ch * fe_chunk;
+        const v4i *fp_c = fp + ch * (COT * 64);
+        const v4i *pe_c = pe + ch * kCH;
+        const v4i *pd_c = pd + ch * kCH;
+        const int8_t *wdl_c = wdl + ch * (9 * kCH);
+        if (ch) __syncthreads();  // the depthwise reads of the previous chunk are done with t1
+
+        // ---- stage 1: expand 64 hidden channels for every pixel of the band's input rows; the
+        // activation fragment of a pixel tile serves the 4 channel tiles ------------------------
+        {
+            v4i pare[4][4];  // channel 16t + 4g + r
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) pare[t][r] = pe_c[16 * t + 4 * g + r];
             for (int pt = wave; pt * 16 < npix1; pt += 4) {
                 const int p = pt * 16 + j;
-                v4i d4 = {0, 0, 0, 0};
+                v4i d4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d4[t] = v4i{0, 0, 0, 0};
                 for (int ks = 0; ks < KSe; ++ks) {
                     // 16 k-bytes of pixel p; bytes beyond cin meet zero weights
-                    const v4i b = *reinterpret_cast<const v4i *>(xs + min(p, npix1 - 1) * cin + 64 * ks + 16 * g);
-                    d4 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fe[(t * KSe + ks) * 64 + lane], b, d4, 0, 0, 0);
+                    const v4i b = *reinterpret_cast<const v4i *>(xs + min(p, npix1 - 1) * cinp + 64 * ks + 16 * g);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        d4[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fe_c[(t * KSe + ks) * 64 + lane], b, d4[t], 0, 0, 0);
                 }
                 if (p < npix1) {
                     const int row = p / W, col = p - row * W;
                     const int ri = ri0 + row;
-                    uint32_t o = 0u;
-                    if (ri >= 0 && ri < a.H) {
+                    const bool inimg = ri >= 0 && ri < a.H;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
                         int v[4];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = requant_sel(a.ne != nullptr, d4[r], par[r], lo_e, hi_e);
-                        o = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                        for (int r = 0; r < 4; ++r) v[r] = requant_sel(PRELU, d4[t][r], pare[t][r], lo_e, hi_e);
+                        const uint32_t o = inimg ? pack4_low_bytes(v[0], v[1], v[2], v[3]) : 0u;
+                        *reinterpret_cast<uint32_t *>(t1 + t * plane + (row * W2 + col + 1) * 16 + 4 * g) = o;
                     }
-                    *reinterpret_cast<uint32_t *>(t1 + (row * W2 + col + 1) * kCH + 16 * t + 4 * g) = o;
                 }
             }
         }
         __syncthreads();
 
-        // ---- stage 2: depthwise 3x3 on the LDS tile --------------------------------------------
+        // ---- stages 2 and 3: depthwise 3x3 by MFMA on the LDS tile, then the projection -----------
         {
-            const int cg = tid & 15;  // 4-channel group of this thread (constant: 256 % 16 == 0)
-            if (4 * cg < chc) {
-                // one-hot weight dwords: byte q of wq[tap][q] is the weight of channel 4cg+q
-                int wq[9][4];
+            // the lane's A operands of the depthwise MFMAs: for channel tile t and tap group q
+            // the weight of channel 16t + (lane & 15) under tap 4q + (lane >> 4), at byte
+            // (lane & 15) of the 16, zero elsewhere
+            const int li = lane & 15;
+            v4i adw[4][3];
 #pragma unroll
-                for (int tap = 0; tap < 9; ++tap) {
-                    const uint32_t w4 = *reinterpret_cast<const uint32_t *>(wdl + tap * kCH + 4 * cg);
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) wq[tap][q] = (int)(w4 & (0xFFu << (8 * q)));
+                for (int q = 0; q < 3; ++q) {
+                    const int tap = 4 * q + g;
+                    const uint32_t wb = tap < 9 ? (uint32_t)(uint8_t)wdl_c[tap * kCH + 16 * t + li] : 0u;
+                    const uint32_t val = wb << (8 * (li & 3));
+                    adw[t][q] = v4i{(li >> 2) == 0 ? (int)val : 0, (li >> 2) == 1 ? (int)val : 0,
+                                    (li >> 2) == 2 ? (int)val : 0, (li >> 2) == 3 ? (int)val : 0};
                 }
-                v4i par[4];
+            v4i pard[4][4];  // channel 16t + 4g + r
 #pragma unroll
-                for (int q = 0; q < 4; ++q) par[q] = pd[4 * cg + q];
-                for (int item = tid >> 4; item < npix2; item += 16) {
-                    const int oy = item / Wo, ox = item - oy * Wo;
-                    const int8_t *src = t1 + ((oy * s) * W2 + ox * s) * kCH + 4 * cg;
-                    int sum[4] = {0, 0, 0, 0};
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int i = 0; i < 3; ++i)
+                for (int r = 0; r < 4; ++r) pard[t][r] = pd_c[16 * t + 4 * g + r];
+            int toff[3];  // LDS offset of the lane's tap in each tap group (tap 8 again where there is none)
 #pragma unroll
-                        for (int jx = 0; jx < 3; ++jx) {
-                            const int xv = *reinterpret_cast<const int *>(src + (i * W2 + jx) * kCH);
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                sum[q] = __builtin_amdgcn_sdot4(xv, wq[i * 3 + jx][q], sum[q], false);
-                        }
-                    int v[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) v[q] = requant_sel(a.nd != nullptr, sum[q], par[q], lo_d, hi_d);
-                    *reinterpret_cast<uint32_t *>(t2 + item * kCH + 4 * cg) = pack4_low_bytes(v[0], v[1], v[2], v[3]);
-                }
+            for (int q = 0; q < 3; ++q) {
+                const int tap = min(4 * q + g, 8);
+                toff[q] = ((tap / 3) * W2 + tap % 3) * 16;
             }
-        }
-        __syncthreads();
-
-        // ---- stage 3: projection, one k step (this chunk's 64 hidden channels) -----------------
 #pragma unroll
-        for (int q = 0; q < TPW; ++q) {
-            const int pt = wave + 4 * q;
-            if (pt * 16 < npix2) {
-                const int p = min(pt * 16 + j, npix2 - 1);
-                const v4i b = *reinterpret_cast<const v4i *>(t2 + p * kCH + 16 * g);
+            for (int q2 = 0; q2 < TPW; ++q2) {
+                const int pt = wave + 4 * q2;
+                {   // tiles beyond the band are computed on its last pixel and never stored: no
+                    // branch, so that the tiles of a wavefront can overlap
+                    const int p = min(pt * 16 + j, npix2 - 1);
+                    const int oy = p / Wo, ox = p - oy * Wo;
+                    const int8_t *src = t1 + ((oy * s) * W2 + ox * s) * 16;  // tap (0, 0) of the pixel, plane 0
+                    v4i accd[4];
 #pragma unroll
-                for (int t = 0; t < COT; ++t)
-                    acc[q][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fp[t * 64 + lane], b, acc[q][t], 0, 0, 0);
+                    for (int t = 0; t < 4; ++t) accd[t] = v4i{0, 0, 0, 0};
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            // taps 9..11 do not exist: their lanes read nothing and contribute zeros
+                            v4i b = {0, 0, 0, 0};
+                            if (q < 2 || g == 0) b = *reinterpret_cast<const v4i *>(src + toff[q] + t * plane);
+                            accd[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(adw[t][q], b, accd[t], 0, 0, 0);
+                        }
+                    }
+                    v4i b2;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        int v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = requant_sel(PRELU, accd[t][r], pard[t][r], lo_d, hi_d);
+                        b2[t] = (int)pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                    }
+#pragma unroll
+                    for (int t = 0; t < COT; ++t)
+                        acc[q2][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fp_c[t * 64 + lane], b2, acc[q2][t], 0, 0, 0);
+                }
             }
         }
     }
@@ -284,47 +341,57 @@ inline int align16(int v) { return (v + 15) & ~15; }
 static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
 {
     const int cin = a.cin, chid = a.chid, cout = a.cout, s = a.stride;
-    if (cin % 16 != 0 || chid % 4 != 0 || cout % 4 != 0 || cout > 64) return false;
+    if (cin % 8 != 0 || chid % 4 != 0 || cout % 4 != 0 || cout > 160) return false;
     if ((long long)a.N * a.H * a.W * (cin > cout ? cin : cout) >= (long long)kOobOffset) return false;
     if (a.W > 1024) return false;
-    // Measured: one fused launch beats the three launches through the workspace only while the block
-    // is small enough that launch and drain of three kernels outweigh the streaming (expanded tensor
-    // up to about 8 MB: 20-28 us against 28-37); on large tensors the unfused kernels stream at 3-5 TB/s and the fused
-    // one, bound by LDS traffic and barriers, is up to 3x slower (112x112x16->96->24 at batch 128:
-    // 257 us against 90), and on 14x14 maps the halo rows of a band cost a third of the work.
-    if ((long long)a.N * a.H * a.W * chid > (8LL << 20)) return false;
-    const int cot = cout <= 32 ? 2 : 4;
+    // projection tiles per pixel tile, and pixel tiles per wavefront so that the projection
+    // accumulators stay within 64 registers
+    const int cot = cout <= 32 ? 2 : cout <= 64 ? 4 : cout <= 96 ? 6 : 10;
+    const int tpw = cot == 2 ? 4 : cot == 4 ? 4 : cot == 6 ? 2 : 1;
     const int kse = (cin + 63) / 64;
-    // the band: at most 4 projection pixel tiles per wavefront (256 output pixels), LDS <= 150 KB,
-    // and enough workgroups to occupy the chip when the image allows it
+    const int nch = (chid + kCH - 1) / kCH;  // every chunk's weights are resident
+    // Measured (MobileNetV2 blocks, batch 1 to 128): the fused launch beats the three launches
+    // through the workspace while the hidden tensor is small enough that the launch, ramp-up and
+    // drain of three kernels outweigh their streaming (28x28x192 at batch 128: 34 us against 44;
+    // any block of up to 3 chunks at batch 1-8: 28-33 us against 35-38); on large tensors the
+    // unfused kernels stream at 4-5 TB/s and win (112x112x96 at batch 128: 87 us against 166), and
+    // with many chunks the resident weights leave no room for a band (14x14x384: 83 against 36).
+    if (nch > 3) return false;
+    if ((long long)a.N * a.H * a.W * chid > (32LL << 20)) return false;
+    // the band: at most tpw projection pixel tiles per wavefront, LDS <= 72 KB (two workgroups per
+    // CU), and enough workgroups to occupy the chip when the image allows it
     int best = 0;
     for (int R = 1; R <= a.Ho; ++R) {
-        if (R * a.Wo > 256) break;
+        if (R * a.Wo > 64 * tpw) break;
         const int RI = (R - 1) * s + 3;
-        const long long bytes = (long long)align16(RI * a.W * cin + 64) + (long long)RI * (a.W + 2) * kCH +
-                                (long long)align16(R * a.Wo) * kCH + 4 * kse * 1024 + cot * 1024 + 2 * kCH * 16 +
-                                16 * cot * 16 + 9 * kCH + 64;
-        if (bytes > 150 * 1024) break;
+        const long long bytes = (long long)align16(RI * a.W * align16(cin) + 64) + (long long)RI * (a.W + 2) * kCH +
+                                (long long)nch * (4 * kse * 1024 + cot * 1024 + 2 * kCH * 16 + 9 * kCH) +
+                                16 * cot * 16 + 64;
+        if (bytes > 72 * 1024) break;
         const int bands = (a.Ho + R - 1) / R;
-        // prefer taller bands (less halo recomputation) as long as there are >= 1.5 workgroups per CU
-        if (best == 0 || (long long)a.N * bands >= 384) best = R;
+        // prefer taller bands (less halo recomputation) as long as there are >= 2 workgroups per CU
+        if (best == 0 || (long long)a.N * bands >= 512) best = R;
     }
     if (best == 0) return false;
     const int R = best;
     a.R = R;
     a.RI = (R - 1) * s + 3;
     a.bands = (a.Ho + R - 1) / R;
-    int off = align16(a.RI * a.W * cin + 64);
+    int off = align16(a.RI * a.W * align16(cin) + 64);
     a.off_t1 = off; off += align16(a.RI * (a.W + 2) * kCH);
-    a.off_t2 = off; off += align16(R * a.Wo) * kCH;
-    a.off_fe = off; off += 4 * kse * 1024;
-    a.off_fp = off; off += cot * 1024;
-    a.off_pe = off; off += kCH * 16;
-    a.off_pd = off; off += kCH * 16;
+    a.off_t2 = 0;
+    a.off_fe = off; off += nch * 4 * kse * 1024;
+    a.off_fp = off; off += nch * cot * 1024;
+    a.off_pe = off; off += nch * kCH * 16;
+    a.off_pd = off; off += nch * kCH * 16;
     a.off_pp = off; off += 16 * cot * 16;
-    a.off_wd = off; off += align16(9 * kCH);
+    a.off_wd = off; off += align16(nch * 9 * kCH);
     lds = (size_t)off;
-    fn = cot == 2 ? &block_fused_kernel<2, 4> : &block_fused_kernel<4, 4>;
+    const bool prelu = a.ne != nullptr || a.nd != nullptr;
+    fn = cot == 2   ? (prelu ? &block_fused_kernel<2, 4, true> : &block_fused_kernel<2, 4, false>)
+         : cot == 4 ? (prelu ? &block_fused_kernel<4, 4, true> : &block_fused_kernel<4, 4, false>)
+         : cot == 6 ? (prelu ? &block_fused_kernel<6, 2, true> : &block_fused_kernel<6, 2, false>)
+                    : (prelu ? &block_fused_kernel<10, 1, true> : &block_fused_kernel<10, 1, false>);
     const long long g = (long long)a.N * a.bands;
     if (g > (1LL << 30)) return false;
     grid = (int)g;
@@ -408,11 +475,12 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
     int grid = 0;
     if (aligned && plan_fused(a, fn, lds, grid)) {
         static std::mutex mu;
-        static bool attr_done[2] = {false, false};
+        static std::vector<BlockFn> attr_done;
         {
             std::lock_guard<std::mutex> lock(mu);
-            const int which = fn == &block_fused_kernel<2, 4> ? 0 : 1;
-            if (!attr_done[which]) {
+            bool done = false;
+            for (BlockFn f : attr_done) done |= f == fn;
+            if (!done) {
                 const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
                 if (e != hipSuccess && lds > 64 * 1024) {
@@ -420,7 +488,7 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
                     (void)hipGetLastError();
                     return PROM_EHIP;
                 }
-                attr_done[which] = true;
+                attr_done.push_back(fn);
             }
         }
         clear_hip_error();

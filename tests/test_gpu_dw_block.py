@@ -116,6 +116,10 @@ def test_block_config4_full_output(P):
     # 17-wide rows, stride 2 on odd sizes, cout below and above one tile, no skip, one pixel
     (3, 13, 17, 16, 9, 16, 1), (2, 15, 13, 16, 5, 24, 2), (1, 28, 28, 32, 6, 64, 1), (2, 1, 1, 16, 4, 16, 1),
     (1, 33, 9, 48, 3, 48, 1), (1, 56, 56, 32, 6, 32, 2), (2, 6, 40, 64, 2, 40, 1), (1, 3, 300, 16, 2, 16, 1),
+    # 24 and 40 input channels (pixels padded to 16 bytes in LDS), wide outputs (6 and 10 projection
+    # tiles), 3 chunks with a ragged last one, the smallest and a single-row image
+    (2, 28, 28, 24, 6, 24, 1), (1, 17, 9, 40, 4, 96, 2), (2, 7, 7, 32, 6, 160, 1), (1, 14, 14, 24, 7, 136, 1),
+    (3, 1, 1, 16, 6, 16, 1), (1, 1, 37, 32, 5, 32, 1), (1, 37, 1, 32, 5, 32, 2),
 ])
 def test_block_shapes(P, shape):
     n, h, w, cin, t, cout, stride = shape

@@ -185,6 +185,7 @@ def _block_prelu(P, B, seed):
     # n, h, w, cin, t, cout, stride; the first rows run the fused kernel, the last the three launches
     (2, 9, 9, 16, 6, 16, 1), (1, 14, 14, 24, 6, 32, 2), (2, 7, 7, 160, 6, 320, 1), (3, 13, 17, 16, 9, 16, 1),
     (1, 28, 28, 32, 6, 64, 1), (2, 15, 13, 16, 5, 24, 2), (1, 5, 6, 8, 1, 8, 1), (16, 56, 56, 24, 6, 24, 1),
+    (2, 14, 14, 64, 6, 64, 1), (80, 56, 56, 24, 6, 24, 1),
 ])
 def test_block_prelu_shapes(P, shape):
     n, h, w, cin, t, cout, stride = shape
@@ -197,4 +198,6 @@ def test_block_prelu_shapes(P, shape):
 
 def test_block_prelu_covers_both_paths(P):
     assert P.prom_block_is_fused(2, 9, 9, 16, 96, 16, 1)
-    assert not P.prom_block_is_fused(16, 56, 56, 24, 144, 24, 1)
+    assert P.prom_block_is_fused(16, 56, 56, 24, 144, 24, 1)        # 24 input channels: padded pixels
+    assert not P.prom_block_is_fused(2, 14, 14, 64, 384, 64, 1)     # 6 chunks of hidden channels
+    assert not P.prom_block_is_fused(80, 56, 56, 24, 144, 24, 1)    # hidden tensor above 32 Mi elements
