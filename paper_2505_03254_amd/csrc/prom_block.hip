@@ -358,9 +358,11 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
     // with many chunks the resident weights leave no room for a band (14x14x384: 83 against 36).
     if (nch > 3) return false;
     if ((long long)a.N * a.H * a.W * chid > (32LL << 20)) return false;
-    // the band: at most tpw projection pixel tiles per wavefront, LDS <= 72 KB (two workgroups per
-    // CU), and enough workgroups to occupy the chip when the image allows it
+    // the band: at most tpw projection pixel tiles per wavefront, LDS <= 72 KB (two workgroups per CU)
+    // Band height by a cost estimate: rounds of workgroups over the chip (two per CU) times the
+    // rows a workgroup expands and filters plus a fixed part (weights, barriers) worth about 4 rows.
     int best = 0;
+    long long best_cost = 0;
     for (int R = 1; R <= a.Ho; ++R) {
         if (R * a.Wo > 64 * tpw) break;
         const int RI = (R - 1) * s + 3;
@@ -369,8 +371,12 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
                                 16 * cot * 16 + 64;
         if (bytes > 72 * 1024) break;
         const int bands = (a.Ho + R - 1) / R;
-        // prefer taller bands (less halo recomputation) as long as there are >= 2 workgroups per CU
-        if (best == 0 || (long long)a.N * bands >= 512) best = R;
+        const long long rounds = ((long long)a.N * bands + 511) / 512;
+        const long long cost = rounds * ((long long)(4 + RI) * a.W + (long long)R * a.Wo);
+        if (best == 0 || cost <= best_cost) {
+            best = R;
+            best_cost = cost;
+        }
     }
     if (best == 0) return false;
     const int R = best;
