@@ -210,11 +210,17 @@ __global__ __launch_bounds__(256, 2) void block_fused_kernel(const BlockArgs a)
             for (int pt = wave; pt * 16 < npix1; pt += 4) {
                 const int p = pt * 16 + j;
                 v4i d4[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) d4[t] = v4i{0, 0, 0, 0};
-                for (int ks = 0; ks < KSe; ++ks) {
+                const int8_t *xp = xs + min(p, npix1 - 1) * cinp + 16 * g;
+                {
                     // 16 k-bytes of pixel p; bytes beyond cin meet zero weights
-                    const v4i b = *reinterpret_cast<const v4i *>(xs + min(p, npix1 - 1) * cinp + 64 * ks + 16 * g);
+                    const v4i b = *reinterpret_cast<const v4i *>(xp);
+                    const v4i zero4 = {0, 0, 0, 0};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        d4[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fe_c[(t * KSe) * 64 + lane], b, zero4, 0, 0, 0);
+                }
+                for (int ks = 1; ks < KSe; ++ks) {
+                    const v4i b = *reinterpret_cast<const v4i *>(xp + 64 * ks);
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         d4[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fe_c[(t * KSe + ks) * 64 + lane], b, d4[t], 0, 0, 0);
@@ -273,16 +279,14 @@ __global__ __launch_bounds__(256, 2) void block_fused_kernel(const BlockArgs a)
                     const int oy = p / Wo, ox = p - oy * Wo;
                     const int8_t *src = t1 + ((oy * s) * W2 + ox * s) * 16;  // tap (0, 0) of the pixel, plane 0
                     v4i accd[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) accd[t] = v4i{0, 0, 0, 0};
+                    const v4i zero4 = {0, 0, 0, 0};
 #pragma unroll
                     for (int q = 0; q < 3; ++q) {
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
-                            // taps 9..11 do not exist: their lanes read nothing and contribute zeros
-                            v4i b = {0, 0, 0, 0};
-                            if (q < 2 || g == 0) b = *reinterpret_cast<const v4i *>(src + toff[q] + t * plane);
-                            accd[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(adw[t][q], b, accd[t], 0, 0, 0);
+                            // lanes whose tap does not exist (9..11) read tap 8 again, against zero weights
+                            const v4i b = *reinterpret_cast<const v4i *>(src + toff[q] + t * plane);
+                            accd[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(adw[t][q], b, q == 0 ? zero4 : accd[t], 0, 0, 0);
                         }
                     }
                     v4i b2;
