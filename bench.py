@@ -544,10 +544,28 @@ def extra_legs(P, torch, dev, batch, log):
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / reps
 
-        return dt, fused, io_bytes, mid_bytes
+        dt_graph = None
+        if batch <= 8:
+            # the same chain captured once in a HIP graph and replayed: what a serving loop would do
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    chain()
+            torch.cuda.current_stream().wait_stream(side)
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for _ in range(20):
+                graph.replay()
+            torch.cuda.synchronize()
+            dt_graph = (time.perf_counter() - tg) / 20
+        return dt, fused, io_bytes, mid_bytes, dt_graph
 
-    dt, fused, io_bytes, mid_bytes = time_chain(batch)
-    dt8, fused8, _io8, _mid8 = time_chain(8)
+    dt, fused, io_bytes, mid_bytes, _g = time_chain(batch)
+    dt8, fused8, _io8, _mid8, dt8_graph = time_chain(8)
 
     # weight preparation: float32 weights of all 34 pointwise and 17 depthwise layers through the
     # device quantisers (ternary absmean straight into the packed layout, 8-bit absmax)
@@ -594,8 +612,10 @@ def extra_legs(P, torch, dev, batch, log):
     log(f"[bench] activation quantiser {list(xa.shape)}: {da * 1e6:.1f} us, {alg / da / 1e9:.0f} GB/s algorithmic")
     del xa, qa
 
-    out["block_chain_batch8"] = {"us": round(dt8 * 1e6, 1), "fused_blocks": fused8}
-    log(f"[bench] 17-block chain at batch 8: {dt8 * 1e6:.1f} us per pass, fused: {', '.join(fused8)}")
+    out["block_chain_batch8"] = {"us": round(dt8 * 1e6, 1), "us_as_hip_graph": round(dt8_graph * 1e6, 1),
+                                 "fused_blocks": fused8}
+    log(f"[bench] 17-block chain at batch 8: {dt8 * 1e6:.1f} us per pass, {dt8_graph * 1e6:.1f} us replayed from a "
+        f"HIP graph; fused: {', '.join(fused8)}")
     out["block_chain"] = {"blocks": 17, "us": round(dt * 1e6, 1), "fused_blocks": fused,
                           "block_io_mb": round(io_bytes / 1e6, 1),
                           "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),

@@ -83,3 +83,63 @@ def test_mobilenetv2_block_chain(P, p_zero, input_hw, n):
     y_dev = P.prom_pw_conv(x_dev, dev(P.prom_pack_ternary(H.weight)), 1280, requant_dev(P, H))
     torch.cuda.synchronize()
     assert_same(y_dev.cpu().numpy(), oracle.pw_conv(x_host, H.weight, H.bias, H.mult, H.shift, 0, 127), "head")
+
+
+def test_chain_replays_from_a_captured_graph(P):
+    """The library's calls on a stream can be captured in a HIP graph (no allocation, no memset,
+    no host synchronisation inside a call once a shape has run): the 16 prom_block calls of the
+    body are captured once and replayed with new inputs, with eager work and synchronisations
+    between the replays; every replay must equal the eager result for the same input."""
+    torch = torch_cuda()
+    n, input_hw = 2, 32
+    blocks = [b for b in mobilenetv2_blocks(input_hw) if b.t != 1]
+    steps = []
+    ws_bytes = 0
+    x0 = torch.empty((n, blocks[0].hw_in, blocks[0].hw_in, blocks[0].cin), dtype=torch.int8, device="cuda")
+    cur = x0
+    for i, b in enumerate(blocks):
+        hw, ho = b.hw_in, (b.hw_in - 1) // b.stride + 1
+        B = make_block(7900 + i, 1, hw, hw, b.cin, b.t, b.cout, b.stride, expand_shift=_pw_shift(b.cin),
+                       dw_shift=DW_SHIFT, project_shift=_pw_shift(b.cin * b.t))
+        e, d, p = B.expand, B.dw, B.project
+        y = torch.empty((n, ho, ho, b.cout), dtype=torch.int8, device="cuda")
+        ws_bytes = max(ws_bytes, P.prom_block_workspace_size(n, hw, hw, b.cin, B.chid, b.cout, b.stride))
+        steps.append((cur, B.chid, b.cout, b.stride, dev(P.prom_pack_ternary(e.weight)), requant_dev(P, e),
+                      dev(d.weight), requant_dev(P, d), dev(P.prom_pack_ternary(p.weight)), requant_dev(P, p),
+                      B.add_residual, y))
+        cur = y
+    ws = torch.empty(ws_bytes, dtype=torch.int8, device="cuda")
+    outs = [s[-1] for s in steps]
+
+    def run_chain():
+        for (xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, y) in steps:
+            P.prom_block(xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, ws, y)
+
+    def new_input(seed):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        x0.copy_(torch.randint(0, 128, x0.shape, dtype=torch.int8, device="cuda", generator=g))
+
+    new_input(1)
+    run_chain()                       # warm-up: every shape has run once before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run_chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for seed in (2, 3, 4):
+        new_input(seed)
+        run_chain()
+        torch.cuda.synchronize()
+        want = [o.clone() for o in outs]
+        for o in outs:
+            o.fill_(-77)              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, (o, w) in enumerate(zip(outs, want)):
+            assert torch.equal(o, w), f"replay for input {seed}: block {blocks[k].name} differs from the eager run"
