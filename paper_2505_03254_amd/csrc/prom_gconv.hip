@@ -507,7 +507,9 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
             }
             const long long units = bd.G > 1 ? ((long long)n + bd.G - 1) / bd.G : (long long)n * bd.bands;
             bd.units = (int)units;
-            long long per_cb = (2 * 256 + bd.ncb - 1) / bd.ncb;  // two workgroups per compute unit
+            // two workgroups per compute unit, and not one more: a workgroup that does not fit in the
+            // first round starts when another has finished all its units and doubles the run time
+            long long per_cb = (2 * 256) / bd.ncb;
             if (per_cb > units) per_cb = units;
             if (per_cb < 1) per_cb = 1;
             bd.wgs_per_cb = (int)per_cb;
