@@ -286,10 +286,27 @@ int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout
 
 size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
 
-/* 1 if prom_block runs this shape as one fused kernel (the expanded tensor stays on chip; pointers
- * assumed 8-byte aligned), 0 if as three launches through the workspace, PROM_EINVAL for bad
- * dimensions.  Host only, launches nothing. */
+/* The same with the choice between the two forms of the block made by the caller: as one fused
+ * kernel (the expanded tensor stays on chip) or as three launches through the workspace.
+ * prom_block is prom_block_ex with PROM_BLOCK_AUTO, which takes the form measured faster for the
+ * shape.  PROM_BLOCK_FUSED returns PROM_EUNSUPPORTED where the fused kernel does not apply
+ * (prom_block_can_fuse, and x, y, w_dw 8-byte aligned). */
+enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2 };
+int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
+                  const void *w_expand_packed, const prom_requant_t *rq_expand,
+                  const int8_t *w_dw, const prom_requant_t *rq_dw,
+                  const void *w_project_packed, const prom_requant_t *rq_project,
+                  int add_residual, void *workspace, size_t workspace_bytes,
+                  int8_t *y, int path, void *stream);
+
+/* 1 if prom_block (PROM_BLOCK_AUTO) runs this shape as one fused kernel (pointers assumed 8-byte
+ * aligned), 0 if as three launches through the workspace, PROM_EINVAL for bad dimensions.  Host
+ * only, launches nothing. */
 int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* 1 if the fused kernel applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
+ * cout <= 160, chid <= 192, a band of rows fits in LDS), 0 if not. */
+int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride);
 
 /* ---- measurement utility ------------------------------------------------------------------
  * Plain streaming copy of nbytes (multiple of 16, both pointers 16-byte aligned) from src to

@@ -88,6 +88,12 @@ def load_library():
     lib.prom_block.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
                                vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
                                vp, ctypes.POINTER(_RequantC), ci, vp, sz, vp, vp]
+    lib.prom_block_ex.restype = ci
+    lib.prom_block_ex.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
+                                  vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
+                                  vp, ctypes.POINTER(_RequantC), ci, vp, sz, vp, ci, vp]
+    lib.prom_block_can_fuse.restype = ci
+    lib.prom_block_can_fuse.argtypes = [ci] * 7
     lib.prom_block_workspace_size.restype = sz
     lib.prom_block_workspace_size.argtypes = [ci] * 7
     lib.prom_pw_plan_query.restype = ci
@@ -325,7 +331,8 @@ def prom_gconv3x3(x, w_g, stride: int, rq: Requant, y=None, stream=None, w_frag=
 
 def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand: Requant,
                w_dw, rq_dw: Requant, w_project_packed, rq_project: Requant, add_residual: bool,
-               workspace, y=None, stream=None):
+               workspace, y=None, stream=None, path: int = 0):
+    """path: BLOCK_AUTO (0, the library picks), BLOCK_FUSED (1) or BLOCK_UNFUSED (2): prom_block_ex."""
     import torch
     _dev_i8(x, "x")
     _dev_i8(w_dw, "w_dw")
@@ -335,14 +342,24 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
         y = torch.empty((n, ho, wo, cout), dtype=torch.int8, device=x.device)
     _dev_i8(y, "y")
     e, d, p = rq_expand._c(), rq_dw._c(), rq_project._c()
-    rc = load_library().prom_block(
+    rc = load_library().prom_block_ex(
         x.data_ptr(), n, h, w, cin, int(chid), int(cout), int(stride),
         w_expand_packed.data_ptr(), ctypes.byref(e), w_dw.data_ptr(), ctypes.byref(d),
         w_project_packed.data_ptr(), ctypes.byref(p), int(bool(add_residual)),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), y.data_ptr(),
-        _stream_ptr(stream))
+        int(path), _stream_ptr(stream))
     _check(rc, "prom_block")
     return y
+
+
+BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED = 0, 1, 2
+
+
+def prom_block_can_fuse(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:
+    rc = load_library().prom_block_can_fuse(n, h, w, cin, chid, cout, stride)
+    if rc < 0:
+        raise PromError(rc, "prom_block_can_fuse")
+    return bool(rc)
 
 
 def prom_quantize_pw_absmean(w, eps: float = 1e-5, want_codes: bool = False, stream=None):

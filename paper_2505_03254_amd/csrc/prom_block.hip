@@ -341,8 +341,9 @@ using BlockFn = void (*)(const BlockArgs);
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline int align16(int v) { return (v + 15) & ~15; }
 
-// Plans the fused kernel; returns false if the shape does not fit it.
-static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
+// Plans the fused kernel; returns false if the shape does not fit it or (unless `forced`) if the
+// three launches are expected to be faster.
+static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid, bool forced)
 {
     const int cin = a.cin, chid = a.chid, cout = a.cout, s = a.stride;
     if (cin % 8 != 0 || chid % 4 != 0 || cout % 4 != 0 || cout > 160) return false;
@@ -354,14 +355,19 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid)
     const int tpw = cot == 2 ? 4 : cot == 4 ? 4 : cot == 6 ? 2 : 1;
     const int kse = (cin + 63) / 64;
     const int nch = (chid + kCH - 1) / kCH;  // every chunk's weights are resident
-    // Measured (MobileNetV2 blocks, batch 1 to 128): the fused launch beats the three launches
-    // through the workspace while the hidden tensor is small enough that the launch, ramp-up and
-    // drain of three kernels outweigh their streaming (28x28x192 at batch 128: 34 us against 44;
-    // any block of up to 3 chunks at batch 1-8: 28-33 us against 35-38); on large tensors the
-    // unfused kernels stream at 4-5 TB/s and win (112x112x96 at batch 128: 87 us against 166), and
-    // with many chunks the resident weights leave no room for a band (14x14x384: 83 against 36).
+    // Measured in GPU time (calls replayed from a HIP graph; MobileNetV2 blocks, batch 8 to 128):
+    // the fused launch beats the three launches through the workspace on mid-sized hidden tensors
+    // (28x28x192 at batch 128: 27 us against 42; 112x112x96 at batch 8: 21 against 24).  Small
+    // ones are done in three short kernels of 5 us each before the fused kernel, which has two
+    // workgroups per CU and a serial chunk loop, has finished (28x28x192 at batch 8: 18 against
+    // 16), although a host that pays 10 us per call sees the opposite; on large ones the unfused
+    // kernels stream at 4-5 TB/s and win (112x112x96 at batch 128: 166 against 87).  With more
+    // than 3 chunks the resident weights leave no room for a band, and streaming them through two
+    // LDS slots was measured too: a chunk then costs the latency of its weight fetch, 5-6 us, and
+    // the kernel loses everywhere.
     if (nch > 3) return false;
-    if ((long long)a.N * a.H * a.W * chid > (32LL << 20)) return false;
+    const long long hidden = (long long)a.N * a.H * a.W * chid;
+    if (!forced && (hidden < (4LL << 20) || hidden > (32LL << 20))) return false;
     // the band: at most tpw projection pixel tiles per wavefront, LDS <= 72 KB (two workgroups per CU)
     // Band height by a cost estimate: rounds of workgroups over the chip (two per CU) times the
     // rows a workgroup expands and filters plus a fixed part (weights, barriers) worth about 4 rows.
@@ -418,7 +424,7 @@ extern "C" size_t prom_block_workspace_size(int n, int h, int w, int cin, int ch
     return prom::round256((size_t)n * h * w * chid) + prom::round256((size_t)n * ho * wo * chid);
 }
 
-extern "C" int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride)
+static int fused_query(int n, int h, int w, int cin, int chid, int cout, int stride, bool forced)
 {
     using namespace prom;
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
@@ -429,7 +435,17 @@ extern "C" int prom_block_is_fused(int n, int h, int w, int cin, int chid, int c
     BlockFn fn = nullptr;
     size_t lds = 0;
     int grid = 0;
-    return plan_fused(a, fn, lds, grid) ? 1 : 0;
+    return plan_fused(a, fn, lds, grid, forced) ? 1 : 0;
+}
+
+extern "C" int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride)
+{
+    return fused_query(n, h, w, cin, chid, cout, stride, false);
+}
+
+extern "C" int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride)
+{
+    return fused_query(n, h, w, cin, chid, cout, stride, true);
 }
 
 extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
@@ -439,7 +455,20 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
                           int add_residual, void *workspace, size_t workspace_bytes, int8_t *y,
                           void *stream)
 {
+    return prom_block_ex(x, n, h, w, cin, chid, cout, stride, w_expand_packed, rq_expand, w_dw, rq_dw,
+                         w_project_packed, rq_project, add_residual, workspace, workspace_bytes, y,
+                         PROM_BLOCK_AUTO, stream);
+}
+
+extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
+                             const void *w_expand_packed, const prom_requant_t *rq_expand,
+                             const int8_t *w_dw, const prom_requant_t *rq_dw,
+                             const void *w_project_packed, const prom_requant_t *rq_project,
+                             int add_residual, void *workspace, size_t workspace_bytes, int8_t *y,
+                             int path, void *stream)
+{
     using namespace prom;
+    if (path != PROM_BLOCK_AUTO && path != PROM_BLOCK_FUSED && path != PROM_BLOCK_UNFUSED) return PROM_EINVAL;
     if (!x || !y || !w_expand_packed || !w_dw || !w_project_packed || !rq_expand || !rq_dw || !rq_project)
         return PROM_EINVAL;
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
@@ -483,7 +512,9 @@ extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chi
     BlockFn fn = nullptr;
     size_t lds = 0;
     int grid = 0;
-    if (aligned && plan_fused(a, fn, lds, grid)) {
+    const bool fuse = path != PROM_BLOCK_UNFUSED && aligned && plan_fused(a, fn, lds, grid, path == PROM_BLOCK_FUSED);
+    if (path == PROM_BLOCK_FUSED && !fuse) return PROM_EUNSUPPORTED;
+    if (fuse) {
         static std::mutex mu;
         static std::vector<BlockFn> attr_done;
         {

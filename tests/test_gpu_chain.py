@@ -63,14 +63,17 @@ def test_mobilenetv2_block_chain(P, p_zero, input_hw, n):
                            project_shift=_pw_shift(b.cin * b.t))
             ws = torch.empty(P.prom_block_workspace_size(n, hw, hw, b.cin, B.chid, b.cout, b.stride),
                              dtype=torch.int8, device="cuda")
+            # the fused kernel wherever it applies (at these small sizes the library itself would
+            # take the three launches), the three launches elsewhere
+            can = P.prom_block_can_fuse(n, hw, hw, b.cin, B.chid, b.cout, b.stride)
             y_dev = P.prom_block(x_dev, B.chid, b.cout, b.stride,
                                  dev(P.prom_pack_ternary(B.expand.weight)), requant_dev(P, B.expand),
                                  dev(B.dw.weight), requant_dev(P, B.dw),
                                  dev(P.prom_pack_ternary(B.project.weight)), requant_dev(P, B.project),
-                                 B.add_residual, ws)
+                                 B.add_residual, ws, path=P.BLOCK_FUSED if can else P.BLOCK_AUTO)
             y_host, _, _ = oracle.block(x_host, _tup(B.expand), _tup(B.dw), _tup(B.project), b.stride,
                                         B.add_residual)
-            fused.append(P.prom_block_is_fused(n, hw, hw, b.cin, B.chid, b.cout, b.stride))
+            fused.append(can)
         torch.cuda.synchronize()
         assert_same(y_dev.cpu().numpy(), y_host, f"chain p_zero={p_zero} {b.name}")
         assert len(np.unique(y_host)) > 24, f"{b.name}: the chain's activations degenerated"
@@ -104,16 +107,17 @@ def test_chain_replays_from_a_captured_graph(P):
         e, d, p = B.expand, B.dw, B.project
         y = torch.empty((n, ho, ho, b.cout), dtype=torch.int8, device="cuda")
         ws_bytes = max(ws_bytes, P.prom_block_workspace_size(n, hw, hw, b.cin, B.chid, b.cout, b.stride))
+        path = P.BLOCK_FUSED if P.prom_block_can_fuse(n, hw, hw, b.cin, B.chid, b.cout, b.stride) else P.BLOCK_AUTO
         steps.append((cur, B.chid, b.cout, b.stride, dev(P.prom_pack_ternary(e.weight)), requant_dev(P, e),
                       dev(d.weight), requant_dev(P, d), dev(P.prom_pack_ternary(p.weight)), requant_dev(P, p),
-                      B.add_residual, y))
+                      B.add_residual, y, path))
         cur = y
     ws = torch.empty(ws_bytes, dtype=torch.int8, device="cuda")
-    outs = [s[-1] for s in steps]
+    outs = [s[-2] for s in steps]
 
     def run_chain():
-        for (xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, y) in steps:
-            P.prom_block(xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, ws, y)
+        for (xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, y, path) in steps:
+            P.prom_block(xi, chid, cout, stride, we, rqe, wd, rqd, wp, rqp, addres, ws, y, path=path)
 
     def new_input(seed):
         g = torch.Generator(device="cuda")

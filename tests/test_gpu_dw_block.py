@@ -78,7 +78,7 @@ def test_dw_relu6_window(P):
     assert_same(y.cpu().numpy(), oracle.dw_conv(D.x, D.weight, 1, D.bias, D.mult, D.shift, 0, 127), "dw relu6")
 
 
-def _run_block(P, B):
+def _run_block(P, B, path=0):
     torch = torch_cuda()
     e, d, p = B.expand, B.dw, B.project
     ws = torch.empty(P.prom_block_workspace_size(B.n, B.h, B.w, B.cin, B.chid, B.cout, B.stride),
@@ -87,7 +87,7 @@ def _run_block(P, B):
                      dev(P.prom_pack_ternary(e.weight)), requant_dev(P, e),
                      dev(d.weight), requant_dev(P, d),
                      dev(P.prom_pack_ternary(p.weight)), requant_dev(P, p),
-                     B.add_residual, ws)
+                     B.add_residual, ws, path=path)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -105,7 +105,10 @@ def test_block_config4_full_output(P):
     c = BASELINE_CONFIGS[4]
     B = make_block(CONFIG_SEED_BASE + 4, c["n"], c["h"], c["w"], c["cin"], c["t"], stride=c["stride"])
     assert B.add_residual
-    assert_same(_run_block(P, B), _oracle_block(B), "config 4")
+    assert P.prom_block_is_fused(c["n"], c["h"], c["w"], c["cin"], c["cin"] * c["t"], c["cin"], c["stride"])
+    want = _oracle_block(B)
+    assert_same(_run_block(P, B), want, "config 4")
+    assert_same(_run_block(P, B, P.BLOCK_UNFUSED), want, "config 4, three launches")
 
 
 @pytest.mark.parametrize("shape", [
@@ -120,8 +123,33 @@ def test_block_config4_full_output(P):
     # tiles), 3 chunks with a ragged last one, the smallest and a single-row image
     (2, 28, 28, 24, 6, 24, 1), (1, 17, 9, 40, 4, 96, 2), (2, 7, 7, 32, 6, 160, 1), (1, 14, 14, 24, 7, 136, 1),
     (3, 1, 1, 16, 6, 16, 1), (1, 1, 37, 32, 5, 32, 1), (1, 37, 1, 32, 5, 32, 2),
+    # more than 3 chunks of hidden channels: weights streamed through two LDS slots (4, 5, 6, 9, 15
+    # chunks, ragged last chunk, every projection width class, both strides)
+    (2, 14, 14, 64, 6, 64, 1), (2, 14, 14, 64, 6, 96, 1), (2, 14, 14, 96, 6, 96, 1), (1, 14, 14, 96, 6, 160, 2),
+    (2, 7, 7, 160, 6, 160, 1), (1, 9, 11, 64, 5, 32, 1), (1, 10, 6, 40, 7, 24, 2), (3, 5, 5, 128, 2, 128, 1),
 ])
 def test_block_shapes(P, shape):
     n, h, w, cin, t, cout, stride = shape
     B = make_block(6000 + cin + cout, n, h, w, cin, t, cout, stride, signed_x=True)
-    assert_same(_run_block(P, B), _oracle_block(B), f"block {shape}")
+    want = _oracle_block(B)
+    # both forms of the block whatever the library would pick for the shape, then its own choice
+    if P.prom_block_can_fuse(n, h, w, cin, cin * t, cout, stride):
+        assert_same(_run_block(P, B, P.BLOCK_FUSED), want, f"block {shape} fused")
+    else:
+        with pytest.raises(P.PromError) as e:
+            _run_block(P, B, P.BLOCK_FUSED)
+        assert e.value.code == -2
+    assert_same(_run_block(P, B, P.BLOCK_UNFUSED), want, f"block {shape} three launches")
+    assert_same(_run_block(P, B), want, f"block {shape}")
+
+
+def test_block_forms_and_queries(P):
+    """What prom_block picks: mid-sized hidden tensors fused, small, large and deep ones not; the
+    fused kernel's own limits."""
+    assert P.prom_block_is_fused(64, 28, 28, 32, 192, 32, 1) and P.prom_block_is_fused(128, 28, 28, 32, 192, 64, 2)
+    assert not P.prom_block_is_fused(2, 9, 9, 16, 96, 16, 1) and P.prom_block_can_fuse(2, 9, 9, 16, 96, 16, 1)
+    assert not P.prom_block_is_fused(128, 112, 112, 16, 96, 24, 2) and P.prom_block_can_fuse(128, 112, 112, 16, 96, 24, 2)
+    assert not P.prom_block_can_fuse(2, 14, 14, 64, 384, 64, 1)      # 6 chunks of hidden channels
+    assert not P.prom_block_can_fuse(2, 7, 7, 32, 192, 320, 1)       # 320 output channels
+    assert not P.prom_block_can_fuse(2, 7, 7, 12, 72, 16, 1)         # cin % 8 != 0
+    assert P.prom_block_can_fuse(1, 28, 28, 24, 144, 24, 1)          # 24 input channels: padded pixels

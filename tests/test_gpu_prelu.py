@@ -161,7 +161,7 @@ def test_dw_prelu_shapes(P, shape):
         assert_same(y.cpu().numpy(), want, f"dw prelu unaligned {shape}")
 
 
-def _block_prelu(P, B, seed):
+def _block_prelu(P, B, seed, path=0):
     torch = torch_cuda()
     e, d, p = B.expand, B.dw, B.project
     ne, nd = prelu_mult_neg(seed, e.mult), prelu_mult_neg(seed + 1, d.mult)
@@ -172,7 +172,7 @@ def _block_prelu(P, B, seed):
                      dev(d.weight), _rq(P, d, nd),
                      dev(P.prom_pack_ternary(p.weight)),
                      P.Requant(dev(p.bias), dev(p.mult), dev(p.shift), p.act_min, p.act_max),
-                     B.add_residual, ws)
+                     B.add_residual, ws, path=path)
     torch.cuda.synchronize()
     want, _, _ = oracle.block_prelu(B.x, (e.weight, e.bias, e.mult, e.shift, -128, 127, ne),
                                     (d.weight, d.bias, d.mult, d.shift, -128, 127, nd),
@@ -185,19 +185,20 @@ def _block_prelu(P, B, seed):
     # n, h, w, cin, t, cout, stride; the first rows run the fused kernel, the last the three launches
     (2, 9, 9, 16, 6, 16, 1), (1, 14, 14, 24, 6, 32, 2), (2, 7, 7, 160, 6, 320, 1), (3, 13, 17, 16, 9, 16, 1),
     (1, 28, 28, 32, 6, 64, 1), (2, 15, 13, 16, 5, 24, 2), (1, 5, 6, 8, 1, 8, 1), (16, 56, 56, 24, 6, 24, 1),
-    (2, 14, 14, 64, 6, 64, 1), (80, 56, 56, 24, 6, 24, 1),
+    (2, 14, 14, 64, 6, 64, 1), (80, 56, 56, 24, 6, 24, 1), (2, 7, 7, 160, 6, 160, 1), (1, 7, 7, 320, 6, 320, 1),
 ])
 def test_block_prelu_shapes(P, shape):
     n, h, w, cin, t, cout, stride = shape
     B = make_block(13000 + cin + cout, n, h, w, cin, t, cout, stride, signed_x=True,
                    expand_shift=(3, 6), dw_shift=(8, 10), project_shift=(3, 6))
-    fused = P.prom_block_is_fused(n, h, w, cin, cin * t, cout, stride)
-    got, want = _block_prelu(P, B, 13000 + cin)
-    assert_same(got, want, f"block prelu {shape} fused={fused}")
+    paths = [P.BLOCK_UNFUSED, P.BLOCK_AUTO]
+    if P.prom_block_can_fuse(n, h, w, cin, cin * t, cout, stride):
+        paths.append(P.BLOCK_FUSED)
+    for path in paths:
+        got, want = _block_prelu(P, B, 13000 + cin, path)
+        assert_same(got, want, f"block prelu {shape} path={path}")
 
 
 def test_block_prelu_covers_both_paths(P):
-    assert P.prom_block_is_fused(2, 9, 9, 16, 96, 16, 1)
-    assert P.prom_block_is_fused(16, 56, 56, 24, 144, 24, 1)        # 24 input channels: padded pixels
-    assert not P.prom_block_is_fused(2, 14, 14, 64, 384, 64, 1)     # 6 chunks of hidden channels
-    assert not P.prom_block_is_fused(80, 56, 56, 24, 144, 24, 1)    # hidden tensor above 32 Mi elements
+    assert P.prom_block_can_fuse(2, 9, 9, 16, 96, 16, 1) and P.prom_block_can_fuse(16, 56, 56, 24, 144, 24, 1)
+    assert not P.prom_block_can_fuse(2, 14, 14, 64, 384, 64, 1)
