@@ -55,8 +55,8 @@ enum {
 /* Per-output-channel requantisation and activation window.  The struct itself is read on
  * the host at call time; its arrays are device memory of C int32 values each.
  *
- * PReLU (the paper's MobileNetV2 and RegNetX models replace ReLU6 / ReLU by PReLU, Section 4,
- * experimental setup): with mult_neg != NULL the multiplier of an output follows the sign of
+ * PReLU (the paper's MobileNetV2 and RegNetX models replace ReLU6 / ReLU by PReLU, Section 3.2,
+ * last paragraph): with mult_neg != NULL the multiplier of an output follows the sign of
  * s = acc + bias[c] (which is the sign of the real pre-activation, the scales being positive):
  *     m = s >= 0 ? mult[c] : mult_neg[c]
  *     q = floor((s*m + 2^(30+shift[c])) / 2^(31+shift[c])),  then the window and the residual

@@ -29,7 +29,7 @@
  * intermediate fits in int64.
  *
  * PReLU variant (the *_prelu functions; the paper's MobileNetV2 and RegNetX models replace
- * ReLU6 / ReLU by PReLU, Section 4 "Experimental Setup"; PReLU itself is
+ * ReLU6 / ReLU by PReLU, Section 3.2, last paragraph; PReLU itself is
  * f(z) = z for z >= 0 and a_c * z for z < 0 with one learned slope a_c per channel).  The
  * real pre-activation is z = sigma_c * s with sigma_c > 0, so its sign is the sign of s, and
  * the slope folds into a second multiplier mult_neg[c] ~ a_c * mult[c] (same shift, any

@@ -251,7 +251,7 @@ def block(x, expand, dw, project, stride: int, add_residual: bool):
 
 def block_prelu(x, expand, dw, project, stride: int, add_residual: bool):
     """The block with PReLU after the expand and depthwise layers (the paper's MobileNetV2
-    variant, Section 4): the three layer functions chained.  expand and dw are tuples
+    variant, Section 3.2): the three layer functions chained.  expand and dw are tuples
     (weight, bias, mult, shift, act_min, act_max, mult_neg); project as in block()."""
     we, be, me, se, loe, hie, ne = expand
     wd_, bd, md, sd, lod, hid, nd = dw

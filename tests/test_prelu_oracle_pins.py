@@ -1,5 +1,5 @@
 """Pins of the oracle's PReLU requantisation (the paper's MobileNetV2 / RegNetX models use
-PReLU where the original networks have ReLU6 / ReLU: Section 4, experimental setup).
+PReLU where the original networks have ReLU6 / ReLU: Section 3.2, last paragraph).
 
 The integer form is this build's contract; it is pinned here against
   - the plain requantisation, which it must equal when both multipliers are the same

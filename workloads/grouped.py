@@ -1,7 +1,8 @@
 """Shapes of the grouped 3x3 convolutions of the other two architecture families the paper
-evaluates (RegNetX and ResNeXt, Section 4), from their public architecture tables at 224x224
-input.  Each bottleneck block has one grouped 3x3 conv with as many outputs as inputs; the first
-block of a stage has stride 2 (ResNeXt's first stage: stride 1)."""
+evaluates (RegNetX and ResNeXt: Section 2 describes their group sizes above one, Section 5 lists
+the models), from their public architecture tables at 224x224 input.  Each bottleneck block has
+one grouped 3x3 conv with as many outputs as inputs; the first block of a stage has stride 2
+(ResNeXt's first stage: stride 1)."""
 from __future__ import annotations
 
 from dataclasses import dataclass
