@@ -2,6 +2,7 @@
 // C entry points) and the generic any-shape kernel.  The streaming kernel lives in
 // prom_pw_stream.h and is instantiated per NT in prom_pw_inst.hip.
 #include "prom_pw_rows.h"
+#include "prom_pw_expand.h"
 #include "prom_launch.h"
 
 #include <mutex>
@@ -106,6 +107,10 @@ constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flig
 constexpr int kBatchNTDeep = 3;
 constexpr int kBatchDeepKS = 10;
 __host__ __device__ constexpr int batch_nt(int ks) { return ks >= kBatchDeepKS ? kBatchNTDeep : kBatchNT; }
+// Pixel tiles per unit of pw_expand_body by number of k steps (registers: 4 per tile and k step).
+constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2;
+__host__ __device__ constexpr int expand_g(int ks) { return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : kExpandG3; }
+constexpr int kExpandLds = 52 * 1024;  // three workgroups per CU
 
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
@@ -118,6 +123,17 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     const int nblk = b.start[i + 1] - b.start[i];
     const PwArgs &a = b.layer[i];
     const int lid = logical_block_id(local, nblk);
+    // a.cw != 0: the host planned the layer for the body that keeps the activations of a pixel
+    // group in registers while it walks over the output channels
+    if (a.cw) {
+        if (a.KS == 1)
+            pw_expand_body<1, kExpandG1>(a, lid, lds_raw);
+        else if (a.KS == 2)
+            pw_expand_body<2, kExpandG2>(a, lid, lds_raw);
+        else
+            pw_expand_body<3, kExpandG3>(a, lid, lds_raw);
+        return;
+    }
     // FULLW bodies (every chunk 16*NT channels wide) have no per-lane conditions in the epilogue;
     // with one k step there is no branch around the epilogue either, so the waits on the prefetch
     // ring are exact (a store in a conditional epilogue makes them conservative)
@@ -516,6 +532,23 @@ static bool conflicts(const PwArgs &a, const PwArgs &b)
     return hits(ya, wb) || hits(yb, wa);
 }
 
+// Sub-chunks (64 output channels) per part if the layer is one for pw_expand_body, else 0:
+// at most 3 k steps, whole sub-chunks, plain epilogue without residual, and fewer passes over
+// the activations than the streaming body's chunks would make.
+static int expand_plan(const PwArgs &m, int *nparts)
+{
+    if (m.residual || m.mult_neg || m.Nc % 64 != 0 || m.KS > 3 || m.K % 16 != 0) return 0;
+    const int sc_total = m.Nc / 64;
+    int nmax = 1;
+    while (nmax < sc_total && lds_bytes_expand(nmax + 1, m.KS) <= (size_t)kExpandLds) ++nmax;
+    const int parts = (sc_total + nmax - 1) / nmax;
+    const int nt = batch_nt(m.KS);
+    const int chunks = (m.Nc / 16 + nt - 1) / nt;
+    if (parts >= chunks) return 0;
+    *nparts = parts;
+    return (sc_total + parts - 1) / parts;
+}
+
 static int launch_batch(const PwLaunch *const *members, int count, hipStream_t st)
 {
     static thread_local PwBatchArgs b;
@@ -530,7 +563,12 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     for (int i = 0; i < count; ++i) {
         const PwArgs &m = members[i]->a;
         const int nt = batch_nt(m.KS);
-        total_work += (long long)m.M * (m.K + 16 * nt) * (((m.Nc + 15) / 16 + nt - 1) / nt);
+        int parts = 0;
+        const int nsc = expand_plan(m, &parts);
+        if (nsc)
+            total_work += (long long)m.M * ((long long)m.K * parts + m.Nc);
+        else
+            total_work += (long long)m.M * (m.K + 16 * nt) * (((m.Nc + 15) / 16 + nt - 1) / nt);
     }
     for (int i = 0; i < count; ++i) {
         // re-planned for the batch body: PT = 1, plain streaming (measured: the row-cooperative
@@ -540,15 +578,36 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         a.cw = 0;
         const int n_tiles = (a.Nc + 15) / 16;
         const int nt = batch_nt(a.KS);
-        a.n_chunks = (n_tiles + nt - 1) / nt;
-        a.units = (a.M + 15) / 16;
+        int parts = 0;
+        const int nsc = expand_plan(a, &parts);
+        long long work;  // bytes one chunk (or part) moves
+        size_t l;
+        if (nsc) {
+            a.cw = nsc;
+            a.n_chunks = parts;
+            a.units = (a.M + 16 * expand_g(a.KS) - 1) / (16 * expand_g(a.KS));
+            work = (long long)a.M * (a.K + 64 * nsc);
+            l = lds_bytes_expand(nsc, a.KS);
+        } else {
+            a.n_chunks = (n_tiles + nt - 1) / nt;
+            a.units = (a.M + 15) / 16;
+            work = (long long)a.M * (a.K + 16 * nt);
+            l = lds_bytes_fast(nt, a.KS);
+        }
         const long long wg_units = (a.units + 3) / 4;
-        const long long work = (long long)a.M * (a.K + 16 * nt);  // bytes one chunk moves
         const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
                                  : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
                                                                    : kBatchBytesPerWg / 4;
         done_work += work * a.n_chunks;
         long long wgs = (work + per_wg - 1) / per_wg;
+        if (nsc) {
+            // units are large here (16*G pixels x all channels of the part): give every wavefront
+            // the same whole number of them
+            const long long unit_bytes = 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
+            long long upw = (per_wg + 2 * unit_bytes) / (4 * unit_bytes);
+            if (upw < 1) upw = 1;
+            wgs = (a.units + 4 * upw - 1) / (4 * upw);
+        }
         if (wgs < 1) wgs = 1;
         if (wgs > wg_units) wgs = wg_units;
         a.wg_per_chunk = (int)wgs;
@@ -556,7 +615,6 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         b.layer[i] = a;
         b.start[i] = start;
         start += nblk;
-        const size_t l = lds_bytes_fast(nt, a.KS);
         if (l > lds) lds = l;
     }
     b.start[count] = start;

@@ -1,0 +1,186 @@
+// Pointwise layer with few input and many output channels (the expansion layers of the
+// inverted-residual blocks, Section 2): the activations of a pixel group stay in registers while
+// the wavefront walks over the output channels, so that they pass through the memory pipeline
+// once per part of the output channels instead of once per 64 of them.
+//
+// Work division.  The output channels are cut into sub-chunks of 64 (4 MFMA tiles) and the
+// sub-chunks into parts of up to a.cw consecutive ones; a workgroup belongs to one part (decoded
+// fragments and parameters of all its sub-chunks in LDS) and its 4 wavefronts take pixel units of
+// 16*G pixels round robin with the other workgroups of the part.  Per unit a wavefront holds
+// G x KSC B operands (16 bytes per lane each), and for every sub-chunk and pixel tile runs
+// 4 x KSC MFMAs, requantises and stores 16 pixels x 64 channels.  The B operands of the next unit
+// are fetched tile by tile during the last sub-chunk, right after a tile's last MFMA.
+//
+// Limits (checked on the host): K % 16 == 0, K <= 64*KSC, Nc % 64 == 0, no residual, no PReLU,
+// tensors below 2^30 bytes.
+#pragma once
+#include "prom_pw_stream.h"
+
+namespace prom {
+
+// LDS bytes: fragments and parameters of a part, one 16 x 64-byte staging tile per wavefront.
+__host__ __device__ constexpr size_t lds_bytes_expand(int nsc, int ks)
+{
+    return (size_t)nsc * (4 * ks * 1024 + 1024) + 4 * 1024;
+}
+
+// Decode the weights of sub-chunks [sc0, sc0 + nsc) into frag[nsc][4][KSC][64 lanes] and their
+// requantisation parameters into lpar[nsc][4][4 g][4 r] = (C lo, C hi, mult, shift); all global
+// loads of a thread are issued before the first decode.  Ends with the workgroup barrier.
+template <int KSC>
+__device__ __forceinline__ void stage_part(const PwArgs &a, int sc0, int nsc, v4i *frag, v4i *lpar)
+{
+    const int tid = threadIdx.x;
+    const int nfrag = nsc * 4 * KSC * 64;
+    constexpr int U = 12;  // words in flight per thread
+    for (int base = 0; base < nfrag; base += 256 * U) {
+        uint32_t word[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            const int tk = idx >> 6;  // (sub-chunk, tile, k step)
+            const int ks = tk % KSC;
+            const int t = (tk / KSC) & 3;
+            const int s = tk / (4 * KSC);
+            const int i = idx & 15;
+            const int c = (sc0 + s) * 64 + chan_of<4>(t, i >> 2, i & 3);
+            const int kw = 4 * ks + ((idx & 63) >> 4);
+            const bool ok = idx < nfrag && kw < a.KW;
+            const uint32_t v = a.wq[ok ? (long long)c * a.KW + kw : 0];
+            word[q] = ok ? v : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256 + tid;
+            if (idx < nfrag) frag[idx] = decode_word(word[q]);
+        }
+    }
+    for (int p = tid; p < nsc * 64; p += 256) {
+        const int c = (sc0 + (p >> 6)) * 64 + chan_of<4>((p >> 4) & 3, (p >> 2) & 3, p & 3);
+        lpar[p] = requant_params(a.bias[c], a.mult[c], 0, a.shift[c], false);
+    }
+    __syncthreads();
+}
+
+template <int KSC, int G>
+__device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15;
+    const int g = lane >> 4;
+
+    const int nparts = a.n_chunks;
+    const int part = lid % nparts;
+    const int wg = lid / nparts;
+    if (wg >= a.wg_per_chunk) return;
+    const int nsc_max = a.cw;
+    const int sc0 = part * nsc_max;
+    const int nsc = min(nsc_max, (a.Nc >> 6) - sc0);  // sub-chunks of this part (>= 1)
+    const int K = a.K, Nc = a.Nc;
+
+    v4i *frag = reinterpret_cast<v4i *>(lds_raw);  // [nsc][4 tiles][KSC][64 lanes]
+    v4i *lpar = frag + nsc_max * 4 * KSC * 64;     // [nsc][4 tiles][4 g][4 r]
+    unsigned char *stage = reinterpret_cast<unsigned char *>(lpar + nsc_max * 64) + wave * 1024;
+
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.M * K, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.M * Nc, kBufFlags);
+
+    const int Wv = a.wg_per_chunk * 4;
+    const int w0 = wg * 4 + wave;
+    // Offsets are unsigned and saturate beyond the tensor, where loads read zero and stores are
+    // dropped, so a unit past the end of the layer (or its ragged last tiles) needs no branch.
+    unsigned xoff = min((unsigned)kOobOffset, (unsigned)(w0 * (16 * G) + j) * (unsigned)K + 16u * g);
+    const unsigned xstep = (unsigned)Wv * (16 * G) * (unsigned)K;
+    v4i B[G][KSC];
+    // The whole offset sits in the vector operand (plus an immediate), which is what the range
+    // check of a raw buffer covers.
+    auto load_tile = [&](int gi) {
+        const unsigned xo = min(xoff + (unsigned)((16 * gi) * K), (unsigned)kOobOffset);
+#pragma unroll
+        for (int k = 0; k < KSC; ++k)
+            B[gi][k] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(xo + 64u * k), 0, 0);
+    };
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) load_tile(gi);
+    xoff = min(xoff + xstep, (unsigned)kOobOffset);
+
+    stage_part<KSC>(a, sc0, nsc, frag, lpar);
+
+    // any shift of the part equal to 0 -> the general form of the requantisation
+    bool sh0 = false;
+    for (int c = lane; c < nsc * 64; c += 64) sh0 |= lpar[c][3] == 0;
+    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    // staged tile -> global: piece `lane` is bytes [16*(lane&3), +16) of pixel row lane>>2
+    const unsigned goff = (unsigned)(lane >> 2) * (unsigned)Nc + 16u * (lane & 3);
+    unsigned ytile = min((unsigned)kOobOffset, (unsigned)(w0 * (16 * G)) * (unsigned)Nc + (unsigned)(sc0 * 64));
+    const unsigned ystep = (unsigned)Wv * (16 * G) * (unsigned)Nc;
+    const int my_units = w0 < a.units ? (a.units - w0 + Wv - 1) / Wv : 0;
+    const v4i zero4 = {0, 0, 0, 0};
+
+    auto run = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        auto sub_chunk = [&](const int sc, auto last_tag) {
+            constexpr bool LAST = decltype(last_tag)::value;
+            v4i par[4][4];
+            const v4i *lpg = lpar + sc * 64 + g * 4;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    par[t][r] = lpg[t * 16 + r];
+                    if constexpr (MODE == 0) par[t][r][3] -= 1;
+                }
+            const v4i *fk = frag + sc * 4 * KSC * 64 + lane;
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                v4i acc[4];
+#pragma unroll
+                for (int k = 0; k < KSC; ++k) {
+                    // opaque offset: with several k steps the fragment reads stay next to their
+                    // MFMAs instead of being kept in 16*KSC registers across the pixel tiles
+                    int fo = k * 64;
+                    if constexpr (KSC > 1) asm volatile("" : "+v"(fo));
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KSC * 64 + fo], B[gi][k],
+                                                                       k == 0 ? zero4 : acc[t], 0, 0, 0);
+                }
+                if constexpr (LAST) load_tile(gi);  // this tile of the next unit
+                uint32_t out[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    int v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = requant_mode<MODE>(acc[t][r], par[t][r], lo, hi);
+                    out[t] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                }
+                // the lane's 16 channels of pixel j: tile t holds channels 16*g + 4*t + r
+                // (16-byte columns swizzled by the row so that neither side has bank conflicts)
+                *reinterpret_cast<v4i *>(stage + j * 64 + 16 * (g ^ (j >> 2))) =
+                    v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+                const v4i v = *reinterpret_cast<const v4i *>(stage + (lane >> 2) * 64 + 16 * ((lane & 3) ^ (lane >> 4)));
+                const unsigned tile_off = ytile + (unsigned)((16 * gi) * Nc + sc * 64);
+                // offset in the vector operand (see the streaming kernel's store)
+                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(goff + tile_off, (unsigned)kOobOffset), 0, 0);
+            }
+        };
+        for (int u = 0; u < my_units; ++u) {
+#pragma nounroll
+            for (int sc = 0; sc + 1 < nsc; ++sc) sub_chunk(sc, std::false_type{});
+            sub_chunk(nsc - 1, std::true_type{});
+            xoff = min(xoff + xstep, (unsigned)kOobOffset);
+            ytile = min(ytile + ystep, (unsigned)kOobOffset);
+        }
+    };
+    if (general_shift)
+        run(std::integral_constant<int, 1>{});
+    else
+        run(std::integral_constant<int, 0>{});
+}
+
+}  // namespace prom

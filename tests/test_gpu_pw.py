@@ -323,3 +323,35 @@ def test_sequence_puts_large_layers_into_one_launch(P):
     m = oracle.pw_conv(A.x, A.weight, A.bias, A.mult, A.shift, -128, 127)
     want = oracle.pw_conv(m, Bq.weight, Bq.bias, Bq.mult, Bq.shift, -128, 127)
     assert_same(out.cpu().numpy(), want, "dependent large layers")
+
+
+def test_sequence_expansion_layers_keep_activations_in_registers(P):
+    """Layers with at most 192 input channels and a multiple of 64 output channels, no residual,
+    take a body of their own inside the shared launch (activations of a pixel group in registers,
+    output channels walked in sub-chunks of 64, in parts when their fragments do not fit LDS
+    together).  One, two and three k steps with and without a ragged last step, part counts 1..5
+    with an uneven last part, pixel counts that leave ragged units and tiles, channels with shift
+    0 (general form of the requantisation) in one layer only; buffers pre-filled so that a
+    missed or misplaced store shows; neighbours in the launch that take the streaming body."""
+    torch = torch_cuda()
+    cases = [  # n, h, w, cin, cout, shift_range
+        (3, 7, 9, 32, 192, (3, 8)), (2, 14, 14, 64, 384, (3, 8)), (5, 5, 5, 16, 64 * 9, (2, 6)),
+        (1, 31, 3, 48, 64 * 10, (0, 4)), (3, 14, 14, 96, 576, (3, 8)), (2, 9, 11, 128, 64 * 11, (1, 7)),
+        (4, 7, 7, 160, 960, (3, 8)), (1, 13, 13, 192, 64 * 7, (0, 3)), (2, 6, 7, 144, 128, (2, 9)),
+        (1, 1, 1, 64, 128, (3, 8)), (1, 1, 17, 80, 256, (3, 8)),
+        (2, 7, 7, 320, 1280, (3, 8)), (3, 7, 9, 384, 64, (3, 8)), (3, 7, 9, 64, 96, (3, 8)),  # streaming body
+    ]
+    layers, wants = [], []
+    for i, (n, h, w, cin, cout, sr) in enumerate(cases):
+        L = make_pw_layer(9500 + i, n, h, w, cin, cout, signed_x=True, act_window=(-128, 127), shift_range=sr)
+        y = torch.full((n, h, w, cout), -99, dtype=torch.int8, device="cuda")
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, requant_dev(P, L), None, y))
+        wants.append(oracle_pw(oracle, L))
+    seq = P.PwSequence(layers)
+    for run in range(2):
+        for l in layers:
+            l[5].fill_(-99)
+        seq.run()
+        torch.cuda.synchronize()
+        for c, l, want in zip(cases, layers, wants):
+            assert_same(l[5].cpu().numpy(), want, f"run {run}: case {c}")
