@@ -106,12 +106,59 @@ constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flig
 // resident workgroups) of the whole launch.
 constexpr int kBatchNTDeep = 3;
 constexpr int kBatchDeepKS = 10;
-__host__ __device__ constexpr int batch_nt(int ks) { return ks >= kBatchDeepKS ? kBatchNTDeep : kBatchNT; }
+// The narrower body also takes the PReLU layers whose last chunk is ragged: the PReLU epilogue
+// with per-lane channel conditions at 4 tiles is the one combination above 168 registers, which
+// would cost every member of the launch its third wavefront per SIMD.
+__host__ __device__ constexpr int batch_nt(int ks, bool prelu_ragged)
+{
+    return ks >= kBatchDeepKS || prelu_ragged ? kBatchNTDeep : kBatchNT;
+}
+__host__ __device__ inline int batch_nt(const PwArgs &a)
+{
+    return batch_nt(a.KS, a.mult_neg != nullptr && a.Nc % (16 * kBatchNT) != 0);
+}
 // Pixel tiles per unit of pw_expand_body by number of k steps (registers: 4 per tile and k step).
 constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2;
 __host__ __device__ constexpr int expand_g(int ks) { return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : kExpandG3; }
 constexpr int kExpandLds = 52 * 1024;  // three workgroups per CU
 
+// One member's work with the epilogue kind E (plain or PReLU) fixed at compile time.
+template <int E>
+__device__ __forceinline__ void pw_batch_member(const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    // FULLW bodies (every chunk 16*NT channels wide) have no per-lane conditions in the epilogue;
+    // with one k step there is no branch around the epilogue either, so the waits on the prefetch
+    // ring are exact (a store in a conditional epilogue makes them conservative)
+    if (batch_nt(a) == kBatchNTDeep) {
+        if (a.Nc % (16 * kBatchNTDeep) == 0)
+            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
+        else
+            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
+    } else if (a.Nc % (16 * kBatchNT) == 0) {
+        if (a.KS == 1)
+            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, E>(a, lid, lds_raw);
+        else
+            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
+    } else {
+        if constexpr (E == kEpiPlain)  // (a PReLU layer with a ragged last chunk has the narrow body)
+            pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
+    }
+}
+
+template <bool PRELU>
+__device__ __forceinline__ void pw_expand_member(const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    if (a.KS == 1)
+        pw_expand_body<1, kExpandG1, PRELU>(a, lid, lds_raw);
+    else if (a.KS == 2)
+        pw_expand_body<2, kExpandG2, PRELU>(a, lid, lds_raw);
+    else
+        pw_expand_body<3, kExpandG3, PRELU>(a, lid, lds_raw);
+}
+
+// EPI: kEpiPlain if no member is a PReLU layer, else kEpiBoth.  A launch of both kinds runs each
+// member through a copy of the bodies compiled for its kind alone (a body that carries both
+// epilogues needs more registers than either).
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
 {
@@ -125,31 +172,19 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     const int lid = logical_block_id(local, nblk);
     // a.cw != 0: the host planned the layer for the body that keeps the activations of a pixel
     // group in registers while it walks over the output channels
-    if (a.cw) {
-        if (a.KS == 1)
-            pw_expand_body<1, kExpandG1>(a, lid, lds_raw);
-        else if (a.KS == 2)
-            pw_expand_body<2, kExpandG2>(a, lid, lds_raw);
-        else
-            pw_expand_body<3, kExpandG3>(a, lid, lds_raw);
-        return;
+    if constexpr (EPI != kEpiPlain) {
+        if (a.mult_neg) {
+            if (a.cw)
+                pw_expand_member<true>(a, lid, lds_raw);
+            else
+                pw_batch_member<kEpiPrelu>(a, lid, lds_raw);
+            return;
+        }
     }
-    // FULLW bodies (every chunk 16*NT channels wide) have no per-lane conditions in the epilogue;
-    // with one k step there is no branch around the epilogue either, so the waits on the prefetch
-    // ring are exact (a store in a conditional epilogue makes them conservative)
-    if (a.KS >= kBatchDeepKS) {
-        if (a.Nc % (16 * kBatchNTDeep) == 0)
-            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, EPI>(a, lid, lds_raw);
-        else
-            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, EPI>(a, lid, lds_raw);
-    } else if (a.Nc % (16 * kBatchNT) == 0) {
-        if (a.KS == 1)
-            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, EPI>(a, lid, lds_raw);
-        else
-            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, EPI>(a, lid, lds_raw);
-    } else {
-        pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, EPI>(a, lid, lds_raw);
-    }
+    if (a.cw)
+        pw_expand_member<false>(a, lid, lds_raw);
+    else
+        pw_batch_member<kEpiPlain>(a, lid, lds_raw);
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst,
@@ -507,7 +542,7 @@ static bool batchable(const PwLaunch &L)
 {
     const PwArgs &a = L.a;
     if (!L.fast || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
-    if (batch_nt(a.KS) * a.KS * 1024 > kLdsBudget) return false;
+    if (batch_nt(a) * a.KS * 1024 > kLdsBudget) return false;
     return (long long)a.M * (a.K + a.Nc) <= kBatchMaxBytes;
 }
 
@@ -533,16 +568,16 @@ static bool conflicts(const PwArgs &a, const PwArgs &b)
 }
 
 // Sub-chunks (64 output channels) per part if the layer is one for pw_expand_body, else 0:
-// at most 3 k steps, whole sub-chunks, plain epilogue without residual, and fewer passes over
+// at most 3 k steps, whole sub-chunks, no residual, and fewer passes over
 // the activations than the streaming body's chunks would make.
 static int expand_plan(const PwArgs &m, int *nparts)
 {
-    if (m.residual || m.mult_neg || m.Nc % 64 != 0 || m.KS > 3 || m.K % 16 != 0) return 0;
+    if (m.residual || m.Nc % 64 != 0 || m.KS > 3 || m.K % 16 != 0) return 0;
     const int sc_total = m.Nc / 64;
     int nmax = 1;
     while (nmax < sc_total && lds_bytes_expand(nmax + 1, m.KS) <= (size_t)kExpandLds) ++nmax;
     const int parts = (sc_total + nmax - 1) / nmax;
-    const int nt = batch_nt(m.KS);
+    const int nt = batch_nt(m);
     const int chunks = (m.Nc / 16 + nt - 1) / nt;
     if (parts >= chunks) return 0;
     *nparts = parts;
@@ -562,7 +597,7 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     long long total_work = 0, done_work = 0;
     for (int i = 0; i < count; ++i) {
         const PwArgs &m = members[i]->a;
-        const int nt = batch_nt(m.KS);
+        const int nt = batch_nt(m);
         int parts = 0;
         const int nsc = expand_plan(m, &parts);
         if (nsc)
@@ -577,7 +612,7 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         PwArgs a = members[i]->a;
         a.cw = 0;
         const int n_tiles = (a.Nc + 15) / 16;
-        const int nt = batch_nt(a.KS);
+        const int nt = batch_nt(a);
         int parts = 0;
         const int nsc = expand_plan(a, &parts);
         long long work;  // bytes one chunk (or part) moves

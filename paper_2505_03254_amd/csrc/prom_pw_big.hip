@@ -40,6 +40,24 @@ size_t pw_big_body_lds(int body, const PwArgs &a)
     }
 }
 
+// One member's work with the epilogue kind E (plain or PReLU) fixed at compile time.
+template <int E>
+__device__ __forceinline__ void pw_big_member(int body, const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    switch (body) {
+    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true, ring_depth<4>(), E>(a, lid, lds_raw); break;
+    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true, ring_depth<1>(), E>(a, lid, lds_raw); break;
+    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false, ring_depth<2>(), E>(a, lid, lds_raw); break;
+    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), E>(a, lid, lds_raw); break;
+    case kBodyR3x8: pw_rows_body<3, true, 8, 4, E>(a, lid, lds_raw); break;
+    case kBodyR3: pw_rows_body<3, true, 16, 4, E>(a, lid, lds_raw); break;
+    default: pw_rows_body<6, true, 16, 4, E>(a, lid, lds_raw); break;
+    }
+}
+
+// EPI: kEpiPlain if no member is a PReLU layer, else kEpiBoth: each member then runs through a
+// copy of the bodies compiled for its kind alone (a body that carries both epilogues needs more
+// registers than either, and the six-tile bodies would spill).
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b)
 {
@@ -49,15 +67,13 @@ __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b
     while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
     const int lid = logical_block_id(bid - b.start[i], b.start[i + 1] - b.start[i]);
     const PwArgs &a = b.layer[i];
-    switch (b.body[i]) {
-    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true, ring_depth<4>(), EPI>(a, lid, lds_raw); break;
-    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true, ring_depth<1>(), EPI>(a, lid, lds_raw); break;
-    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false, ring_depth<2>(), EPI>(a, lid, lds_raw); break;
-    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), EPI>(a, lid, lds_raw); break;
-    case kBodyR3x8: pw_rows_body<3, true, 8, 4, EPI>(a, lid, lds_raw); break;
-    case kBodyR3: pw_rows_body<3, true, 16, 4, EPI>(a, lid, lds_raw); break;
-    default: pw_rows_body<6, true, 16, 4, EPI>(a, lid, lds_raw); break;
+    if constexpr (EPI != kEpiPlain) {
+        if (a.mult_neg) {
+            pw_big_member<kEpiPrelu>(b.body[i], a, lid, lds_raw);
+            return;
+        }
     }
+    pw_big_member<kEpiPlain>(b.body[i], a, lid, lds_raw);
 }
 
 // any_prelu: a member of the launch is a PReLU layer.

@@ -11,8 +11,8 @@
 // 4 x KSC MFMAs, requantises and stores 16 pixels x 64 channels.  The B operands of the next unit
 // are fetched tile by tile during the last sub-chunk, right after a tile's last MFMA.
 //
-// Limits (checked on the host): K % 16 == 0, K <= 64*KSC, Nc % 64 == 0, no residual, no PReLU,
-// tensors below 2^30 bytes.
+// Limits (checked on the host): K % 16 == 0, K <= 64*KSC, Nc % 64 == 0, no residual, tensors
+// below 2^30 bytes.  PRELU: the layer has PReLU multipliers (a.mult_neg).
 #pragma once
 #include "prom_pw_stream.h"
 
@@ -25,9 +25,10 @@ __host__ __device__ constexpr size_t lds_bytes_expand(int nsc, int ks)
 }
 
 // Decode the weights of sub-chunks [sc0, sc0 + nsc) into frag[nsc][4][KSC][64 lanes] and their
-// requantisation parameters into lpar[nsc][4][4 g][4 r] = (C lo, C hi, mult, shift); all global
+// requantisation parameters into lpar[nsc][4][4 g][4 r] = (C lo, C hi, mult, shift), or (bias, mult,
+// mult_neg, shift) for a PReLU layer; all global
 // loads of a thread are issued before the first decode.  Ends with the workgroup barrier.
-template <int KSC>
+template <int KSC, bool PRELU>
 __device__ __forceinline__ void stage_part(const PwArgs &a, int sc0, int nsc, v4i *frag, v4i *lpar)
 {
     const int tid = threadIdx.x;
@@ -57,12 +58,12 @@ __device__ __forceinline__ void stage_part(const PwArgs &a, int sc0, int nsc, v4
     }
     for (int p = tid; p < nsc * 64; p += 256) {
         const int c = (sc0 + (p >> 6)) * 64 + chan_of<4>((p >> 4) & 3, (p >> 2) & 3, p & 3);
-        lpar[p] = requant_params(a.bias[c], a.mult[c], 0, a.shift[c], false);
+        lpar[p] = requant_params(a.bias[c], a.mult[c], PRELU ? a.mult_neg[c] : 0, a.shift[c], PRELU);
     }
     __syncthreads();
 }
 
-template <int KSC, int G>
+template <int KSC, int G, bool PRELU = false>
 __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
     const int tid = threadIdx.x;
@@ -107,11 +108,12 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
     for (int gi = 0; gi < G; ++gi) load_tile(gi);
     xoff = min(xoff + xstep, (unsigned)kOobOffset);
 
-    stage_part<KSC>(a, sc0, nsc, frag, lpar);
+    stage_part<KSC, PRELU>(a, sc0, nsc, frag, lpar);
 
     // any shift of the part equal to 0 -> the general form of the requantisation
     bool sh0 = false;
-    for (int c = lane; c < nsc * 64; c += 64) sh0 |= lpar[c][3] == 0;
+    if constexpr (!PRELU)
+        for (int c = lane; c < nsc * 64; c += 64) sh0 |= lpar[c][3] == 0;
     const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
 
     const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
@@ -146,9 +148,14 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
                     int fo = k * 64;
                     if constexpr (KSC > 1) asm volatile("" : "+v"(fo));
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
+                    for (int t = 0; t < 4; ++t) {
+                        // PReLU: the biases are the accumulators' start value, so that the sign of
+                        // an accumulator is the sign that selects the multiplier
+                        v4i c0 = zero4;
+                        if constexpr (MODE == 2) c0 = v4i{par[t][0][0], par[t][1][0], par[t][2][0], par[t][3][0]};
                         acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fk[t * KSC * 64 + fo], B[gi][k],
-                                                                       k == 0 ? zero4 : acc[t], 0, 0, 0);
+                                                                       k == 0 ? c0 : acc[t], 0, 0, 0);
+                    }
                 }
                 if constexpr (LAST) load_tile(gi);  // this tile of the next unit
                 uint32_t out[4];
@@ -156,7 +163,12 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
                 for (int t = 0; t < 4; ++t) {
                     int v[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = requant_mode<MODE>(acc[t][r], par[t][r], lo, hi);
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (MODE == 2)
+                            v[r] = requant_prelu_s(acc[t][r], par[t][r][1], par[t][r][2], par[t][r][3], lo, hi);
+                        else
+                            v[r] = requant_mode<MODE>(acc[t][r], par[t][r], lo, hi);
+                    }
                     out[t] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
                 }
                 // the lane's 16 channels of pixel j: tile t holds channels 16*g + 4*t + r
@@ -177,7 +189,9 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
             ytile = min(ytile + ystep, (unsigned)kOobOffset);
         }
     };
-    if (general_shift)
+    if constexpr (PRELU)
+        run(std::integral_constant<int, 2>{});
+    else if (general_shift)
         run(std::integral_constant<int, 1>{});
     else
         run(std::integral_constant<int, 0>{});

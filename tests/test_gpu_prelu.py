@@ -136,6 +136,41 @@ def test_sequence_mixes_prelu_and_plain_layers(P):
             assert int((l[5] != want).sum()) == 0, f"run {run}: {cin}->{cout} @ {hw} prelu={prelu}"
 
 
+def test_sequence_expansion_layers_with_prelu(P):
+    """The body of the shared launch that keeps a pixel group's activations in registers and walks
+    over the output channels, for PReLU layers: one to three k steps, one to five parts, ragged
+    pixel units, shift 0, most negative and zero negative-side multipliers, next to plain members
+    that take the same body and members that take the streaming bodies."""
+    torch = torch_cuda()
+    cases = [  # n, h, w, cin, cout, shift_range, prelu
+        (3, 7, 9, 32, 192, (3, 8), True), (2, 14, 14, 64, 384, (0, 8), True), (5, 5, 5, 16, 64 * 9, (2, 6), False),
+        (1, 31, 3, 48, 64 * 10, (0, 4), True), (3, 14, 14, 96, 576, (3, 8), True), (2, 9, 11, 128, 64 * 11, (1, 7), True),
+        (4, 7, 7, 160, 960, (3, 8), True), (1, 13, 13, 192, 64 * 7, (0, 3), True), (2, 6, 7, 144, 128, (2, 9), False),
+        (1, 1, 1, 64, 128, (3, 8), True), (2, 7, 7, 320, 1280, (3, 8), True), (3, 7, 9, 64, 96, (3, 8), True),
+        (3, 7, 9, 384, 64, (3, 8), False),
+    ]
+    layers, wants = [], []
+    for i, (n, h, w, cin, cout, sr, prelu) in enumerate(cases):
+        L = make_pw_layer(11900 + i, n, h, w, cin, cout, signed_x=True, act_window=(-128, 127), shift_range=sr)
+        mneg = None
+        if prelu:
+            mneg = prelu_mult_neg(11900 + i, L.mult)
+            mneg[::7] = -(1 << 31)
+            mneg[3::11] = 0
+        rq = _rq(P, L, mneg) if prelu else P.Requant(dev(L.bias), dev(L.mult), dev(L.shift), -128, 127)
+        y = torch.full((n, h, w, cout), -99, dtype=torch.int8, device="cuda")
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, rq, None, y))
+        wants.append(oracle.pw_conv(L.x, L.weight, L.bias, L.mult, L.shift, -128, 127, mult_neg=mneg))
+    seq = P.PwSequence(layers)
+    for run in range(2):
+        for l in layers:
+            l[5].fill_(-99)
+        seq.run()
+        torch.cuda.synchronize()
+        for c, l, want in zip(cases, layers, wants):
+            assert_same(l[5].cpu().numpy(), want, f"run {run}: case {c}")
+
+
 DW_SHAPES = [(2, 4, 5, 12, 1), (2, 4, 5, 12, 2), (1, 7, 7, 960, 1), (3, 14, 14, 384, 1), (2, 28, 28, 192, 2),
              (1, 9, 11, 20, 2), (2, 5, 4, 5, 1), (2, 5, 4, 7, 2), (1, 13, 10, 4, 2), (8, 56, 56, 144, 1)]
 
