@@ -34,9 +34,10 @@
 
 namespace prom {
 
-// Which epilogues a kernel body carries: the plain forms, the PReLU form, or both (shared launches
-// that hold layers of both kinds).  A body is compiled per kind because the registers of a kernel
-// are those of its hungriest path.
+// Which epilogues a kernel body carries: the plain forms, the PReLU form, or both.  A body is
+// compiled per kind because the registers of a kernel are those of its hungriest path; the
+// shared-launch kernels take kEpiBoth to mean "members of either kind" and run each member through
+// a body of its own kind, so no body is instantiated with both at present.
 constexpr int kEpiPlain = 0, kEpiPrelu = 1, kEpiBoth = 2;
 
 struct PwArgs {
