@@ -692,7 +692,10 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         PwArgs a = L.a;  // keeps its own plan (tiles, pixel tiles, chunks); only the grid changes
         const int width = 16 * L.nt * (L.rows ? a.cw : 1);
         const long long work = (long long)a.M * (a.K + width);
-        const int per_step = L.rows ? rows_groups(a.cw) : 4;
+        int per_step = L.rows ? rows_groups(a.cw) : 4;
+        int replanned = 0;
+        const int body = pw_big_replan(L.big_body, a, &replanned);
+        if (replanned) per_step = replanned;
         const long long wg_units = (a.units + per_step - 1) / per_step;
         const long long per_wg = done_work * 10 < total_work * 8   ? kBigBytesPerWg
                                  : done_work * 20 < total_work * 19 ? kBigBytesPerWg / 2
@@ -704,10 +707,10 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         a.wg_per_chunk = (int)wgs;
         const int nblk = (int)((wgs * a.n_chunks + 7) / 8 * 8);
         b.layer[i] = a;
-        b.body[i] = (unsigned char)L.big_body;
+        b.body[i] = (unsigned char)body;
         b.start[i] = start;
         start += nblk;
-        const size_t l = pw_big_body_lds(L.big_body, a);
+        const size_t l = pw_big_body_lds(body, a);
         if (l > lds) lds = l;
     }
     b.start[count] = start;

@@ -4,11 +4,13 @@
 // those of the plans of the large layers at the head of MobileNetV2 (high resolution, few
 // channels); a layer with another plan is launched on its own.
 #include "prom_pw_rows.h"
+#include "prom_pw_expand.h"
 
 namespace prom {
 
 // body ids
-enum { kBodyS1x4 = 0, kBodyS6x1 = 1, kBodyR3x8 = 2, kBodyS2x2 = 3, kBodyS2x4 = 4, kBodyR3 = 5, kBodyR6 = 6 };
+enum { kBodyS1x4 = 0, kBodyS6x1 = 1, kBodyR3x8 = 2, kBodyS2x2 = 3, kBodyS2x4 = 4, kBodyR3 = 5, kBodyR6 = 6, kBodyE3x8 = 7 };
+constexpr int kExpandRowsG = 4;  // pixel tiles per unit of the full-row body
 
 int pw_big_body_id(int nt, int pt, int xmode, bool ks1, bool fullw, int row_waves)
 {
@@ -27,6 +29,26 @@ int pw_big_body_id(int nt, int pt, int xmode, bool ks1, bool fullw, int row_wave
     return -1;
 }
 
+// A layer planned for the row-cooperative body with 8-byte loads (one k step, rows of 48-channel
+// pieces: 24 -> 144) runs faster in the body where one wavefront assembles whole rows by itself
+// (7 -> about 11 GB/s per workgroup inside the shared launch; the same exchange for the six-tile
+// streaming body of 16 -> 96 was measured and is slower).  That body has no residual path.
+// Returns the body to run and re-plans `a` for it; *units_per_wg_round is the number of pixel
+// units a workgroup takes per round, or 0 if the plan is unchanged.
+int pw_big_replan(int body, PwArgs &a, int *units_per_wg_round)
+{
+    *units_per_wg_round = 0;
+    if (body == kBodyR3x8 && !a.residual && a.KS == 1 && a.Nc % 48 == 0 &&
+        lds_bytes_expand_rows(a.Nc / 48, 3, kExpandRowsG, a.Nc) <= 56 * 1024) {
+        a.cw = 0;
+        a.n_chunks = 1;
+        a.units = (a.M + 16 * kExpandRowsG - 1) / (16 * kExpandRowsG);
+        *units_per_wg_round = 4;
+        return kBodyE3x8;
+    }
+    return body;
+}
+
 size_t pw_big_body_lds(int body, const PwArgs &a)
 {
     switch (body) {
@@ -36,6 +58,7 @@ size_t pw_big_body_lds(int body, const PwArgs &a)
     case kBodyS2x4: return lds_bytes_fast(2, a.KS);
     case kBodyR3x8:
     case kBodyR3: return lds_bytes_rows(3, a.cw, a.KS);
+    case kBodyE3x8: return lds_bytes_expand_rows(a.Nc / 48, 3, kExpandRowsG, a.Nc);
     default: return lds_bytes_rows(6, a.cw, a.KS);
     }
 }
@@ -51,6 +74,7 @@ __device__ __forceinline__ void pw_big_member(int body, const PwArgs &a, const i
     case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), E>(a, lid, lds_raw); break;
     case kBodyR3x8: pw_rows_body<3, true, 8, 4, E>(a, lid, lds_raw); break;
     case kBodyR3: pw_rows_body<3, true, 16, 4, E>(a, lid, lds_raw); break;
+    case kBodyE3x8: pw_expand_rows_body<kExpandRowsG, 3, 8, E == kEpiPrelu>(a, lid, lds_raw); break;
     default: pw_rows_body<6, true, 16, 4, E>(a, lid, lds_raw); break;
     }
 }

@@ -197,4 +197,158 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
         run(std::integral_constant<int, 0>{});
 }
 
+// ============================================================================================
+// The same walk over the output channels for wide rows of few input channels at high resolution
+// (one k step, cout = nsc sub-chunks of 16*NTS channels, all of them in every workgroup): the
+// outputs of a whole pixel unit (16*G pixels x Nc bytes, contiguous in NHWC) are assembled in the
+// wavefront's own LDS area and leave as one contiguous run of 16-byte stores.  One wavefront does
+// what the row-cooperative kernel spreads over the wavefronts of a workgroup, without its barriers.
+//   XMODE 16: K % 16 == 0, one 16-byte load per lane; XMODE 8: K % 8 == 0, two 8-byte loads.
+//   (16*G*Nc) % 16 == 0 always; no residual.
+__host__ __device__ constexpr size_t lds_bytes_expand_rows(int nsc, int nts, int g, int nc)
+{
+    return (size_t)nsc * nts * (1024 + 256) + (size_t)4 * 16 * g * nc;
+}
+
+template <int G, int NTS, int XMODE, bool PRELU>
+__device__ __forceinline__ void pw_expand_rows_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    static_assert(NTS == 3 || NTS == 4, "sub-chunks of 48 or 64 channels");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15;
+    const int g = lane >> 4;
+    if (lid >= a.wg_per_chunk) return;
+    const int K = a.K, Nc = a.Nc;
+    const int nsc = Nc / (16 * NTS);
+
+    v4i *frag = reinterpret_cast<v4i *>(lds_raw);  // [nsc][NTS][64 lanes]
+    v4i *lpar = frag + nsc * NTS * 64;             // [nsc][NTS][4 g][4 r]
+    unsigned char *stage = reinterpret_cast<unsigned char *>(lpar + nsc * NTS * 16) + wave * (16 * G * Nc);
+
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.M * K, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.M * Nc, kBufFlags);
+
+    const int Wv = a.wg_per_chunk * 4;
+    const int w0 = lid * 4 + wave;
+    unsigned xoff = min((unsigned)kOobOffset, (unsigned)(w0 * (16 * G) + j) * (unsigned)K + 16u * g);
+    const unsigned xstep = (unsigned)Wv * (16 * G) * (unsigned)K;
+    v4i B[G];
+    auto load_tile = [&](int gi) {
+        const unsigned xo = min(xoff + (unsigned)((16 * gi) * K), (unsigned)kOobOffset);
+        if constexpr (XMODE == 16) {
+            B[gi] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo, 0, 0);
+        } else {
+            const v2i lo2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)xo, 0, 0);
+            const v2i hi2 = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(xo + 8u), 0, 0);
+            B[gi] = v4i{lo2[0], lo2[1], hi2[0], hi2[1]};
+        }
+    };
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) load_tile(gi);
+    xoff = min(xoff + xstep, (unsigned)kOobOffset);
+
+    // ---- weights and parameters of all sub-chunks ------------------------------------------------
+    {
+        const int nfrag = nsc * NTS * 64;
+        for (int idx = tid; idx < nfrag; idx += 256) {
+            const int tk = idx >> 6;
+            const int t = tk % NTS, sc = tk / NTS;
+            const int i = idx & 15;
+            const int c = sc * (16 * NTS) + chan_of<NTS>(t, i >> 2, i & 3);
+            const int kw = (idx & 63) >> 4;
+            frag[idx] = decode_word(kw < a.KW ? a.wq[(long long)c * a.KW + kw] : 0u);
+        }
+        for (int p = tid; p < nsc * NTS * 16; p += 256) {
+            const int q = p % (NTS * 16);
+            const int c = (p / (NTS * 16)) * (16 * NTS) + chan_of<NTS>(q >> 4, (q >> 2) & 3, q & 3);
+            lpar[p] = requant_params(a.bias[c], a.mult[c], PRELU ? a.mult_neg[c] : 0, a.shift[c], PRELU);
+        }
+        __syncthreads();
+    }
+    bool sh0 = false;
+    if constexpr (!PRELU)
+        for (int c = lane; c < nsc * NTS * 16; c += 64) sh0 |= lpar[c][3] == 0;
+    const bool general_shift = __builtin_amdgcn_ballot_w64(sh0) != 0;
+
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int unit_bytes = 16 * G * Nc;
+    unsigned yunit = min((unsigned)kOobOffset, (unsigned)w0 * (unsigned)unit_bytes);
+    const unsigned ystep = (unsigned)Wv * (unsigned)unit_bytes;
+    const int my_units = w0 < a.units ? (a.units - w0 + Wv - 1) / Wv : 0;
+    const v4i zero4 = {0, 0, 0, 0};
+
+    auto run = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        auto sub_chunk = [&](const int sc, auto last_tag) {
+            constexpr bool LAST = decltype(last_tag)::value;
+            v4i par[NTS][4];
+            const v4i *lpg = lpar + sc * (NTS * 16) + g * 4;
+#pragma unroll
+            for (int t = 0; t < NTS; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    par[t][r] = lpg[t * 16 + r];
+                    if constexpr (MODE == 0) par[t][r][3] -= 1;
+                }
+            v4i wf[NTS];
+#pragma unroll
+            for (int t = 0; t < NTS; ++t) wf[t] = frag[(sc * NTS + t) * 64 + lane];
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                v4i acc[NTS];
+#pragma unroll
+                for (int t = 0; t < NTS; ++t) {
+                    v4i c0 = zero4;
+                    if constexpr (MODE == 2) c0 = v4i{par[t][0][0], par[t][1][0], par[t][2][0], par[t][3][0]};
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[t], B[gi], c0, 0, 0, 0);
+                }
+                if constexpr (LAST) load_tile(gi);  // this tile of the next unit
+                uint32_t out[NTS];
+#pragma unroll
+                for (int t = 0; t < NTS; ++t) {
+                    int v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (MODE == 2)
+                            v[r] = requant_prelu_s(acc[t][r], par[t][r][1], par[t][r][2], par[t][r][3], lo, hi);
+                        else
+                            v[r] = requant_mode<MODE>(acc[t][r], par[t][r], lo, hi);
+                    }
+                    out[t] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                }
+                // pixel row (16*gi + j) of the unit, channels of this sub-chunk: the lane's tiles
+                // are stored in groups of 4, 2, 1 (chan_of), each group contiguous
+                unsigned char *sp = stage + (16 * gi + j) * Nc + sc * (16 * NTS);
+                if constexpr (NTS == 4) {
+                    *reinterpret_cast<v4i *>(sp + 16 * g) = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+                } else {
+                    *reinterpret_cast<v2i *>(sp + 8 * g) = v2i{(int)out[0], (int)out[1]};
+                    *reinterpret_cast<uint32_t *>(sp + 32 + 4 * g) = out[2];
+                }
+            }
+        };
+        for (int u = 0; u < my_units; ++u) {
+#pragma nounroll
+            for (int sc = 0; sc + 1 < nsc; ++sc) sub_chunk(sc, std::false_type{});
+            sub_chunk(nsc - 1, std::true_type{});
+            // the unit's 16*G*Nc bytes, in 16-byte pieces in memory order
+            for (int p = lane; p < unit_bytes / 16; p += 64) {
+                const v4i v = *reinterpret_cast<const v4i *>(stage + 16 * p);
+                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(yunit + 16u * p, (unsigned)kOobOffset), 0, 0);
+            }
+            xoff = min(xoff + xstep, (unsigned)kOobOffset);
+            yunit = min(yunit + ystep, (unsigned)kOobOffset);
+        }
+    };
+    if constexpr (PRELU)
+        run(std::integral_constant<int, 2>{});
+    else if (general_shift)
+        run(std::integral_constant<int, 1>{});
+    else
+        run(std::integral_constant<int, 0>{});
+}
+
 }  // namespace prom

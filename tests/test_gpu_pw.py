@@ -355,3 +355,29 @@ def test_sequence_expansion_layers_keep_activations_in_registers(P):
         torch.cuda.synchronize()
         for c, l, want in zip(cases, layers, wants):
             assert_same(l[5].cpu().numpy(), want, f"run {run}: case {c}")
+
+
+def test_sequence_large_wide_row_layers_ragged_pixel_count(P):
+    """24 -> 144 at high resolution inside the launch of large layers runs in the body where one
+    wavefront assembles whole output rows of a 64-pixel unit; here with pixel counts that leave a
+    ragged last unit and a ragged last 16-pixel tile, a second such layer with 48 output channels
+    per pixel more, and a 16 -> 96 neighbour; outputs pre-filled, every byte compared."""
+    torch = torch_cuda()
+    shapes = [(65, 56, 55, 24, 144), (33, 111, 56, 24, 192), (64, 112, 112, 16, 96), (37, 113, 57, 24, 144)]
+    classes = [P.prom_pw_batch_class(n, h, w, cin, cout) for n, h, w, cin, cout in shapes]
+    assert classes == [2, 2, 2, 2], classes
+    layers, wants = [], []
+    for i, (n, h, w, cin, cout) in enumerate(shapes):
+        assert (n * h * w) % 64 != 0 or cin == 16
+        L = make_pw_layer(9700 + i, n, h, w, cin, cout, signed_x=True, act_window=(-128, 127), shift_range=(0, 6) if i == 3 else (2, 7))
+        y = torch.full((n, h, w, cout), -99, dtype=torch.int8, device="cuda")
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, requant_dev(P, L), None, y))
+        wants.append(dev(oracle_pw(oracle, L)))
+    seq = P.PwSequence(layers)
+    for run in range(2):
+        for l in layers:
+            l[5].fill_(-99)
+        seq.run()
+        torch.cuda.synchronize()
+        for sh, l, want in zip(shapes, layers, wants):
+            assert int((l[5] != want).sum()) == 0, f"run {run}: {sh}"
