@@ -26,8 +26,8 @@ __host__ __device__ constexpr size_t lds_bytes_expand(int nsc, int ks)
 
 // Decode the weights of sub-chunks [sc0, sc0 + nsc) into frag[nsc][4][KSC][64 lanes] and their
 // requantisation parameters into lpar[nsc][4][4 g][4 r] = (C lo, C hi, mult, shift), or (bias, mult,
-// mult_neg, shift) for a PReLU layer; all global
-// loads of a thread are issued before the first decode.  Ends with the workgroup barrier.
+// mult_neg, shift) for a PReLU layer; all global loads of a thread are issued before the first
+// decode.  Ends with the workgroup barrier.
 template <int KSC, bool PRELU>
 __device__ __forceinline__ void stage_part(const PwArgs &a, int sc0, int nsc, v4i *frag, v4i *lpar)
 {
