@@ -121,6 +121,7 @@ __host__ __device__ inline int batch_nt(const PwArgs &a)
 constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2;
 __host__ __device__ constexpr int expand_g(int ks) { return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : kExpandG3; }
 constexpr int kExpandLds = 52 * 1024;  // three workgroups per CU
+constexpr int kExpandRowsG1 = 2;       // pixel tiles per unit of the full-row form (one k step)
 
 // One member's work with the epilogue kind E (plain or PReLU) fixed at compile time.
 template <int E>
@@ -171,17 +172,21 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     const PwArgs &a = b.layer[i];
     const int lid = logical_block_id(local, nblk);
     // a.cw != 0: the host planned the layer for the body that keeps the activations of a pixel
-    // group in registers while it walks over the output channels
+    // group in registers while it walks over the output channels (a.cw < 0: its full-row form)
     if constexpr (EPI != kEpiPlain) {
         if (a.mult_neg) {
-            if (a.cw)
+            if (a.cw < 0)
+                pw_expand_rows_body<kExpandRowsG1, 4, 16, true>(a, lid, lds_raw);
+            else if (a.cw)
                 pw_expand_member<true>(a, lid, lds_raw);
             else
                 pw_batch_member<kEpiPrelu>(a, lid, lds_raw);
             return;
         }
     }
-    if (a.cw)
+    if (a.cw < 0)
+        pw_expand_rows_body<kExpandRowsG1, 4, 16, false>(a, lid, lds_raw);
+    else if (a.cw)
         pw_expand_member<false>(a, lid, lds_raw);
     else
         pw_batch_member<kEpiPlain>(a, lid, lds_raw);
@@ -617,7 +622,16 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         const int nsc = expand_plan(a, &parts);
         long long work;  // bytes one chunk (or part) moves
         size_t l;
-        if (nsc) {
+        const bool full_rows = nsc && parts == 1 && a.KS == 1 &&
+                               lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc) <= (size_t)kExpandLds;
+        if (full_rows) {
+            // all output channels in one part and a unit's rows small enough for LDS: whole rows
+            a.cw = -1;
+            a.n_chunks = 1;
+            a.units = (a.M + 16 * kExpandRowsG1 - 1) / (16 * kExpandRowsG1);
+            work = (long long)a.M * (a.K + a.Nc);
+            l = lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc);
+        } else if (nsc) {
             a.cw = nsc;
             a.n_chunks = parts;
             a.units = (a.M + 16 * expand_g(a.KS) - 1) / (16 * expand_g(a.KS));
@@ -638,7 +652,7 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         if (nsc) {
             // units are large here (16*G pixels x all channels of the part): give every wavefront
             // the same whole number of them
-            const long long unit_bytes = 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
+            const long long unit_bytes = full_rows ? 16LL * kExpandRowsG1 * (a.K + a.Nc) : 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
             long long upw = (per_wg + 2 * unit_bytes) / (4 * unit_bytes);
             if (upw < 1) upw = 1;
             wgs = (a.units + 4 * upw - 1) / (4 * upw);
