@@ -684,6 +684,7 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
 
 // A large layer can join the launch of large layers if pw_bigbatch_kernel carries the body of its plan.
 constexpr long long kBigBytesPerWg = 768LL << 10;  // measured best of 128 KB .. 2 MB on the MobileNetV2 head
+constexpr double kBigWgMicros = 60.0;              // workgroup time aimed at where the body's speed is known
 static bool big_batchable(const PwLaunch &L)
 {
     return L.fast && L.mode == 0 && L.big_body >= 0 && !batchable(L) && L.lds <= (size_t)kLdsBudget;
@@ -716,6 +717,16 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
                                                                     : kBigBytesPerWg / 4;
         done_work += work * a.n_chunks;
         long long wgs = (work + per_wg - 1) / per_wg;
+        // Bodies differ in speed (3 to 18 ns per pixel and workgroup), and workgroups of equal
+        // bytes then end the launch with the slow ones still running: where the body's speed is
+        // known, size by time instead -- 60 us for the first 70 % of the work, 30 us after it
+        // (swept 30-100 us and 60-100 %: 116-118 us against 121-122 for the launch of the six
+        // MobileNetV2 head layers).
+        const double ns = pw_big_body_ns_per_pixel(body);
+        if (ns > 0) {
+            const bool early = (done_work - work * a.n_chunks) * 10 < total_work * 7;
+            wgs = (long long)((double)a.M * ns / ((early ? kBigWgMicros : kBigWgMicros / 2) * 1000.0) + 0.999);
+        }
         if (wgs < 1) wgs = 1;
         if (wgs > wg_units) wgs = wg_units;
         a.wg_per_chunk = (int)wgs;

@@ -49,6 +49,20 @@ int pw_big_replan(int body, PwArgs &a, int *units_per_wg_round)
     return body;
 }
 
+// Time a workgroup of the body spends per pixel while the chip is full (ns; from the per-workgroup
+// timeline of the MobileNetV2 head at batch 128: 32->16, 16->96, 96/144->24, 24->144), or 0 for a
+// body that was not measured.  The launch sizes its workgroups by it so that they take about equally long.
+double pw_big_body_ns_per_pixel(int body)
+{
+    switch (body) {
+    case kBodyS1x4: return 3.1;
+    case kBodyS6x1: return 9.0;
+    case kBodyS2x2: return 12.0;
+    case kBodyE3x8: return 18.0;
+    default: return 0.0;
+    }
+}
+
 size_t pw_big_body_lds(int body, const PwArgs &a)
 {
     switch (body) {

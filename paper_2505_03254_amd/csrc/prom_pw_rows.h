@@ -353,6 +353,7 @@ using PwBatchFn = void (*)(PwBatchArgs);
 int pw_big_body_id(int nt, int pt, int xmode, bool ks1, bool fullw, int row_waves);
 PwBatchFn pw_bigbatch_fn(bool any_prelu);
 size_t pw_big_body_lds(int body, const PwArgs &a);
+double pw_big_body_ns_per_pixel(int body);
 int pw_big_replan(int body, PwArgs &a, int *units_per_wg_round);
 
 // Defined in prom_pw_rows.hip: the instantiation for NT in 1..6 and load width 16 or 8, or nullptr.
