@@ -118,8 +118,11 @@ __host__ __device__ inline int batch_nt(const PwArgs &a)
     return batch_nt(a.KS, a.mult_neg != nullptr && a.Nc % (16 * kBatchNT) != 0);
 }
 // Pixel tiles per unit of pw_expand_body by number of k steps (registers: 4 per tile and k step).
-constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2;
-__host__ __device__ constexpr int expand_g(int ks) { return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : kExpandG3; }
+constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2, kExpandG5 = 1;
+__host__ __device__ constexpr int expand_g(int ks)
+{
+    return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : ks == 3 ? kExpandG3 : kExpandG5;
+}
 constexpr int kExpandLds = 52 * 1024;  // three workgroups per CU
 constexpr int kExpandRowsG1 = 2;       // pixel tiles per unit of the full-row form (one k step)
 
@@ -153,8 +156,10 @@ __device__ __forceinline__ void pw_expand_member(const PwArgs &a, const int lid,
         pw_expand_body<1, kExpandG1, PRELU>(a, lid, lds_raw);
     else if (a.KS == 2)
         pw_expand_body<2, kExpandG2, PRELU>(a, lid, lds_raw);
-    else
+    else if (a.KS == 3)
         pw_expand_body<3, kExpandG3, PRELU>(a, lid, lds_raw);
+    else
+        pw_expand_body<5, kExpandG5, PRELU>(a, lid, lds_raw);
 }
 
 // EPI: kEpiPlain if no member is a PReLU layer, else kEpiBoth.  A launch of both kinds runs each
@@ -573,11 +578,11 @@ static bool conflicts(const PwArgs &a, const PwArgs &b)
 }
 
 // Sub-chunks (64 output channels) per part if the layer is one for pw_expand_body, else 0:
-// at most 3 k steps, whole sub-chunks, no residual, and fewer passes over
-// the activations than the streaming body's chunks would make.
+// 1, 2, 3 or 5 k steps (the bodies that are compiled), whole sub-chunks, no residual, and fewer
+// passes over the activations than the streaming body's chunks would make.
 static int expand_plan(const PwArgs &m, int *nparts)
 {
-    if (m.residual || m.Nc % 64 != 0 || m.KS > 3 || m.K % 16 != 0) return 0;
+    if (m.residual || m.Nc % 64 != 0 || (m.KS > 3 && m.KS != 5) || m.K % 16 != 0) return 0;
     const int sc_total = m.Nc / 64;
     int nmax = 1;
     while (nmax < sc_total && lds_bytes_expand(nmax + 1, m.KS) <= (size_t)kExpandLds) ++nmax;
