@@ -171,6 +171,37 @@ def test_sequence_expansion_layers_with_prelu(P):
             assert_same(l[5].cpu().numpy(), want, f"run {run}: case {c}")
 
 
+def test_sequence_large_wide_row_layers_with_prelu(P):
+    """24 -> 144 at high resolution with PReLU inside the launch of large layers (the body where one
+    wavefront assembles whole rows): shift ranges from 0 and from 2, ragged pixel counts, most
+    negative, largest and zero negative-side multipliers, a plain neighbour."""
+    torch = torch_cuda()
+    cases = [(65, 56, 55, 24, 144, (2, 9), True), (37, 113, 57, 24, 144, (0, 5), True),
+             (64, 56, 56, 24, 144, (2, 3), True), (64, 112, 112, 16, 96, (2, 7), False)]
+    assert [P.prom_pw_batch_class(n, h, w, ci, co) for n, h, w, ci, co, _, _ in cases] == [2, 2, 2, 2]
+    layers, wants = [], []
+    for i, (n, h, w, cin, cout, sr, prelu) in enumerate(cases):
+        L = make_pw_layer(12300 + i, n, h, w, cin, cout, signed_x=True, act_window=(-128, 127), shift_range=sr)
+        mneg = None
+        if prelu:
+            mneg = prelu_mult_neg(12300 + i, L.mult)
+            mneg[::7] = -(1 << 31)
+            mneg[3::11] = 0
+            mneg[5::13] = (1 << 31) - 1
+        rq = _rq(P, L, mneg) if prelu else P.Requant(dev(L.bias), dev(L.mult), dev(L.shift), -128, 127)
+        y = torch.full((n, h, w, cout), -99, dtype=torch.int8, device="cuda")
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, rq, None, y))
+        wants.append(dev(oracle.pw_conv(L.x, L.weight, L.bias, L.mult, L.shift, -128, 127, mult_neg=mneg)))
+    seq = P.PwSequence(layers)
+    for run in range(2):
+        for l in layers:
+            l[5].fill_(-99)
+        seq.run()
+        torch.cuda.synchronize()
+        for c, l, want in zip(cases, layers, wants):
+            assert int((l[5] != want).sum()) == 0, f"run {run}: case {c}"
+
+
 DW_SHAPES = [(2, 4, 5, 12, 1), (2, 4, 5, 12, 2), (1, 7, 7, 960, 1), (3, 14, 14, 384, 1), (2, 28, 28, 192, 2),
              (1, 9, 11, 20, 2), (2, 5, 4, 5, 1), (2, 5, 4, 7, 2), (1, 13, 10, 4, 2), (8, 56, 56, 144, 1)]
 
