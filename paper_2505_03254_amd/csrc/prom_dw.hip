@@ -5,9 +5,10 @@
 // vector ALU, and the work per output byte decides its speed.
 //
 // dw_kernel_v4: a thread owns 4 consecutive channels (one dword of the NHWC row) of one output
-// column and 4 consecutive output rows; lanes run over channels, then columns, so every load and
-// store instruction of a wavefront covers one contiguous run.  The input rows feeding the 4
-// outputs (6 at stride 1, 9 at stride 2) are loaded for each of the 3 kernel columns as one
+// column and ROWS consecutive output rows (4, or 8 at stride 1 on maps at least 8 rows high);
+// lanes run over channels, then columns, so every load and store instruction of a wavefront
+// covers one contiguous run.  The input rows feeding the outputs (ROWS + 2 at stride 1,
+// 2*ROWS + 1 at stride 2) are loaded for each of the 3 kernel columns as one
 // dword per pixel and transposed in registers (v_perm_b32, 4x4 bytes) so that a dword holds 4
 // vertically neighbouring pixels of ONE channel; the 3 vertical taps of an output are then one
 // v_dot4_i32_i8 against the dword (w[0][j], w[1][j], w[2][j], 0) of that channel and kernel
@@ -50,16 +51,16 @@ __device__ __forceinline__ void transpose4x4(const uint32_t (&in)[4], uint32_t (
 
 // C % 4 == 0, 4-byte aligned x / y / w, one image below 2^31 bytes.
 // Grid: x over Wo * C/4 (channels fastest, then output columns: the lanes of a wavefront read and
-// write contiguous runs), y = group of 4 output rows, z = image.  Row and image indices are
+// write contiguous runs), y = group of ROWS output rows, z = image.  Row and image indices are
 // uniform per workgroup, so every address is a per-lane column offset plus a scalar row offset;
 // the image is addressed through a buffer resource of its own, which makes rows above and below
 // it read as zero (and such output rows vanish) without a test, and a column outside the image
 // gets an offset beyond the resource.
-template <int S>
+template <int S, int ROWS = 4>
 __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
 {
-    constexpr int NPIX = S == 1 ? 6 : 9;  // input rows feeding 4 output rows
-    constexpr int NB = (NPIX + 3) / 4;    // transposed dwords per channel
+    constexpr int NPIX = S * (ROWS - 1) + 3;  // input rows feeding ROWS output rows
+    constexpr int NB = (NPIX + 3) / 4;        // transposed dwords per channel
     constexpr int kFlags = 0x00020000;
     constexpr int kOob = 0x7ffff000;
     const int C4 = a.C >> 2;
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     if (t >= a.Wo * C4) return;
     const int ox = t / C4;
     const int c = (t - ox * C4) * 4;
-    const int oy0 = blockIdx.y * 4;
+    const int oy0 = blockIdx.y * ROWS;
     const int n = blockIdx.z;
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     for (int q = 0; q < 4; ++q) Cq[q] = (long long)pb[q] * pm[q] + (1LL << (30 + ps[q]));
     const int lo = in_vgpr(a.lo_b - kQBias), hi = in_vgpr(a.hi_b - kQBias);
 
-    int acc[4][4];  // [output row][channel]
+    int acc[ROWS][4];  // [output row][channel]
 #pragma unroll
     for (int jx = 0; jx < 3; ++jx) {
         uint32_t tr[NB][4];
@@ -119,22 +120,14 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            // byte window of channel q for output row o: input rows S*o .. S*o+3 of this column
-            uint32_t w[4];
-            if (S == 1) {
-                w[0] = tr[0][q];
-                w[1] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 1);
-                w[2] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 2);
-                w[3] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 3);
-            } else {
-                w[0] = tr[0][q];
-                w[1] = __builtin_amdgcn_alignbyte(tr[1][q], tr[0][q], 2);
-                w[2] = tr[1][q];
-                w[3] = __builtin_amdgcn_alignbyte(tr[NB - 1][q], tr[1][q], 2);
-            }
 #pragma unroll
-            for (int o = 0; o < 4; ++o)
-                acc[o][q] = __builtin_amdgcn_sdot4((int)w[o], (int)wcol[jx][q], jx == 0 ? 0 : acc[o][q], false);
+            for (int o = 0; o < ROWS; ++o) {
+                // byte window of channel q for output row o: input rows S*o .. S*o+3 of this column
+                const int first = S * o;
+                const int b = first >> 2, sh = first & 3;
+                const uint32_t w = sh == 0 ? tr[b][q] : __builtin_amdgcn_alignbyte(tr[b + 1 < NB ? b + 1 : b][q], tr[b][q], sh);
+                acc[o][q] = __builtin_amdgcn_sdot4((int)w, (int)wcol[jx][q], jx == 0 ? 0 : acc[o][q], false);
+            }
         }
     }
     const int yoff = ox * a.C + c;
@@ -142,7 +135,7 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     if (a.mult_neg) {  // PReLU layer (uniform over the launch)
         const v4i pn = *reinterpret_cast<const v4i *>(a.mult_neg + c);
 #pragma unroll
-        for (int o = 0; o < 4; ++o) {
+        for (int o = 0; o < ROWS; ++o) {
             int out[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q)
@@ -153,7 +146,7 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
         return;
     }
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
+    for (int o = 0; o < ROWS; ++o) {
         int out[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -226,13 +219,18 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
                       ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg | (uintptr_t)rq->shift) & 15) == 0) &&
                       (long long)h * w * c < (1LL << 31) - (1LL << 24) && n <= 65535;
     if (fast) {
-        a.strip_rows = 4;
-        a.strips = (a.Ho + 3) / 4;
+        // stride 1: 8 output rows per thread where the map is high enough (fewer instructions per
+        // output: the transposes and the weights are shared by twice as many rows)
+        const int rows = (stride == 1 && a.Ho >= 8) ? 8 : 4;
+        a.strip_rows = rows;
+        a.strips = (a.Ho + rows - 1) / rows;
         a.total = 0;
         const long long xblocks = ((long long)a.Wo * (c / 4) + 255) / 256;
         if (xblocks > (1LL << 31) - 1 || a.strips > 65535 || n > 65535) return PROM_EUNSUPPORTED;
         const dim3 grid((unsigned)xblocks, (unsigned)a.strips, (unsigned)n);
-        if (stride == 1)
+        if (stride == 1 && rows == 8)
+            hipLaunchKernelGGL((dw_kernel_v4<1, 8>), grid, dim3(256), 0, st, a);
+        else if (stride == 1)
             hipLaunchKernelGGL(dw_kernel_v4<1>, grid, dim3(256), 0, st, a);
         else
             hipLaunchKernelGGL(dw_kernel_v4<2>, grid, dim3(256), 0, st, a);
