@@ -12,8 +12,11 @@
 // dword per pixel and transposed in registers (v_perm_b32, 4x4 bytes) so that a dword holds 4
 // vertically neighbouring pixels of ONE channel; the 3 vertical taps of an output are then one
 // v_dot4_i32_i8 against the dword (w[0][j], w[1][j], w[2][j], 0) of that channel and kernel
-// column, on a byte window cut out with v_alignbyte_b32.  About 12 vector instructions per
-// output byte against about 32 for one multiply-add per tap.  Requantisation as in the pointwise kernels:
+// column.  At stride 2 the 4-row blocks are disjoint and the byte window of an output row is cut
+// out with v_alignbyte_b32; at stride 1 the blocks start at every second input row, so that
+// even output rows read their block at byte 0 and odd ones at byte 1, against a copy of the
+// weight dword shifted by one byte.  About 15 vector instructions per output byte (8 rows per
+// thread) against about 32 for one multiply-add per tap.  Requantisation as in the pointwise kernels:
 // t = acc*mult + C (one v_mad_i64_i32, C = bias*mult + 2^(30+shift)), q = (t >> 31) >> shift.
 #include "prom.h"
 #include "prom_device.h"
@@ -110,23 +113,51 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     const int lo = in_vgpr(a.lo_b - kQBias), hi = in_vgpr(a.hi_b - kQBias);
 
     int acc[ROWS][4];  // [output row][channel]
+    if constexpr (S == 1) {
+        // Stride 1: blocks of 4 input rows that start at every second row (rows 0-3, 2-5, ...), so
+        // that output row o finds its 3 rows in block o/2 at byte 0 (o even) or byte 1 (o odd),
+        // and a second copy of the weight dwords shifted by one byte takes the odd rows: one more
+        // transpose per column instead of a v_alignbyte_b32 for three of four windows.
+        uint32_t wodd[3][4];
 #pragma unroll
-    for (int jx = 0; jx < 3; ++jx) {
-        uint32_t tr[NB][4];
+        for (int jx = 0; jx < 3; ++jx)
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint32_t in[4] = {v[jx][4 * b], v[jx][4 * b + 1], v[jx][4 * b + 2], v[jx][4 * b + 3]};
-            transpose4x4(in, tr[b]);
+            for (int q = 0; q < 4; ++q) wodd[jx][q] = wcol[jx][q] << 8;
+#pragma unroll
+        for (int jx = 0; jx < 3; ++jx) {
+#pragma unroll
+            for (int b = 0; b < ROWS / 2; ++b) {
+                const uint32_t in[4] = {v[jx][2 * b], v[jx][2 * b + 1], v[jx][2 * b + 2], v[jx][2 * b + 3]};
+                uint32_t tr[4];
+                transpose4x4(in, tr);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[2 * b][q] = __builtin_amdgcn_sdot4((int)tr[q], (int)wcol[jx][q], jx == 0 ? 0 : acc[2 * b][q], false);
+                    acc[2 * b + 1][q] =
+                        __builtin_amdgcn_sdot4((int)tr[q], (int)wodd[jx][q], jx == 0 ? 0 : acc[2 * b + 1][q], false);
+                }
+            }
         }
+    } else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int jx = 0; jx < 3; ++jx) {
+            uint32_t tr[NB][4];
 #pragma unroll
-            for (int o = 0; o < ROWS; ++o) {
-                // byte window of channel q for output row o: input rows S*o .. S*o+3 of this column
-                const int first = S * o;
-                const int b = first >> 2, sh = first & 3;
-                const uint32_t w = sh == 0 ? tr[b][q] : __builtin_amdgcn_alignbyte(tr[b + 1 < NB ? b + 1 : b][q], tr[b][q], sh);
-                acc[o][q] = __builtin_amdgcn_sdot4((int)w, (int)wcol[jx][q], jx == 0 ? 0 : acc[o][q], false);
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t in[4] = {v[jx][4 * b], v[jx][4 * b + 1], v[jx][4 * b + 2], v[jx][4 * b + 3]};
+                transpose4x4(in, tr[b]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int o = 0; o < ROWS; ++o) {
+                    // byte window of channel q for output row o: input rows S*o .. S*o+3 of this column
+                    const int first = S * o;
+                    const int b = first >> 2, sh = first & 3;
+                    const uint32_t w =
+                        sh == 0 ? tr[b][q] : __builtin_amdgcn_alignbyte(tr[b + 1 < NB ? b + 1 : b][q], tr[b][q], sh);
+                    acc[o][q] = __builtin_amdgcn_sdot4((int)w, (int)wcol[jx][q], jx == 0 ? 0 : acc[o][q], false);
+                }
             }
         }
     }
