@@ -21,6 +21,7 @@
 #include "prom.h"
 #include "prom_device.h"
 #include "prom_launch.h"
+#include <type_traits>
 
 namespace prom {
 
@@ -176,18 +177,32 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
         }
         return;
     }
+    // q = (t >> 31) >> shift; where every shift of the wavefront's channels is at least 1 the high
+    // dword of t shifted by shift-1 is the same number and one instruction less per output.
+    const bool any_shift0 =
+        __builtin_amdgcn_ballot_w64((ps[0] == 0) | (ps[1] == 0) | (ps[2] == 0) | (ps[3] == 0)) != 0;
+    auto epilogue = [&](auto general_tag) {
+        constexpr bool GENERAL = decltype(general_tag)::value;
+        int sh[4];
 #pragma unroll
-    for (int o = 0; o < ROWS; ++o) {
-        int out[4];
+        for (int q = 0; q < 4; ++q) sh[q] = GENERAL ? ps[q] : ps[q] - 1;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const long long tq = (long long)acc[o][q] * (long long)pm[q] + Cq[q];
-            out[q] = med3_i32((int)(tq >> 31) >> ps[q], lo, hi);
+        for (int o = 0; o < ROWS; ++o) {
+            int out[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const long long tq = (long long)acc[o][q] * (long long)pm[q] + Cq[q];
+                out[q] = med3_i32((GENERAL ? (int)(tq >> 31) : (int)(tq >> 32)) >> sh[q], lo, hi);
+            }
+            // an output row below the image is beyond the resource and is dropped
+            __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(out[0], out[1], out[2], out[3]), ry, yoff,
+                                                  (oy0 + o) * yrow, 0);
         }
-        // an output row below the image is beyond the resource and is dropped
-        __builtin_amdgcn_raw_buffer_store_b32((int)pack4_low_bytes(out[0], out[1], out[2], out[3]), ry, yoff,
-                                              (oy0 + o) * yrow, 0);
-    }
+    };
+    if (any_shift0)
+        epilogue(std::true_type{});
+    else
+        epilogue(std::false_type{});
 }
 
 // Any C and alignment: one thread per output element.

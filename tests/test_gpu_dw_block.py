@@ -49,6 +49,13 @@ def test_dw_full_shift_range_and_unaligned_parameters(P):
     y = P.prom_dw_conv(dev(D.x), dev(D.weight), 1, requant_dev(P, D))
     torch.cuda.synchronize()
     assert_same(y.cpu().numpy(), want, "dw shifts 0..31")
+    for seed, shape, stride, sr in ((5051, (2, 11, 13, 40), 2, (0, 31)), (5052, (3, 17, 9, 64), 1, (0, 2)),
+                                    (5053, (3, 17, 9, 64), 2, (0, 1)), (5054, (2, 5, 9, 24), 1, (0, 3))):
+        D2 = make_dw_layer(seed, *shape, stride, signed_x=True, act_window=(-128, 127), shift_range=sr)
+        y2 = P.prom_dw_conv(dev(D2.x), dev(D2.weight), stride, requant_dev(P, D2))
+        torch.cuda.synchronize()
+        assert_same(y2.cpu().numpy(), oracle.dw_conv(D2.x, D2.weight, stride, D2.bias, D2.mult, D2.shift, -128, 127),
+                    f"dw {shape} stride {stride} shifts {sr}")
     pad = lambda a: dev(np.concatenate([np.zeros(1, a.dtype), a]))[1:]
     rq = P.Requant(pad(D.bias), pad(D.mult), pad(D.shift), -128, 127)
     y = P.prom_dw_conv(dev(D.x), dev(D.weight), 1, rq)
