@@ -727,7 +727,8 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         // known, size by time instead -- 60 us for the first 70 % of the work, 30 us after it
         // (swept 30-100 us and 60-100 %: 116-118 us against 121-122 for the launch of the six
         // MobileNetV2 head layers).
-        const double ns = pw_big_body_ns_per_pixel(body);
+        // (the figures were taken with 1 to 3 k steps; a deeper layer keeps the byte rule)
+        const double ns = a.KS <= 3 ? pw_big_body_ns_per_pixel(body) : 0.0;
         if (ns > 0) {
             const bool early = (done_work - work * a.n_chunks) * 10 < total_work * 7;
             wgs = (long long)((double)a.M * ns / ((early ? kBigWgMicros : kBigWgMicros / 2) * 1000.0) + 0.999);
