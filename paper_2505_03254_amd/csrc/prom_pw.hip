@@ -135,17 +135,17 @@ __device__ __forceinline__ void pw_batch_member(const PwArgs &a, const int lid, 
     // ring are exact (a store in a conditional epilogue makes them conservative)
     if (batch_nt(a) == kBatchNTDeep) {
         if (a.Nc % (16 * kBatchNTDeep) == 0)
-            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, E, kStoreStreaming>(a, lid, lds_raw);
+            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
         else
-            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, E, kStoreStreaming>(a, lid, lds_raw);
+            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
     } else if (a.Nc % (16 * kBatchNT) == 0) {
         if (a.KS == 1)
-            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, E, kStoreStreaming>(a, lid, lds_raw);
+            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, E>(a, lid, lds_raw);
         else
-            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, E, kStoreStreaming>(a, lid, lds_raw);
+            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
     } else {
         if constexpr (E == kEpiPlain)  // (a PReLU layer with a ragged last chunk has the narrow body)
-            pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, E, kStoreStreaming>(a, lid, lds_raw);
+            pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
     }
 }
 

@@ -82,10 +82,10 @@ template <int E>
 __device__ __forceinline__ void pw_big_member(int body, const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
     switch (body) {
-    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true, ring_depth<4>(), E, kStoreStreaming>(a, lid, lds_raw); break;
-    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true, ring_depth<1>(), E, kStoreStreaming>(a, lid, lds_raw); break;
-    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false, ring_depth<2>(), E, kStoreStreaming>(a, lid, lds_raw); break;
-    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), E, kStoreStreaming>(a, lid, lds_raw); break;
+    case kBodyS1x4: pw_stream_body<1, 4, 16, true, true, ring_depth<4>(), E>(a, lid, lds_raw); break;
+    case kBodyS6x1: pw_stream_body<6, 1, 16, true, true, ring_depth<1>(), E>(a, lid, lds_raw); break;
+    case kBodyS2x2: pw_stream_body<2, 2, 16, false, false, ring_depth<2>(), E>(a, lid, lds_raw); break;
+    case kBodyS2x4: pw_stream_body<2, 4, 16, false, false, ring_depth<4>(), E>(a, lid, lds_raw); break;
     case kBodyR3x8: pw_rows_body<3, true, 8, 4, E>(a, lid, lds_raw); break;
     case kBodyR3: pw_rows_body<3, true, 16, 4, E>(a, lid, lds_raw); break;
     case kBodyE3x8: pw_expand_rows_body<kExpandRowsG, 3, 8, E == kEpiPrelu>(a, lid, lds_raw); break;

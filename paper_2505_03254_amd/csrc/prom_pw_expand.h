@@ -12,8 +12,7 @@
 // are fetched tile by tile during the last sub-chunk, right after a tile's last MFMA.
 //
 // Limits (checked on the host): K % 16 == 0, K <= 64*KSC, Nc % 64 == 0, no residual, tensors
-// below 2^30 bytes.  The bodies of this file run in the shared launches only and store their
-// outputs with the streaming hint (kStoreStreaming).  PRELU: the layer has PReLU multipliers (a.mult_neg).
+// below 2^30 bytes.  PRELU: the layer has PReLU multipliers (a.mult_neg).
 #pragma once
 #include "prom_pw_stream.h"
 
@@ -179,7 +178,7 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
                 const v4i v = *reinterpret_cast<const v4i *>(stage + (lane >> 2) * 64 + 16 * ((lane & 3) ^ (lane >> 4)));
                 const unsigned tile_off = ytile + (unsigned)((16 * gi) * Nc + sc * 64);
                 // offset in the vector operand (see the streaming kernel's store)
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(goff + tile_off, (unsigned)kOobOffset), 0, kStoreStreaming);
+                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(goff + tile_off, (unsigned)kOobOffset), 0, 0);
             }
         };
         for (int u = 0; u < my_units; ++u) {
@@ -338,7 +337,7 @@ __device__ __forceinline__ void pw_expand_rows_body(const PwArgs &a, const int l
             // the unit's 16*G*Nc bytes, in 16-byte pieces in memory order
             for (int p = lane; p < unit_bytes / 16; p += 64) {
                 const v4i v = *reinterpret_cast<const v4i *>(stage + 16 * p);
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(yunit + 16u * p, (unsigned)kOobOffset), 0, kStoreStreaming);
+                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(yunit + 16u * p, (unsigned)kOobOffset), 0, 0);
             }
             xoff = min(xoff + xstep, (unsigned)kOobOffset);
             yunit = min(yunit + ystep, (unsigned)kOobOffset);

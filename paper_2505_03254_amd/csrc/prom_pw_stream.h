@@ -164,13 +164,6 @@ __host__ __device__ constexpr size_t lds_bytes_generic(int nt, int ks)
 }
 
 constexpr int kBufFlags = 0x00020000;   // raw buffer of dwords, gfx9 family
-// Non-temporal hint for output stores.  The shared launches of prom_pw_conv_sequence use it: their
-// members' outputs are not read again inside the launch and a sweep of layers moves far more than
-// the caches hold (measured: 4 us of 247 off the MobileNetV2 sweep, 8 of 275 off its PReLU
-// form).  The single-layer kernels do not: in a chain of dependent small layers the next kernel
-// reads the output straight away, and the hint costs there (294 -> 297 us for the 17-block chain
-// at batch 8 replayed from a graph).
-constexpr int kStoreStreaming = 2;
 constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled here
 
 // ============================================================================================
@@ -182,8 +175,7 @@ constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled
 //          conditions, compile-time staging geometry).
 // ============================================================================================
 // `lid` is the workgroup's logical id within this layer's grid (see logical_block_id).
-// YAUX: cache-policy bits of the output stores (0 = default; kStoreStreaming in the shared launches).
-template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>(), int EPI = kEpiPlain, int YAUX = 0>
+template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>(), int EPI = kEpiPlain>
 __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
     // PReLU layer?  Known at compile time unless the body carries both kinds of epilogue.
@@ -419,7 +411,7 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
                         // the 16 bytes of data may be overwritten right after the store is issued,
                         // and on this chip the store then now and then picked up the new contents.
                         // goff is unsigned-saturated, so the sum cannot wrap into the tensor.
-                        __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min((unsigned)goff[i] + (unsigned)tile_off, (unsigned)kOobOffset), 0, YAUX);
+                        __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min((unsigned)goff[i] + (unsigned)tile_off, (unsigned)kOobOffset), 0, 0);
                     }
                 }
                 ytile = min(ytile + ystep, (unsigned)kOobOffset);
