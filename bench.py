@@ -267,8 +267,23 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     copy_gbs = 5 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
     log(f"[bench] copy kernel (512 MB, read+write): {copy_gbs:.0f} GB/s")
+    # One pass of the sweep right after that copy has gone through the caches (1 GB of traffic, four
+    # times the Infinity Cache): what a pass costs when nothing of it is cached, against the
+    # back-to-back figure of the timed region, where a step starts among the dirty lines of the last.
+    cold = []
+    for _ in range(9):
+        P.prom_copy_bytes(src, dst)
+        c0 = torch.cuda.Event(enable_timing=True)
+        c1 = torch.cuda.Event(enable_timing=True)
+        c0.record()
+        one_step()
+        c1.record()
+        torch.cuda.synchronize()
+        cold.append(c0.elapsed_time(c1) * 1e3)
+    cold_pass_us = sorted(cold)[len(cold) // 2]
+    del src, dst
+    log(f"[bench] one pass after a cache-flushing copy: {cold_pass_us:.1f} us (median of {len(cold)})")
 
     result = {
         "metric": "ternary pointwise conv Gop/s and % of roofline, MobileNetV2 layers, batch 128",
@@ -293,6 +308,7 @@ def main():
                   "gadd_per_s": round(value / 2, 1),
                   "sum_layer_event_us": round(sum_us, 1),
                   "copy_kernel_gbs": round(copy_gbs, 0),
+                  "pass_after_cache_flush_us": round(cold_pass_us, 1),
                   "layers_overlapped_on_streams": conc},
         "roofline": {"bound": "hbm", "kernel": dom_name,
                      "layers": groups[dom_name]["layers"],
