@@ -49,7 +49,9 @@ enum {
     PROM_EALIAS = -3,        /* output overlaps an input it must not overlap                  */
     PROM_EWORKSPACE = -4,    /* workspace missing or too small                                */
     PROM_EHIP = -5,          /* the HIP runtime reported an error at launch                   */
-    PROM_EVALUE = -6         /* prom_pack_ternary: a weight outside {-1,0,+1}                 */
+    PROM_EVALUE = -6,        /* prom_pack_ternary: a weight outside {-1,0,+1}                 */
+    PROM_ESCRATCH = -7       /* a no-allocation entry point: the problem needs more scratch
+                                memory than the library's fixed array holds                  */
 };
 
 /* Per-output-channel requantisation and activation window.  The struct itself is read on
@@ -307,6 +309,31 @@ int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int st
 /* 1 if the fused kernel applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
  * cout <= 160, chid <= 192, a band of rows fits in LDS), 0 if not. */
 int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* ---- the block for callers that cannot allocate --------------------------------------------
+ * For callers that cannot call hipMalloc or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  prom_block with PROM_BLOCK_AUTO, but
+ * the two intermediates of the three-launch form live in a fixed array inside the library's
+ * device image instead of a caller workspace: the call allocates nothing (no hipMalloc, no
+ * hipFree, no allocating library routine) and takes inputs and outputs only.
+ *   Limit    prom_block_workspace_size(...) of the shape must not exceed
+ *            prom_block_noalloc_max_workspace() (32 MiB), else PROM_ESCRATCH and nothing is
+ *            enqueued.  All other arguments, limits and errors are prom_block's.
+ *   Memory   the array exists once per GPU that the library runs on, from the first call there
+ *            until the process ends.  Its device address is looked up on the first call on each
+ *            device (with that device current).
+ *   Sharing  every call on a GPU uses that GPU's one array and finds the previous call's bytes
+ *            in it; nothing in it has to start at zero (each intermediate element is written
+ *            before it is read).  Two calls that overlap in time on one GPU (different streams
+ *            without an ordering between them) race on it: order them. */
+int prom_block_noalloc(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
+                       const void *w_expand_packed, const prom_requant_t *rq_expand,
+                       const int8_t *w_dw, const prom_requant_t *rq_dw,
+                       const void *w_project_packed, const prom_requant_t *rq_project,
+                       int add_residual, int8_t *y, void *stream);
+
+/* Bytes of the fixed array behind prom_block_noalloc. */
+size_t prom_block_noalloc_max_workspace(void);
 
 /* ---- measurement utility ------------------------------------------------------------------
  * Plain streaming copy of nbytes (multiple of 16, both pointers 16-byte aligned) from src to

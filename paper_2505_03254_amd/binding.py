@@ -92,6 +92,12 @@ def load_library():
     lib.prom_block_ex.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
                                   vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
                                   vp, ctypes.POINTER(_RequantC), ci, vp, sz, vp, ci, vp]
+    lib.prom_block_noalloc.restype = ci
+    lib.prom_block_noalloc.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci,
+                                       vp, ctypes.POINTER(_RequantC), vp, ctypes.POINTER(_RequantC),
+                                       vp, ctypes.POINTER(_RequantC), ci, vp, vp]
+    lib.prom_block_noalloc_max_workspace.restype = sz
+    lib.prom_block_noalloc_max_workspace.argtypes = []
     lib.prom_block_can_fuse.restype = ci
     lib.prom_block_can_fuse.argtypes = [ci] * 7
     lib.prom_block_workspace_size.restype = sz
@@ -353,6 +359,29 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
 
 
 BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED = 0, 1, 2
+
+
+def prom_block_noalloc(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand: Requant,
+                       w_dw, rq_dw: Requant, w_project_packed, rq_project: Requant, add_residual: bool,
+                       y, stream=None):
+    """prom_block without a workspace: the intermediates live in the library's fixed device array.
+    The caller passes the output tensor (nothing is allocated here either)."""
+    _dev_i8(x, "x")
+    _dev_i8(w_dw, "w_dw")
+    _dev_i8(y, "y")
+    n, h, w, cin = x.shape
+    e, d, p = rq_expand._c(), rq_dw._c(), rq_project._c()
+    rc = load_library().prom_block_noalloc(
+        x.data_ptr(), n, h, w, cin, int(chid), int(cout), int(stride),
+        w_expand_packed.data_ptr(), ctypes.byref(e), w_dw.data_ptr(), ctypes.byref(d),
+        w_project_packed.data_ptr(), ctypes.byref(p), int(bool(add_residual)), y.data_ptr(),
+        _stream_ptr(stream))
+    _check(rc, "prom_block_noalloc")
+    return y
+
+
+def prom_block_noalloc_max_workspace() -> int:
+    return int(load_library().prom_block_noalloc_max_workspace())
 
 
 def prom_block_can_fuse(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:

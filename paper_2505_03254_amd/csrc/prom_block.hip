@@ -553,3 +553,66 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
     return prom_pw_conv(t2, n, ho, wo, chid, w_project_packed, cout, rq_project,
                         add_residual ? x : nullptr, y, stream);
 }
+
+// ---- the block for callers that cannot allocate -------------------------------------------------
+// The three-launch form needs the two intermediates somewhere.  prom_block takes them from the
+// caller's workspace; prom_block_noalloc keeps them in a fixed array in the library's own device
+// image, so that a caller under graph capture or in a loop that must not call hipMalloc needs no
+// workspace of its own.  The array exists once per GPU the library runs on, from the moment the
+// code object is loaded there until the process ends.
+namespace prom {
+
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device (the name `scratch` in host code is only a
+// handle for the runtime, not an address a kernel could use).  Looked up once per device.
+static int noalloc_scratch(void **out)
+{
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        last_hip_error() = e != hipSuccess ? e : hipErrorInvalidDevice;
+        (void)hipGetLastError();
+        return PROM_EHIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            last_hip_error() = e != hipSuccess ? e : hipErrorInvalidSymbol;
+            (void)hipGetLastError();
+            return PROM_EHIP;
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return PROM_OK;
+}
+
+}  // namespace prom
+
+extern "C" size_t prom_block_noalloc_max_workspace(void) { return prom::kNoAllocScratchBytes; }
+
+extern "C" int prom_block_noalloc(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
+                                  const void *w_expand_packed, const prom_requant_t *rq_expand,
+                                  const int8_t *w_dw, const prom_requant_t *rq_dw,
+                                  const void *w_project_packed, const prom_requant_t *rq_project,
+                                  int add_residual, int8_t *y, void *stream)
+{
+    if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
+        return PROM_EINVAL;
+    const size_t need = prom_block_workspace_size(n, h, w, cin, chid, cout, stride);
+    if (need > prom::kNoAllocScratchBytes) return PROM_ESCRATCH;
+    void *ws = nullptr;
+    const int rc = prom::noalloc_scratch(&ws);
+    if (rc != PROM_OK) return rc;
+    return prom_block_ex(x, n, h, w, cin, chid, cout, stride, w_expand_packed, rq_expand, w_dw, rq_dw,
+                         w_project_packed, rq_project, add_residual, ws, prom::kNoAllocScratchBytes, y,
+                         PROM_BLOCK_AUTO, stream);
+}

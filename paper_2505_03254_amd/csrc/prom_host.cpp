@@ -122,6 +122,7 @@ extern "C" const char *prom_strerror(int code)
     case PROM_EUNSUPPORTED: return "shape beyond a compiled limit";
     case PROM_EALIAS: return "output buffer overlaps an input";
     case PROM_EWORKSPACE: return "workspace or output buffer missing or too small";
+    case PROM_ESCRATCH: return "the problem needs more scratch memory than the fixed array of this no-allocation entry point holds";
     case PROM_EHIP: return "HIP runtime error at kernel launch";
     case PROM_EVALUE: return "weight value outside {-1,0,+1}";
     default: return "unknown error code";
