@@ -35,10 +35,15 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def _extra_flags():
+    """Extra hipcc flags for a developer build, e.g. PROM_BUILD_FLAGS=-DPROM_TIMELINE."""
+    return os.environ.get("PROM_BUILD_FLAGS", "").split()
+
+
 def _compile(job) -> str:
     src, defines, tag = job
     obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + tag + ".o")
-    cmd = [_hipcc()] + HIPCC_FLAGS + defines + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc()] + HIPCC_FLAGS + _extra_flags() + defines + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     p = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in p.stderr.splitlines() if "packed-fp32-ops" not in l)
     if p.returncode != 0:

@@ -3,6 +3,7 @@
 // prom_pw_stream.h and is instantiated per NT in prom_pw_inst.hip.
 #include "prom_pw_rows.h"
 #include "prom_pw_expand.h"
+#include "prom_pw_wreg.h"
 #include "prom_launch.h"
 
 #include <mutex>
@@ -162,9 +163,49 @@ __device__ __forceinline__ void pw_expand_member(const PwArgs &a, const int lid,
         pw_expand_body<5, kExpandG5, PRELU>(a, lid, lds_raw);
 }
 
+// Bodies of pw_wreg_body (weights in registers) a batch member can be planned for: body id ->
+// (k steps, tiles per wavefront, pixel tiles fetched ahead).
+enum { kWreg6x1 = 1, kWreg6x2 = 2, kWreg9x2 = 3, kWreg9x3 = 4, kWreg15x3 = 5 };
+
+template <int E>
+__device__ __forceinline__ void pw_wreg_member(int body, const PwArgs &a, const int lid, unsigned char *lds_raw)
+{
+    switch (body) {
+    case kWreg6x1: pw_wreg_body<6, 1, 3, true, E>(a, lid, lds_raw); break;
+    case kWreg6x2: pw_wreg_body<6, 2, 3, true, E>(a, lid, lds_raw); break;
+    case kWreg9x2: pw_wreg_body<9, 2, 2, false, E>(a, lid, lds_raw); break;
+    case kWreg9x3: pw_wreg_body<9, 3, 2, false, E>(a, lid, lds_raw); break;
+    default: pw_wreg_body<15, 3, 1, false, E>(a, lid, lds_raw); break;
+    }
+}
+
 // EPI: kEpiPlain if no member is a PReLU layer, else kEpiBoth.  A launch of both kinds runs each
 // member through a copy of the bodies compiled for its kind alone (a body that carries both
 // epilogues needs more registers than either).
+#ifdef PROM_TIMELINE
+// Developer build (-DPROM_TIMELINE): every workgroup of the shared launch of small layers records
+// the constant-rate clock (100 MHz) at its start and end and the member it ran, for a
+// per-workgroup timeline of the launch; read back with prom_debug_timeline.
+constexpr int kTimelineMax = 32768;
+__device__ unsigned long long g_timeline[2 * kTimelineMax];
+__device__ int g_timeline_member[kTimelineMax];
+struct TimelineScope {
+    int bid, member;
+    __device__ TimelineScope(int bid_, int member_) : bid(bid_), member(member_)
+    {
+        if (threadIdx.x == 0 && bid < kTimelineMax) {
+            g_timeline[2 * bid] = wall_clock64();
+            g_timeline_member[bid] = member;
+        }
+    }
+    __device__ ~TimelineScope()
+    {
+        __syncthreads();
+        if (threadIdx.x == 0 && bid < kTimelineMax) g_timeline[2 * bid + 1] = wall_clock64();
+    }
+};
+#endif
+
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
 {
@@ -174,8 +215,16 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
     const int local = bid - b.start[i];
     const int nblk = b.start[i + 1] - b.start[i];
-    const PwArgs &a = b.layer[i];
+    const PwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
     const int lid = logical_block_id(local, nblk);
+#ifdef PROM_TIMELINE
+    TimelineScope timeline_scope(bid, i);
+#endif
+    // a.cw <= -10: the host planned the layer for the body that keeps the weights in registers
+    if (a.cw <= -10) {  // (never a PReLU layer: the host plans those for the other bodies)
+        pw_wreg_member<kEpiPlain>(-10 - a.cw, a, lid, lds_raw);
+        return;
+    }
     // a.cw != 0: the host planned the layer for the body that keeps the activations of a pixel
     // group in registers while it walks over the output channels (a.cw < 0: its full-row form)
     if constexpr (EPI != kEpiPlain) {
@@ -594,6 +643,26 @@ static int expand_plan(const PwArgs &m, int *nparts)
     return (sc_total + parts - 1) / parts;
 }
 
+// Plan of a batch member for pw_wreg_body (weights in registers, activations through LDS), if its
+// shape is one the compiled bodies take (6, 9 or 15 k steps, no PReLU).  Measured on the launch of
+// the 28 small MobileNetV2 layers at batch 128 (per-workgroup timeline): 384 -> 96 moves 7.3
+// instead of 4.7 GB/s per workgroup, 576 -> 96 6.1 instead of 4.0, 960 -> 160 3.9-4.7 instead of
+// 1.7, and the layers that were one chunk anyway (384 -> 64) gain from the coalesced loads.
+struct WregPlan { int body, ntw, la, groups; };
+static bool wreg_plan(const PwArgs &m, WregPlan *p)
+{
+    if (m.K % 16 != 0 || m.Nc % 16 != 0 || m.mult_neg) return false;
+    const int tiles = m.Nc / 16;
+    switch (m.KS) {
+    case 6: p->ntw = tiles <= 4 ? 1 : 2; p->la = 3; p->body = tiles <= 4 ? kWreg6x1 : kWreg6x2; break;
+    case 9: p->ntw = tiles <= 8 ? 2 : 3; p->la = 2; p->body = tiles <= 8 ? kWreg9x2 : kWreg9x3; break;
+    case 15: p->ntw = 3; p->la = 1; p->body = kWreg15x3; break;
+    default: return false;
+    }
+    p->groups = (tiles + 4 * p->ntw - 1) / (4 * p->ntw);
+    return true;
+}
+
 static int launch_batch(const PwLaunch *const *members, int count, hipStream_t st)
 {
     static thread_local PwBatchArgs b;
@@ -610,7 +679,10 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         const int nt = batch_nt(m);
         int parts = 0;
         const int nsc = expand_plan(m, &parts);
-        if (nsc)
+        WregPlan wp;
+        if (wreg_plan(m, &wp))
+            total_work += (long long)m.M * ((long long)m.K * wp.groups + m.Nc);
+        else if (nsc)
             total_work += (long long)m.M * ((long long)m.K * parts + m.Nc);
         else
             total_work += (long long)m.M * (m.K + 16 * nt) * (((m.Nc + 15) / 16 + nt - 1) / nt);
@@ -629,7 +701,18 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
         size_t l;
         const bool full_rows = nsc && parts == 1 && a.KS == 1 &&
                                lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc) <= (size_t)kExpandLds;
-        if (full_rows) {
+        WregPlan wp;
+        const bool wreg = wreg_plan(a, &wp);
+        if (wreg) {
+            a.cw = -10 - wp.body;
+            // weights in registers: a workgroup belongs to one group of 64*ntw channels and walks
+            // over 16-pixel tiles, all four wavefronts on the same tile
+            a.n_chunks = wp.groups;
+            a.units = (a.M + 15) / 16;
+            const int gw = 64 * wp.ntw < a.Nc ? 64 * wp.ntw : a.Nc;
+            work = (long long)a.M * (a.K + gw);
+            l = lds_bytes_wreg(a.K, wp.ntw);
+        } else if (full_rows) {
             // all output channels in one part and a unit's rows small enough for LDS: whole rows
             a.cw = -1;
             a.n_chunks = 1;
@@ -648,13 +731,18 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
             work = (long long)a.M * (a.K + 16 * nt);
             l = lds_bytes_fast(nt, a.KS);
         }
-        const long long wg_units = (a.units + 3) / 4;
+        const long long wg_units = wreg ? a.units : (a.units + 3) / 4;
         const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
                                  : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
                                                                    : kBatchBytesPerWg / 4;
         done_work += work * a.n_chunks;
         long long wgs = (work + per_wg - 1) / per_wg;
-        if (nsc) {
+        if (wreg) {
+            // whole rounds of the prefetch ring: every workgroup the same number of steps
+            long long tiles_per_wg = (a.units + wgs - 1) / wgs;
+            tiles_per_wg = (tiles_per_wg + wp.la - 1) / wp.la * wp.la;
+            wgs = (a.units + tiles_per_wg - 1) / tiles_per_wg;
+        } else if (nsc) {
             // units are large here (16*G pixels x all channels of the part): give every wavefront
             // the same whole number of them
             const long long unit_bytes = full_rows ? 16LL * kExpandRowsG1 * (a.K + a.Nc) : 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
@@ -761,6 +849,23 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
 }
 
 }  // namespace prom
+
+#ifdef PROM_TIMELINE
+// Copies the timeline of the last launch of small layers to the host: t[2*i], t[2*i+1] = start
+// and end clock of workgroup i (0 if it never ran), member[i] = its layer.  Synchronises the device.
+extern "C" int prom_debug_timeline(unsigned long long *t_host, int *member_host, int n)
+{
+    if (!t_host || !member_host || n <= 0 || n > prom::kTimelineMax) return PROM_EINVAL;
+    if (hipDeviceSynchronize() != hipSuccess) return PROM_EHIP;
+    if (hipMemcpyFromSymbol(t_host, HIP_SYMBOL(prom::g_timeline), sizeof(unsigned long long) * 2 * n) != hipSuccess)
+        return PROM_EHIP;
+    if (hipMemcpyFromSymbol(member_host, HIP_SYMBOL(prom::g_timeline_member), sizeof(int) * n) != hipSuccess)
+        return PROM_EHIP;
+    static unsigned long long zeros[2 * prom::kTimelineMax];
+    if (hipMemcpyToSymbol(HIP_SYMBOL(prom::g_timeline), zeros, sizeof(zeros)) != hipSuccess) return PROM_EHIP;
+    return PROM_OK;
+}
+#endif
 
 extern "C" int prom_pw_batchable(int n, int h, int w, int cin, int cout)
 {

@@ -381,3 +381,47 @@ def test_sequence_large_wide_row_layers_ragged_pixel_count(P):
         torch.cuda.synchronize()
         for sh, l, want in zip(shapes, layers, wants):
             assert int((l[5] != want).sum()) == 0, f"run {run}: {sh}"
+
+
+def test_sequence_deep_projection_layers_keep_weights_in_registers(P):
+    """Layers with 6, 9 or 15 k steps (384, 576, 960 input channels and ragged variants) inside the
+    shared launch of small layers run the body that holds the weights in registers and passes the
+    activations through LDS.  Group counts 1 and 2 with a ragged last group, channel tiles that
+    leave wavefronts idle, pixel counts with a ragged last 16-pixel tile and fewer tiles than a
+    prefetch round, enough pixels for several workgroups and rounds, residual (also in place),
+    channels with shift 0, cin not a multiple of 64; outputs pre-filled, every byte compared."""
+    torch = torch_cuda()
+    cases = [  # n, h, w, cin, cout, shift_range, residual
+        (3, 7, 9, 384, 96, (3, 8), False), (3, 7, 9, 576, 96, (3, 8), True), (2, 7, 7, 576, 160, (3, 8), False),
+        (4, 7, 7, 960, 160, (3, 8), True), (5, 7, 7, 960, 320, (2, 9), False), (1, 1, 1, 960, 320, (3, 8), False),
+        (1, 3, 5, 576, 112, (0, 5), True), (2, 5, 3, 912, 208, (3, 8), False), (1, 9, 9, 336, 128, (0, 3), False),
+        (64, 14, 14, 576, 96, (3, 8), False), (40, 14, 14, 384, 96, (3, 8), True), (96, 7, 7, 960, 320, (3, 8), True),
+        (3, 7, 9, 64, 96, (3, 8), False), (3, 7, 9, 32, 192, (3, 8), False),  # neighbours with other bodies
+    ]
+    layers, wants = [], []
+    for i, (n, h, w, cin, cout, sr, res) in enumerate(cases):
+        L = make_pw_layer(9800 + i, n, h, w, cin, cout, signed_x=True, act_window=(-128, 127), shift_range=sr,
+                          with_residual=res)
+        y = torch.full((n, h, w, cout), -99, dtype=torch.int8, device="cuda")
+        r = dev(L.residual) if res else None
+        layers.append((dev(L.x), dev(P.prom_pack_ternary(L.weight)), cout, requant_dev(P, L), r, y))
+        wants.append(oracle_pw(oracle, L, residual=res))
+    seq = P.PwSequence(layers)
+    for run in range(2):
+        for l in layers:
+            l[5].fill_(-99)
+        seq.run()
+        torch.cuda.synchronize()
+        for c, l, want in zip(cases, layers, wants):
+            assert_same(l[5].cpu().numpy(), want, f"run {run}: case {c}")
+    # the residual read from the output buffer itself
+    inplace = []
+    for c, l, (n, h, w, cin, cout, sr, res) in zip(cases, layers, cases):
+        if res:
+            yb = l[4].clone()
+            inplace.append((c, (l[0], l[1], l[2], l[3], yb, yb)))
+    P.PwSequence([l for _c, l in inplace]).run()
+    torch.cuda.synchronize()
+    for (c, l) in inplace:
+        i = cases.index(c)
+        assert_same(l[5].cpu().numpy(), wants[i], f"in-place residual: case {c}")
