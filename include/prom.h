@@ -341,6 +341,18 @@ size_t prom_block_noalloc_max_workspace(void);
  * kernel is compared with, and the known-size reference for scaling hardware byte counters. */
 int prom_copy_bytes(const void *src, void *dst, size_t nbytes, void *stream);
 
+/* Read-only and write-only streaming kernels over nbytes (multiple of 16, 16-byte aligned) of
+ * device memory: the measured HBM ceilings that go beside the data-sheet bandwidth.  sink is a
+ * device int that is never written for ordinary data (it keeps the reads alive). */
+int prom_stream_read(const void *src, size_t nbytes, int *sink, void *stream);
+int prom_stream_write(void *dst, size_t nbytes, int value, void *stream);
+
+/* Register-resident int8 matrix-core loop (v_mfma_i32_16x16x64_i8, no memory traffic): the measured
+ * MFMA ceiling.  Every wavefront of a grid that fills the chip issues 8 * iters instructions.
+ * Returns the number of integer operations the launch performs (2 per multiply-accumulate), or a
+ * negative error code. */
+long long prom_mfma_i8_loop(int iters, int *sink, void *stream);
+
 /* Static, human-readable text for a return code. */
 const char *prom_strerror(int code);
 

@@ -122,6 +122,12 @@ def load_library():
     lib.prom_pw_batchable.argtypes = [ci, ci, ci, ci, ci]
     lib.prom_copy_bytes.restype = ci
     lib.prom_copy_bytes.argtypes = [vp, vp, sz, vp]
+    lib.prom_stream_read.restype = ci
+    lib.prom_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.prom_stream_write.restype = ci
+    lib.prom_stream_write.argtypes = [vp, sz, ci, vp]
+    lib.prom_mfma_i8_loop.restype = ctypes.c_longlong
+    lib.prom_mfma_i8_loop.argtypes = [ci, vp, vp]
     lib.prom_strerror.restype = ctypes.c_char_p
     lib.prom_strerror.argtypes = [ci]
     lib.prom_last_hip_error.restype = ctypes.c_char_p
@@ -525,3 +531,25 @@ def prom_copy_bytes(src, dst, nbytes: Optional[int] = None, stream=None):
     _check(load_library().prom_copy_bytes(src.data_ptr(), dst.data_ptr(), int(nbytes),
                                           _stream_ptr(stream)), "prom_copy_bytes")
     return dst
+
+
+def prom_stream_read(src, sink, nbytes: Optional[int] = None, stream=None):
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    _check(load_library().prom_stream_read(src.data_ptr(), int(nbytes), sink.data_ptr(), _stream_ptr(stream)),
+           "prom_stream_read")
+
+
+def prom_stream_write(dst, value: int = 0, nbytes: Optional[int] = None, stream=None):
+    if nbytes is None:
+        nbytes = dst.numel() * dst.element_size()
+    _check(load_library().prom_stream_write(dst.data_ptr(), int(nbytes), int(value), _stream_ptr(stream)),
+           "prom_stream_write")
+
+
+def prom_mfma_i8_loop(iters: int, sink, stream=None) -> int:
+    """Launches the register-resident int8 MFMA loop; returns the operations it performs."""
+    ops = int(load_library().prom_mfma_i8_loop(int(iters), sink.data_ptr(), _stream_ptr(stream)))
+    if ops < 0:
+        raise PromError(ops, "prom_mfma_i8_loop")
+    return ops
