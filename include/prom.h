@@ -288,12 +288,14 @@ int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout
 
 size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
 
-/* The same with the choice between the two forms of the block made by the caller: as one fused
- * kernel (the expanded tensor stays on chip) or as three launches through the workspace.
- * prom_block is prom_block_ex with PROM_BLOCK_AUTO, which takes the form measured faster for the
- * shape.  PROM_BLOCK_FUSED returns PROM_EUNSUPPORTED where the fused kernel does not apply
- * (prom_block_can_fuse, and x, y, w_dw 8-byte aligned). */
-enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2 };
+/* The same with the choice between the forms of the block made by the caller: as one fused kernel
+ * (the expanded tensor stays on chip), as three launches through the workspace, or as two launches
+ * (expand, then depthwise and projection fused: prom_dw_pw_conv; only the expanded tensor goes
+ * through the workspace).  prom_block is prom_block_ex with PROM_BLOCK_AUTO, which takes the form
+ * measured faster for the shape.  PROM_BLOCK_FUSED returns PROM_EUNSUPPORTED where the fused kernel
+ * does not apply (prom_block_can_fuse, and x, y, w_dw 8-byte aligned), PROM_BLOCK_DWPROJ where
+ * prom_dw_pw_can_fuse says no. */
+enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2, PROM_BLOCK_DWPROJ = 3 };
 int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
                   const void *w_expand_packed, const prom_requant_t *rq_expand,
                   const int8_t *w_dw, const prom_requant_t *rq_dw,
@@ -309,6 +311,25 @@ int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int st
 /* 1 if the fused kernel applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
  * cout <= 160, chid <= 192, a band of rows fits in LDS), 0 if not. */
 int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* ---- depthwise 3x3 and the pointwise projection behind it, in one kernel ---------------------
+ * The second half of the block (Section 2; Figure 4: depthwise, then the projecting pointwise
+ * layer, then the skip): y = pw(dw(x)) (+ residual), the depthwise output never leaves the chip.
+ * It is also the whole first bottleneck of MobileNetV2 (t = 1: no expansion layer).
+ *   x                 dev int8 [n][h][w][c]; w_dw dev int8 [3][3][c]; rq_dw [c]
+ *   w_project_packed  dev, prom_pack_ternary output for [cout][c]; rq_project [cout]
+ *   residual          dev int8 [n][ho][wo][cout] or NULL (may be y itself); y dev int8 [n][ho][wo][cout]
+ * The result is bit for bit that of prom_dw_conv followed by prom_pw_conv.  Limits
+ * (PROM_EUNSUPPORTED otherwise; prom_dw_pw_can_fuse tells): c % 16 == 0, cout % 4 == 0,
+ * cout <= 320, 4-byte aligned tensors below 2 GiB, and a band of at least one output row whose
+ * input rows are at most 256 pixels (w <= 85 at stride 1) and fit LDS with the layer's weights. */
+int prom_dw_pw_conv(const int8_t *x, int n, int h, int w, int c, const int8_t *w_dw, int stride,
+                    const prom_requant_t *rq_dw, const void *w_project_packed, int cout,
+                    const prom_requant_t *rq_project, const int8_t *residual, int8_t *y, void *stream);
+
+/* 1 if prom_dw_pw_conv takes the shape (pointers assumed aligned), 0 if not, PROM_EINVAL for bad
+ * dimensions.  Host only. */
+int prom_dw_pw_can_fuse(int n, int h, int w, int c, int cout, int stride);
 
 /* ---- the block for callers that cannot allocate --------------------------------------------
  * For callers that cannot call hipMalloc or bring a workspace: code under HIP graph capture,

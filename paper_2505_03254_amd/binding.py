@@ -98,6 +98,11 @@ def load_library():
                                        vp, ctypes.POINTER(_RequantC), ci, vp, vp]
     lib.prom_block_noalloc_max_workspace.restype = sz
     lib.prom_block_noalloc_max_workspace.argtypes = []
+    lib.prom_dw_pw_conv.restype = ci
+    lib.prom_dw_pw_conv.argtypes = [vp, ci, ci, ci, ci, vp, ci, ctypes.POINTER(_RequantC), vp, ci,
+                                    ctypes.POINTER(_RequantC), vp, vp, vp]
+    lib.prom_dw_pw_can_fuse.restype = ci
+    lib.prom_dw_pw_can_fuse.argtypes = [ci] * 6
     lib.prom_block_can_fuse.restype = ci
     lib.prom_block_can_fuse.argtypes = [ci] * 7
     lib.prom_block_workspace_size.restype = sz
@@ -364,7 +369,36 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
     return y
 
 
-BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED = 0, 1, 2
+BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ = 0, 1, 2, 3
+
+
+def prom_dw_pw_conv(x, w_dw, stride: int, rq_dw: Requant, w_project_packed, cout: int, rq_project: Requant,
+                    residual=None, y=None, stream=None):
+    """Depthwise 3x3 and the pointwise projection behind it in one kernel."""
+    import torch
+    _dev_i8(x, "x")
+    _dev_i8(w_dw, "w_dw")
+    n, h, w, c = x.shape
+    ho, wo = (h - 1) // stride + 1, (w - 1) // stride + 1
+    if y is None:
+        y = torch.empty((n, ho, wo, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(y, "y")
+    if residual is not None:
+        _dev_i8(residual, "residual")
+    d, p = rq_dw._c(), rq_project._c()
+    rc = load_library().prom_dw_pw_conv(
+        x.data_ptr(), n, h, w, c, w_dw.data_ptr(), int(stride), ctypes.byref(d), w_project_packed.data_ptr(),
+        int(cout), ctypes.byref(p), residual.data_ptr() if residual is not None else None, y.data_ptr(),
+        _stream_ptr(stream))
+    _check(rc, "prom_dw_pw_conv")
+    return y
+
+
+def prom_dw_pw_can_fuse(n: int, h: int, w: int, c: int, cout: int, stride: int) -> bool:
+    rc = load_library().prom_dw_pw_can_fuse(n, h, w, c, cout, stride)
+    if rc < 0:
+        raise PromError(rc, "prom_dw_pw_can_fuse")
+    return bool(rc)
 
 
 def prom_block_noalloc(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand: Requant,

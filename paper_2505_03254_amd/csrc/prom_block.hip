@@ -416,6 +416,23 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid, bool f
 
 }  // namespace prom
 
+// Whether PROM_BLOCK_AUTO takes the two-launch form (expand; depthwise + projection fused) instead
+// of three launches: at present never.  Measured (GPU time of depthwise + projection as two kernels
+// against the one fused kernel): a workgroup of the fused kernel walks over the hidden channels in
+// chunks of 64 at 1.3 to 1.8 us per chunk (instruction latency of one wavefront per SIMD, not
+// memory) plus 8 us of staging and epilogue.  It is level with the two kernels at 14x14x384 (18 to
+// 22 against 18 to 19 us), loses from 576 hidden channels on (27 to 37 against 19 to 22) and on large
+// maps (56x56x144 at batch 128: 106 against 44), and where it wins under eager launches (28x28x192 at
+// batch 8: 11.8 against 18.4; at batch 128: 19.8 against 23.7) the 17-block chain replayed from a HIP
+// graph is slower with it (316 against 291 us at batch 8), because two short kernels cost less there
+// than the serial chunk loop.  The form stays available through PROM_BLOCK_DWPROJ and
+// prom_dw_pw_conv: it moves one intermediate tensor less through HBM.
+static bool dwproj_is_faster(int n, int h, int w, int chid, int cout, int stride)
+{
+    (void)n; (void)h; (void)w; (void)chid; (void)cout; (void)stride;
+    return false;
+}
+
 extern "C" size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride)
 {
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
@@ -468,7 +485,8 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
                              int path, void *stream)
 {
     using namespace prom;
-    if (path != PROM_BLOCK_AUTO && path != PROM_BLOCK_FUSED && path != PROM_BLOCK_UNFUSED) return PROM_EINVAL;
+    if (path != PROM_BLOCK_AUTO && path != PROM_BLOCK_FUSED && path != PROM_BLOCK_UNFUSED && path != PROM_BLOCK_DWPROJ)
+        return PROM_EINVAL;
     if (!x || !y || !w_expand_packed || !w_dw || !w_project_packed || !rq_expand || !rq_dw || !rq_project)
         return PROM_EINVAL;
     if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
@@ -512,7 +530,8 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
     BlockFn fn = nullptr;
     size_t lds = 0;
     int grid = 0;
-    const bool fuse = path != PROM_BLOCK_UNFUSED && aligned && plan_fused(a, fn, lds, grid, path == PROM_BLOCK_FUSED);
+    const bool fuse = path != PROM_BLOCK_UNFUSED && path != PROM_BLOCK_DWPROJ && aligned &&
+                      plan_fused(a, fn, lds, grid, path == PROM_BLOCK_FUSED);
     if (path == PROM_BLOCK_FUSED && !fuse) return PROM_EUNSUPPORTED;
     if (fuse) {
         static std::mutex mu;
@@ -545,6 +564,16 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
         return check_launch();
     }
 
+    // two launches: expand, then depthwise and projection in one kernel
+    const bool can_dwproj = prom_dw_pw_can_fuse(n, h, w, chid, cout, stride) == 1 &&
+                            ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_project_packed | (uintptr_t)w_dw) & 3) == 0);
+    if (path == PROM_BLOCK_DWPROJ && !can_dwproj) return PROM_EUNSUPPORTED;
+    if (path == PROM_BLOCK_DWPROJ || (path == PROM_BLOCK_AUTO && can_dwproj && dwproj_is_faster(n, h, w, chid, cout, stride))) {
+        const int rc2 = prom_pw_conv(x, n, h, w, cin, w_expand_packed, chid, rq_expand, nullptr, t1, stream);
+        if (rc2 != PROM_OK) return rc2;
+        return prom_dw_pw_conv(t1, n, h, w, chid, w_dw, stride, rq_dw, w_project_packed, cout, rq_project,
+                               add_residual ? x : nullptr, y, stream);
+    }
     // three launches through the workspace
     int rc = prom_pw_conv(x, n, h, w, cin, w_expand_packed, chid, rq_expand, nullptr, t1, stream);
     if (rc != PROM_OK) return rc;

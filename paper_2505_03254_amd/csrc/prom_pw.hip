@@ -183,6 +183,15 @@ __device__ __forceinline__ void pw_wreg_member(int body, const PwArgs &a, const 
 // member through a copy of the bodies compiled for its kind alone (a body that carries both
 // epilogues needs more registers than either).
 #ifdef PROM_TIMELINE
+// Developer build: where single-layer launches record their stamps (see PW_STAMP), and a marker
+// kernel that records the clock between launches.
+static int32_t *&debug_stamp_buffer()
+{
+    static int32_t *p = nullptr;
+    return p;
+}
+__global__ void debug_mark_kernel(unsigned long long *buf, int slot) { buf[slot] = wall_clock64(); }
+
 // Developer build (-DPROM_TIMELINE): every workgroup of the shared launch of small layers records
 // the constant-rate clock (100 MHz) at its start and end and the member it ran, for a
 // per-workgroup timeline of the launch; read back with prom_debug_timeline.
@@ -408,6 +417,9 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     a.residual = mode == 0 ? residual : nullptr;
     a.y = y;
     a.acc_out = acc_out;
+#ifdef PROM_TIMELINE
+    if (mode == 0) a.acc_out = debug_stamp_buffer();
+#endif
     a.M = (int)M;
     a.K = cin;
     a.Nc = cout;
@@ -851,6 +863,18 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
 }  // namespace prom
 
 #ifdef PROM_TIMELINE
+extern "C" int prom_debug_set_stamp_buffer(void *dev_buf)
+{
+    prom::debug_stamp_buffer() = static_cast<int32_t *>(dev_buf);
+    return PROM_OK;
+}
+extern "C" int prom_debug_mark(void *dev_buf, int slot, void *stream)
+{
+    hipLaunchKernelGGL(prom::debug_mark_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream),
+                       static_cast<unsigned long long *>(dev_buf), slot);
+    return PROM_OK;
+}
+
 // Copies the timeline of the last launch of small layers to the host: t[2*i], t[2*i+1] = start
 // and end clock of workgroup i (0 if it never ran), member[i] = its layer.  Synchronises the device.
 extern "C" int prom_debug_timeline(unsigned long long *t_host, int *member_host, int n)

@@ -42,15 +42,38 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
     const int KS = a.KS, Nc = a.Nc;
     const int NTT = CW * NT;
     const int nfrag = NTT * KS * 64;
+    // The parameter loads and the first batch of weight loads are issued in straight-line code, so
+    // that they leave together with the activation loads issued before this call: one memory
+    // round trip for everything a workgroup needs before its first MFMA.
+    constexpr int PU = 2;  // parameter slots per thread (NTT*16 <= 24*16 channels, >= 192 threads)
+    int pb[PU], pm[PU], pn[PU], ps[PU];
+#pragma unroll
+    for (int q = 0; q < PU; ++q) {
+        const int s = tid + q * nthr;
+        const int tt = (s >> 4) < NTT ? (s >> 4) : 0;
+        const int cw = tt / NT;
+        const int t = tt - cw * NT;
+        const int c = cbase + cw * NT * 16 + chan_of<NT>(t, (s >> 2) & 3, s & 3);
+        const bool ok = s < NTT * 16 && c < Nc;
+        const int ci = ok ? c : 0;
+        pb[q] = a.bias[ci];
+        pm[q] = a.mult[ci];
+        ps[q] = a.shift[ci];
+        pn[q] = prelu ? a.mult_neg[ci] : 0;
+        if (!ok) {
+            pb[q] = 0; pm[q] = 0; pn[q] = 0; ps[q] = 1;
+        }
+    }
     constexpr int U = 8;  // words in flight per thread
-    for (int base = 0; base < nfrag; base += nthr * U) {
+    const unsigned recip = (65536u + (unsigned)KS - 1u) / (unsigned)KS;  // tk / KS == (tk * recip) >> 16 for tk < 1024
+    auto batch = [&](const int base) __attribute__((always_inline)) {
         uint32_t word[U];
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const int idx = base + q * nthr + tid;
-            const int tk = idx >> 6;
-            const int ks = tk % KS;
-            const int tt = tk / KS;
+            const int tk = idx < nfrag ? idx >> 6 : 0;
+            const int tt = (int)(((unsigned)tk * recip) >> 16);
+            const int ks = tk - tt * KS;
             const int cw = tt / NT;
             const int t = tt - cw * NT;
             const int i = idx & 15;
@@ -65,20 +88,27 @@ __device__ __forceinline__ void stage_weights_rows(const PwArgs &a, int cbase, i
             const int idx = base + q * nthr + tid;
             if (idx < nfrag) frag[idx] = decode_word(word[q]);
         }
+    };
+    batch(0);
+    for (int base = nthr * U; base < nfrag; base += nthr * U) batch(base);
+#pragma unroll
+    for (int q = 0; q < PU; ++q) {
+        const int s = tid + q * nthr;
+        if (s < NTT * 16) lpar[s] = requant_params(pb[q], pm[q], pn[q], ps[q], prelu);
     }
-    for (int s = tid; s < NTT * 16; s += nthr) {
+    for (int s = tid + PU * nthr; s < NTT * 16; s += nthr) {  // (not reached with the compiled shapes)
         const int tt = s >> 4;
         const int cw = tt / NT;
         const int t = tt - cw * NT;
         const int c = cbase + cw * NT * 16 + chan_of<NT>(t, (s >> 2) & 3, s & 3);
-        int pb = 0, pm = 0, pn = 0, ps = 1;
+        int qb = 0, qm = 0, qn = 0, qs = 1;
         if (c < Nc) {
-            pb = a.bias[c];
-            pm = a.mult[c];
-            ps = a.shift[c];
-            if (prelu) pn = a.mult_neg[c];
+            qb = a.bias[c];
+            qm = a.mult[c];
+            qs = a.shift[c];
+            if (prelu) qn = a.mult_neg[c];
         }
-        lpar[s] = requant_params(pb, pm, pn, ps, prelu);
+        lpar[s] = requant_params(qb, qm, qn, qs, prelu);
     }
     __syncthreads();
 }

@@ -101,8 +101,9 @@ template <int NT, bool WITH_PARAMS>
 __device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *frag, v4i *lpar, bool prelu)
 {
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KS = a.KS, Nc = a.Nc;
-    const int nfrag = NT * KS * 64;
     int pb = 0, pm = 0, pn = 0, ps = 1;
     const bool ptid = WITH_PARAMS && tid < NT * 16;
     if (ptid) {
@@ -114,28 +115,74 @@ __device__ __forceinline__ void stage_weights(const PwArgs &a, int cbase, v4i *f
             if (prelu) pn = a.mult_neg[c];
         }
     }
-    constexpr int U = 16;  // words in flight per thread
-    for (int base = 0; base < nfrag; base += 256 * U) {
-        uint32_t word[U];
+    // A fragment entry e = t*KS + ks is 64 lanes x 16 bytes: lane (i, kg) holds the decoded word
+    // 4*ks + kg of the row of channel chan_of(t, i).  The loads of a batch are issued back to back
+    // -- the first batch in straight-line code, so that it leaves together with the activation
+    // loads issued before this call instead of behind a wait at a loop header -- and decoded as
+    // they arrive.
+    const int total = NT * KS;
+    if ((a.KW & 3) == 0 && (reinterpret_cast<uintptr_t>(a.wq) & 15) == 0) {
+        // Rows of whole 16-byte pieces: a thread fetches the four words of (entry, i) with one
+        // load and decodes them for the lanes kg = 0..3 of the entry; 16 threads per entry.
+        constexpr int U = 4;
+        const unsigned recip = (65536u + (unsigned)KS - 1u) / (unsigned)KS;  // e / KS == (e * recip) >> 16 for e < 1024
+        const int i = tid & 15;
+        auto batch = [&](const int v0) __attribute__((always_inline)) {
+            v4i w4[U];
 #pragma unroll
-        for (int q = 0; q < U; ++q) {
-            const int idx = base + q * 256 + tid;
-            const int tk = idx >> 6;
-            const int ks = tk % KS;
-            const int t = tk / KS;
-            const int i = idx & 15;
-            const int c = cbase + chan_of<NT>(t, i >> 2, i & 3);
-            const int kw = 4 * ks + ((idx & 63) >> 4);
-            // clamp instead of branching so that the loads of a batch are issued back to back
-            const bool ok = idx < nfrag && c < Nc && kw < a.KW;
-            const uint32_t v = a.wq[ok ? (long long)c * a.KW + kw : 0];
-            word[q] = ok ? v : 0u;
-        }
+            for (int q = 0; q < U; ++q) {
+                const int e = (v0 + 256 * q + tid) >> 4;
+                const int t = (int)(((unsigned)e * recip) >> 16), ks = e - t * KS;
+                const bool valid = e < total;
+                const int c = cbase + chan_of<NT>(valid ? t : 0, i >> 2, i & 3);
+                const bool ok = valid && c < Nc;
+                const v4i v = *reinterpret_cast<const v4i *>(a.wq + (ok ? (long long)c * a.KW + 4 * ks : 0));
+                w4[q] = ok ? v : v4i{0, 0, 0, 0};
+            }
 #pragma unroll
-        for (int q = 0; q < U; ++q) {
-            const int idx = base + q * 256 + tid;
-            if (idx < nfrag) frag[idx] = decode_word(word[q]);
+            for (int q = 0; q < U; ++q) {
+                const int e = (v0 + 256 * q + tid) >> 4;
+                if (e < total) {
+#pragma unroll
+                    for (int kg = 0; kg < 4; ++kg) frag[e * 64 + 16 * kg + i] = decode_word((uint32_t)w4[q][kg]);
+                }
+            }
+        };
+        batch(0);
+        for (int v0 = 256 * U; v0 < total * 16; v0 += 256 * U) batch(v0);
+    } else {
+        // Any row length: one word per lane; wavefront w decodes entries w, w + 4, ... (tile and k
+        // step of an entry are wave-uniform and advance without a division).
+        constexpr int U = 16;
+        const int i = lane & 15, kg = lane >> 4;
+        int t = 0, ks = wave;
+        while (ks >= KS) {
+            ks -= KS;
+            ++t;
         }
+        auto batch = [&](const int e0) __attribute__((always_inline)) {
+            uint32_t word[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const bool valid = e0 + 4 * q < total;
+                const int c = cbase + chan_of<NT>(valid ? t : 0, i >> 2, i & 3);
+                const int kw = 4 * ks + kg;
+                // clamp instead of branching so that the loads of a batch are issued back to back
+                const bool ok = valid && c < Nc && kw < a.KW;
+                const uint32_t v = a.wq[ok ? (long long)c * a.KW + kw : 0];
+                word[q] = ok ? v : 0u;
+                ks += 4;
+                while (ks >= KS) {
+                    ks -= KS;
+                    ++t;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q)
+                if (e0 + 4 * q < total) frag[(e0 + 4 * q) * 64 + lane] = decode_word(word[q]);
+        };
+        batch(wave);
+        for (int e0 = wave + 4 * U; e0 < total; e0 += 4 * U) batch(e0);
     }
     if (ptid) lpar[tid] = requant_params(pb, pm, pn, ps, prelu);
     __syncthreads();
@@ -175,9 +222,22 @@ constexpr int kOobOffset = 0x7ffff000;  // byte offset beyond any tensor handled
 //          conditions, compile-time staging geometry).
 // ============================================================================================
 // `lid` is the workgroup's logical id within this layer's grid (see logical_block_id).
+#ifdef PROM_TIMELINE
+// Developer build: the first 64 logical workgroups of a single-layer launch record the 100 MHz
+// clock at 8 points of their life into the buffer the host passed in a.acc_out (unused otherwise).
+#define PW_STAMP(i)                                                                                  \
+    do {                                                                                             \
+        if (a.acc_out && threadIdx.x == 0 && lid < 64)                                               \
+            reinterpret_cast<unsigned long long *>(a.acc_out)[lid * 8 + (i)] = wall_clock64();       \
+    } while (0)
+#else
+#define PW_STAMP(i) do { } while (0)
+#endif
+
 template <int NT, int PT, int XMODE, bool KS1, bool FULLW, int D = ring_depth<PT>(), int EPI = kEpiPlain>
 __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, unsigned char *lds_raw)
 {
+    PW_STAMP(0);
     // PReLU layer?  Known at compile time unless the body carries both kinds of epilogue.
     const bool prelu = EPI == kEpiPrelu || (EPI == kEpiBoth && a.mult_neg != nullptr);
     constexpr int NI = (NT + 3) / 4;  // 16-byte store instructions per staged tile
@@ -234,7 +294,9 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
     v4i ring[D][PT];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
+    PW_STAMP(1);
     stage_weights<NT, true>(a, cbase, frag, lpar, prelu);
+    PW_STAMP(2);
 
     // per-lane parameters: 4 channels per tile slot.  The lanes of a wavefront hold every channel
     // of the chunk between them, so a wavefront can see by itself whether any shift is 0 and
@@ -417,9 +479,11 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
                 ytile = min(ytile + ystep, (unsigned)kOobOffset);
             }
         };
+        PW_STAMP(3);
         for (int it = 0; it < full_rounds; ++it) {
 #pragma unroll
             for (int d = 0; d < D; ++d) step(ring[d], std::true_type{});
+            if (it == 0) PW_STAMP(4);
         }
 #pragma nounroll
         for (int r = 0; r < tail_steps; ++r) {
@@ -429,6 +493,11 @@ __device__ __forceinline__ void pw_stream_body(const PwArgs &a, const int lid, u
 #pragma unroll
                 for (int p = 0; p < PT; ++p) ring[d][p] = ring[d + 1][p];
         }
+        PW_STAMP(5);
+#ifdef PROM_TIMELINE
+        __builtin_amdgcn_s_waitcnt(0);
+        PW_STAMP(6);
+#endif
     };
 
     using Fast = std::integral_constant<int, 0>;

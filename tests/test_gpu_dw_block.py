@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from workloads import make_dw_layer, make_block, BASELINE_CONFIGS, CONFIG_SEED_BASE
+from workloads import make_dw_layer, make_pw_layer, make_block, BASELINE_CONFIGS, CONFIG_SEED_BASE
 from gpu_util import assert_same, dev, requant_dev, torch_cuda
 
 pytestmark = pytest.mark.gpu
@@ -130,8 +130,9 @@ def test_block_config4_full_output(P):
     # tiles), 3 chunks with a ragged last one, the smallest and a single-row image
     (2, 28, 28, 24, 6, 24, 1), (1, 17, 9, 40, 4, 96, 2), (2, 7, 7, 32, 6, 160, 1), (1, 14, 14, 24, 7, 136, 1),
     (3, 1, 1, 16, 6, 16, 1), (1, 1, 37, 32, 5, 32, 1), (1, 37, 1, 32, 5, 32, 2),
-    # more than 3 chunks of hidden channels: weights streamed through two LDS slots (4, 5, 6, 9, 15
-    # chunks, ragged last chunk, every projection width class, both strides)
+    # more than 3 chunks of hidden channels (4, 5, 6, 9, 15 chunks, ragged last chunk, every
+    # projection width class, both strides): the fully fused kernel refuses these, the two-launch
+    # form (depthwise and projection fused) takes them
     (2, 14, 14, 64, 6, 64, 1), (2, 14, 14, 64, 6, 96, 1), (2, 14, 14, 96, 6, 96, 1), (1, 14, 14, 96, 6, 160, 2),
     (2, 7, 7, 160, 6, 160, 1), (1, 9, 11, 64, 5, 32, 1), (1, 10, 6, 40, 7, 24, 2), (3, 5, 5, 128, 2, 128, 1),
 ])
@@ -147,6 +148,13 @@ def test_block_shapes(P, shape):
             _run_block(P, B, P.BLOCK_FUSED)
         assert e.value.code == -2
     assert_same(_run_block(P, B, P.BLOCK_UNFUSED), want, f"block {shape} three launches")
+    # expand, then depthwise and projection in one kernel
+    if P.prom_dw_pw_can_fuse(n, h, w, cin * t, cout, stride):
+        assert_same(_run_block(P, B, P.BLOCK_DWPROJ), want, f"block {shape} two launches")
+    else:
+        with pytest.raises(P.PromError) as e:
+            _run_block(P, B, P.BLOCK_DWPROJ)
+        assert e.value.code == -2
     assert_same(_run_block(P, B), want, f"block {shape}")
 
 
@@ -160,3 +168,68 @@ def test_block_forms_and_queries(P):
     assert not P.prom_block_can_fuse(2, 7, 7, 32, 192, 320, 1)       # 320 output channels
     assert not P.prom_block_can_fuse(2, 7, 7, 12, 72, 16, 1)         # cin % 8 != 0
     assert P.prom_block_can_fuse(1, 28, 28, 24, 144, 24, 1)          # 24 input channels: padded pixels
+
+
+DWPW_SHAPES = [
+    # n, h, w, c, cout, stride, residual
+    (2, 14, 14, 384, 64, 1, True), (3, 14, 14, 576, 96, 1, True), (2, 14, 14, 576, 160, 2, False),
+    (3, 7, 7, 960, 160, 1, True), (2, 7, 7, 960, 320, 1, False), (40, 14, 14, 384, 96, 1, False),
+    (80, 7, 7, 960, 160, 1, True), (1, 1, 1, 64, 16, 1, True), (1, 1, 9, 16, 8, 1, False), (2, 9, 1, 32, 4, 2, False),
+    # ragged last chunk of hidden channels (144, 80, 208), bands with a ragged last one, wide rows,
+    # stride 2 on odd and even sizes, every projection width class
+    (2, 12, 12, 144, 24, 1, True), (1, 13, 17, 80, 40, 2, False), (2, 28, 28, 192, 32, 1, True),
+    (1, 28, 28, 192, 64, 2, False), (1, 56, 56, 144, 24, 1, True), (1, 5, 85, 48, 16, 1, False),
+    (2, 15, 11, 208, 112, 2, False), (1, 7, 7, 128, 320, 1, True), (5, 6, 7, 320, 200, 1, False),
+    (1, 30, 85, 32, 16, 1, False),
+]
+
+
+@pytest.mark.parametrize("shape", DWPW_SHAPES)
+def test_dw_pw_fused_shapes(P, shape):
+    """prom_dw_pw_conv (depthwise 3x3 and the projection behind it in one kernel) against the
+    oracle's depthwise layer followed by its pointwise layer, every output."""
+    torch = torch_cuda()
+    n, h, w, c, cout, stride, res = shape
+    ho, wo = (h - 1) // stride + 1, (w - 1) // stride + 1
+    D = make_dw_layer(7100 + c + cout, n, h, w, c, stride, signed_x=True, act_window=(0, 127), shift_range=(4, 10))
+    Q = make_pw_layer(7200 + c + cout, n, ho, wo, c, cout, act_window=(-128, 127), shift_range=(5, 9),
+                      with_residual=res, make_x=False)
+    assert P.prom_dw_pw_can_fuse(n, h, w, c, cout, stride)
+    mid = oracle.dw_conv(D.x, D.weight, stride, D.bias, D.mult, D.shift, 0, 127)
+    want = oracle.pw_conv(mid, Q.weight, Q.bias, Q.mult, Q.shift, -128, 127, Q.residual if res else None)
+    y = torch.full((n, ho, wo, cout), -99, dtype=torch.int8, device="cuda")
+    P.prom_dw_pw_conv(dev(D.x), dev(D.weight), stride, requant_dev(P, D), dev(P.prom_pack_ternary(Q.weight)), cout,
+                      requant_dev(P, Q), dev(Q.residual) if res else None, y)
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), want, f"dw+pw {shape}")
+    if res:  # the residual read from the output buffer itself
+        yb = dev(Q.residual)
+        P.prom_dw_pw_conv(dev(D.x), dev(D.weight), stride, requant_dev(P, D), dev(P.prom_pack_ternary(Q.weight)),
+                          cout, requant_dev(P, Q), yb, yb)
+        torch.cuda.synchronize()
+        assert_same(yb.cpu().numpy(), want, f"dw+pw {shape}, residual in place")
+
+
+def test_dw_pw_fused_shift_zero_prelu_and_limits(P):
+    """Shifts from 0 up in both layers, PReLU multipliers in either or both layers, and the shapes
+    the kernel refuses."""
+    torch = torch_cuda()
+    from workloads import prelu_mult_neg
+    n, h, w, c, cout = 3, 14, 14, 384, 96
+    for case, (dsr, psr, dneg, pneg) in enumerate([((0, 4), (0, 6), False, False), ((3, 8), (4, 8), True, False),
+                                                   ((3, 8), (4, 8), False, True), ((0, 5), (0, 5), True, True)]):
+        D = make_dw_layer(7300 + case, n, h, w, c, 1, signed_x=True, act_window=(-128, 127), shift_range=dsr)
+        Q = make_pw_layer(7310 + case, n, h, w, c, cout, act_window=(-128, 127), shift_range=psr, make_x=False)
+        dn = prelu_mult_neg(7320 + case, D.mult) if dneg else None
+        pn = prelu_mult_neg(7330 + case, Q.mult) if pneg else None
+        mid = oracle.dw_conv(D.x, D.weight, 1, D.bias, D.mult, D.shift, -128, 127, mult_neg=dn)
+        want = oracle.pw_conv(mid, Q.weight, Q.bias, Q.mult, Q.shift, -128, 127, mult_neg=pn)
+        rqd = P.Requant(dev(D.bias), dev(D.mult), dev(D.shift), -128, 127, dev(dn) if dneg else None)
+        rqp = P.Requant(dev(Q.bias), dev(Q.mult), dev(Q.shift), -128, 127, dev(pn) if pneg else None)
+        y = P.prom_dw_pw_conv(dev(D.x), dev(D.weight), 1, rqd, dev(P.prom_pack_ternary(Q.weight)), cout, rqp)
+        torch.cuda.synchronize()
+        assert_same(y.cpu().numpy(), want, f"dw+pw case {case}")
+    assert not P.prom_dw_pw_can_fuse(1, 8, 8, 24, 16, 1)     # c % 16 != 0
+    assert not P.prom_dw_pw_can_fuse(1, 8, 8, 32, 336, 1)    # more than 320 output channels
+    assert not P.prom_dw_pw_can_fuse(1, 8, 200, 32, 16, 1)   # three input rows are more than 256 pixels
+    assert P.prom_dw_pw_can_fuse(128, 14, 14, 576, 96, 1) and P.prom_dw_pw_can_fuse(128, 7, 7, 960, 320, 1)
