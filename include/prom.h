@@ -5,8 +5,8 @@
  *   - a pointwise 1x1 convolution whose weights are ternary {-1,0,+1}, so that every
  *     output is a signed sum of int8 input channels (paper Section 2, last paragraph;
  *     Section 3.1 "Pointwise Convolutions"; Figure 12, inference branch), followed by a
- *     per-output-channel rescale (Section 3.1: "scaled by alpha afterwards"; Figure 12:
- *     dequantise after the convolution), here in integer form;
+ *     per-output-channel rescale after the convolution (Section 3.1, "Pointwise
+ *     Convolutions"; Figure 12), here in integer form;
  *   - the int8 depthwise 3x3 convolution that sits between two pointwise convolutions
  *     (Section 2, first paragraph; Section 3.1 "Depthwise Convolutions", Eq. 4-5);
  *   - the block expand -> depthwise -> project with optional skip (Section 2; Figure 4).
@@ -28,9 +28,13 @@
  *               The paper rescales in floating point (Figure 12); this integer form with
  *               bias (folded BatchNorm shift), Q31 multiplier and shift is the contract of
  *               this library.  Preconditions (not checked, the arrays live on the device):
- *               0 < mult[c] < 2^31, 0 <= shift[c] <= 31, |bias[c]| < 2^29 and |acc + bias[c]| < 2^30.
- *   Errors      every int-returning function returns PROM_OK (0) or a negative code; on
- *               error nothing has been enqueued.
+ *               0 < mult[c] < 2^31, 0 <= shift[c] <= 31, |bias[c]| < 2^29 and |acc + bias[c]| < 2^30;
+ *               prom_requant_check copies the arrays back and checks them, for tests and bring-up.
+ *   Errors      every int-returning function returns PROM_OK (0) or a negative code; on an
+ *               argument error nothing has been enqueued.  PROM_EHIP (the runtime refused a
+ *               launch) from an entry point that makes several launches -- prom_block in its
+ *               multi-launch forms, prom_pw_conv_sequence -- can leave the earlier launches
+ *               enqueued.
  */
 #ifndef PROM_H
 #define PROM_H
@@ -74,6 +78,17 @@ typedef struct {
     int32_t act_max;         /*  output scale maps 6.0 to 127                                 */
     const int32_t *mult_neg; /* dev [C] or NULL: PReLU multiplier for acc + bias < 0          */
 } prom_requant_t;
+
+/* Opt-in check of the preconditions above, for tests and bring-up (the layer entry points cannot
+ * afford it: the arrays live on the device).  Copies bias, mult and shift of `channels` channels
+ * back to the host -- which waits for the work already enqueued on the device -- and returns
+ * PROM_EINVAL, with the first offending channel in *bad_channel (if not NULL), when a multiplier
+ * is not in (0, 2^31), a shift not in [0, 31], |bias| >= 2^29, or 128 * cin + |bias| >= 2^30
+ * (the accumulator of a pointwise layer with cin input channels is at most 128 * cin in
+ * magnitude; for a depthwise or grouped 3x3 layer, whose weights reach 127, pass
+ * cin = 9 * 127 * group_size).  mult_neg may be
+ * any int32 and is not looked at.  PROM_EHIP if the copies fail. */
+int prom_requant_check(const prom_requant_t *rq, int channels, int cin, int *bad_channel);
 
 /* Optional launch plan of prom_pw_conv_ex; zero in a field means "library default".
  * With tiles_per_wave or pixel_tiles given and row_waves == 0 the plain streaming kernel runs

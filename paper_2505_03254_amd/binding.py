@@ -133,6 +133,8 @@ def load_library():
     lib.prom_stream_write.argtypes = [vp, sz, ci, vp]
     lib.prom_mfma_i8_loop.restype = ctypes.c_longlong
     lib.prom_mfma_i8_loop.argtypes = [ci, vp, vp]
+    lib.prom_requant_check.restype = ci
+    lib.prom_requant_check.argtypes = [ctypes.POINTER(_RequantC), ci, ci, ctypes.POINTER(ci)]
     lib.prom_strerror.restype = ctypes.c_char_p
     lib.prom_strerror.argtypes = [ci]
     lib.prom_last_hip_error.restype = ctypes.c_char_p
@@ -587,3 +589,16 @@ def prom_mfma_i8_loop(iters: int, sink, stream=None) -> int:
     if ops < 0:
         raise PromError(ops, "prom_mfma_i8_loop")
     return ops
+
+
+def prom_requant_check(rq: Requant, cin: int) -> int:
+    """Opt-in check of the requantisation preconditions (copies the arrays to the host).  Returns -1
+    if they hold, else the first offending channel."""
+    rqc = rq._c()
+    bad = ctypes.c_int(-1)
+    rc = load_library().prom_requant_check(ctypes.byref(rqc), int(rq.bias.numel()), int(cin), ctypes.byref(bad))
+    if rc == PROM_OK:
+        return -1
+    if rc == -1 and bad.value >= 0:
+        return bad.value
+    raise PromError(rc, "prom_requant_check")

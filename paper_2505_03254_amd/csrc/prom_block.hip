@@ -564,6 +564,13 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
         return check_launch();
     }
 
+    // the multi-launch forms: refuse now what one of the later layers would refuse
+    {
+        int rc0 = pw_shape_check(n, h, w, cin, chid);
+        if (rc0 == PROM_OK) rc0 = dw_shape_check(n, h, w, chid, stride);
+        if (rc0 == PROM_OK) rc0 = pw_shape_check(n, ho, wo, chid, cout);
+        if (rc0 != PROM_OK) return rc0;
+    }
     // two launches: expand, then depthwise and projection in one kernel
     const bool can_dwproj = prom_dw_pw_can_fuse(n, h, w, chid, cout, stride) == 1 &&
                             ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_project_packed | (uintptr_t)w_dw) & 3) == 0);

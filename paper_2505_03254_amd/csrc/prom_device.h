@@ -11,18 +11,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
 
-// Bias applied to the rounded quotient before the float->int truncation so that the
-// truncation acts as floor over the whole clamp window (see requant_to_biased).
-constexpr int kQBias = 256;
-
-// Put the wave's double-precision rounding mode to round-toward-minus-infinity (MODE
-// register FP_ROUND bits [3:2]).  Every kernel that calls requant_to_biased executes this
-// first; the kernels use no other f64/f16 arithmetic whose rounding matters.
-__device__ __forceinline__ void set_f64_round_down()
-{
-    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 2");
-}
-
 // min(max(v, lo), hi); becomes one v_med3_i32 when lo and hi sit in vector registers or are
 // inline constants (the instruction can read at most one scalar register).
 __device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max(v, lo), hi); }
@@ -42,27 +30,6 @@ __device__ __forceinline__ int in_vgpr(int v)
 {
     asm volatile("" : "+v"(v));
     return v;
-}
-
-// scale = mult * 2^-(31+shift), exact in double (mult has at most 31 significant bits).
-__device__ __forceinline__ double make_scale(int mult, int shift)
-{
-    return __builtin_ldexp((double)mult, -(31 + shift));
-}
-
-// Returns clamp(q, lo, hi) + kQBias where q = floor(s*scale + 1/2) is the exact rounded
-// quotient; lo_b = lo + kQBias, hi_b = hi + kQBias.
-// Why it is exact: (double)s and scale are exact, and 256.5 is exact, so the FMA computes
-// RD(s*scale + 256.5) with a single round-down.  Round-down never crosses an integer
-// (integers of this magnitude are representable), hence floor(RD(v)) == floor(v).  The
-// conversion truncates toward zero, which equals floor for v >= 0; for v < 0 it yields a
-// value <= 0 < lo_b, and the true floor is also below lo_b, so both clamp to lo_b.  Values
-// beyond int32 saturate in the conversion and clamp to hi_b or lo_b likewise.
-__device__ __forceinline__ int requant_to_biased(int s, double scale, int lo_b, int hi_b)
-{
-    const double v = __builtin_fma((double)s, scale, 256.5);
-    const int qe = (int)v;
-    return clamp_i32(qe, lo_b, hi_b);
 }
 
 // ---- integer requantisation ------------------------------------------------------------------
@@ -108,6 +75,16 @@ __device__ __forceinline__ int requant_prelu_i64(int accv, const v4i &pr, int lo
     return requant_prelu_s(accv + pr[0], pr[1], pr[2], pr[3], lo, hi);
 }
 
+// The definition itself for one value, with s = acc + bias already formed and the multiplier already
+// chosen (PReLU: by the sign of s): q = floor((s*m + 2^(30+shift)) / 2^(31+shift)), clamp.  An
+// arithmetic right shift of a 64-bit integer is a floor division; |s*m| < 2^62 and the rounding
+// constant is at most 2^61.  Used by the one-thread-per-output kernels.
+__device__ __forceinline__ int requant_s_i64(int s, int m, int shift, int lo, int hi)
+{
+    const long long t = (long long)s * (long long)m + (1LL << (30 + shift));
+    return clamp_i32((int)(t >> (31 + shift)), lo, hi);
+}
+
 // Epilogue forms: 0 = every shift of the wavefront's channels >= 1 (pr.w holds shift-1),
 // 1 = any shift, 2 = PReLU.
 template <int MODE>
@@ -117,6 +94,19 @@ __device__ __forceinline__ int requant_mode(int accv, const v4i &pr, int lo, int
         return requant_prelu_i64(accv, pr, lo, hi);
     else
         return requant_i64<MODE == 1>(accv, pr, lo, hi);
+}
+
+// 16-byte buffer store, offset in the vector operand, with its data registers protected in the
+// source.  On gfx950 a buffer store of more than 8 bytes picked up, now and then, the NEW contents
+// of its data registers when the instruction right behind it overwrote them (seen with a scalar
+// offset register, the one form for which the compiler inserts no wait state).  The empty
+// statement behind the store reads the four data registers, so no instruction that overwrites them
+// can be scheduled before it, and its two wait states are what the store needs -- whatever form of
+// offset a later compiler picks.
+__device__ __forceinline__ void store_b128_guarded(const v4i v, __amdgpu_buffer_rsrc_t rsrc, int voffset)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, voffset, 0, 0);
+    asm volatile("s_nop 1" : : "v"(v));
 }
 
 // Low bytes of four ints -> one dword (a in bits 0..7).

@@ -36,7 +36,7 @@ struct DwArgs {
     int N, H, W, C, Ho, Wo, stride;
     int strips;      // row strips per image
     int strip_rows;  // output rows per strip
-    int lo_b, hi_b;
+    int lo, hi;
     long long total;  // threads with work
 };
 
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
     long long Cq[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) Cq[q] = (long long)pb[q] * pm[q] + (1LL << (30 + ps[q]));
-    const int lo = in_vgpr(a.lo_b - kQBias), hi = in_vgpr(a.hi_b - kQBias);
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
 
     int acc[ROWS][4];  // [output row][channel]
     if constexpr (S == 1) {
@@ -208,7 +208,6 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
 // Any C and alignment: one thread per output element.
 __global__ __launch_bounds__(256) void dw_kernel_generic(const DwArgs a)
 {
-    set_f64_round_down();
     const long long tid = (long long)blockIdx.x * 256 + threadIdx.x;
     if (tid >= a.total) return;
     const int c = (int)(tid % a.C);
@@ -229,8 +228,7 @@ __global__ __launch_bounds__(256) void dw_kernel_generic(const DwArgs a)
         }
     }
     const int m = (a.mult_neg && acc < 0) ? a.mult_neg[c] : a.mult[c];
-    const int v = requant_to_biased(acc, make_scale(m, a.shift[c]), a.lo_b, a.hi_b);
-    a.y[tid] = (int8_t)(v - kQBias);
+    a.y[tid] = (int8_t)requant_s_i64(acc, m, a.shift[c], a.lo, a.hi);
 }
 
 static bool overlaps(const void *p, size_t pn, const void *q, size_t qn)
@@ -240,6 +238,20 @@ static bool overlaps(const void *p, size_t pn, const void *q, size_t qn)
 }
 
 }  // namespace prom
+
+// The limits of prom_dw_conv that depend on the shape alone (the vector kernel's grid is
+// (columns x channels, strips of rows, images); the one-thread-per-output kernel has a 1-D grid).
+int prom::dw_shape_check(int n, int h, int w, int c, int stride)
+{
+    if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || (stride != 1 && stride != 2)) return PROM_EINVAL;
+    const int ho = (h - 1) / stride + 1, wo = (w - 1) / stride + 1;
+    const size_t xbytes = (size_t)n * h * w * c, ybytes = (size_t)n * ho * wo * c;
+    if (xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
+    if (n > 65535 || (ho + 3) / 4 > 65535) return PROM_EUNSUPPORTED;  // (either kernel may be taken)
+    if (((long long)wo * (c / 4) + 255) / 256 > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
+    if (((long long)ybytes + 255) / 256 > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
+    return PROM_OK;
+}
 
 extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const int8_t *w_dw, int stride,
                             const prom_requant_t *rq, int8_t *y, void *stream)
@@ -253,8 +265,8 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
     a.N = n; a.H = h; a.W = w; a.C = c; a.stride = stride;
     a.Ho = (h - 1) / stride + 1;
     a.Wo = (w - 1) / stride + 1;
-    a.lo_b = rq->act_min + kQBias;
-    a.hi_b = rq->act_max + kQBias;
+    a.lo = rq->act_min;
+    a.hi = rq->act_max;
     const size_t xbytes = (size_t)n * h * w * c, ybytes = (size_t)n * a.Ho * a.Wo * c;
     if (xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
     if (overlaps(y, ybytes, x, xbytes) || overlaps(y, ybytes, w_dw, (size_t)9 * c)) return PROM_EALIAS;

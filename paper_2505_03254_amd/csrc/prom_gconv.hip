@@ -374,8 +374,7 @@ __global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, c
                     }
                     // the lane's channels cl .. cl+15 of its pixel (C % 4 == 0: whole dwords are in or out)
                     if (valid[p] && cl + 16 <= C) {
-                        __builtin_amdgcn_raw_buffer_store_b128(v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]},
-                                                               ry, yo[p], 0, 0);
+                        store_b128_guarded(v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]}, ry, yo[p]);
                     } else if (valid[p]) {
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
@@ -395,7 +394,6 @@ __global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, c
 // Any C, group size and alignment: one thread per output element.
 __global__ __launch_bounds__(256) void gconv_kernel_generic(const GconvArgs a)
 {
-    set_f64_round_down();
     const long long tid = (long long)blockIdx.x * 256 + threadIdx.x;
     if (tid >= a.total) return;
     const int c = (int)(tid % a.C);
@@ -418,8 +416,7 @@ __global__ __launch_bounds__(256) void gconv_kernel_generic(const GconvArgs a)
         }
     }
     const int m = (a.mult_neg && acc < 0) ? a.mult_neg[c] : a.mult[c];
-    const int v = requant_to_biased(acc, make_scale(m, a.shift[c]), a.lo + kQBias, a.hi + kQBias);
-    a.y[tid] = (int8_t)(v - kQBias);
+    a.y[tid] = (int8_t)requant_s_i64(acc, m, a.shift[c], a.lo, a.hi);
 }
 
 using GconvFn = void (*)(const GconvArgs);

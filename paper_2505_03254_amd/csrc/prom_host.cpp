@@ -4,6 +4,7 @@
 #include "prom_launch.h"
 
 #include <cstring>
+#include <vector>
 
 namespace {
 inline int words_per_row(int cin) { return (cin + 15) / 16; }
@@ -107,6 +108,32 @@ hipError_t &prom::last_hip_error()
 {
     static thread_local hipError_t e = hipSuccess;
     return e;
+}
+
+extern "C" int prom_requant_check(const prom_requant_t *rq, int channels, int cin, int *bad_channel)
+{
+    if (bad_channel) *bad_channel = -1;
+    if (!rq || !rq->bias || !rq->mult || !rq->shift || channels <= 0 || cin < 0) return PROM_EINVAL;
+    if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
+    std::vector<int32_t> b(channels), m(channels), sh(channels);
+    const size_t nbytes = (size_t)channels * sizeof(int32_t);
+    // hipMemcpy from device memory waits for the work already enqueued on the device
+    if (hipMemcpy(b.data(), rq->bias, nbytes, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(m.data(), rq->mult, nbytes, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(sh.data(), rq->shift, nbytes, hipMemcpyDeviceToHost) != hipSuccess) {
+        prom::last_hip_error() = hipGetLastError();
+        return PROM_EHIP;
+    }
+    const long long acc_max = 128LL * cin;  // |x| <= 128 and, in a pointwise layer, |w| <= 1
+    for (int c = 0; c < channels; ++c) {
+        const long long ab = b[c] < 0 ? -(long long)b[c] : (long long)b[c];
+        const bool ok = m[c] > 0 && sh[c] >= 0 && sh[c] <= 31 && ab < (1LL << 29) && acc_max + ab < (1LL << 30);
+        if (!ok) {
+            if (bad_channel) *bad_channel = c;
+            return PROM_EINVAL;
+        }
+    }
+    return PROM_OK;
 }
 
 extern "C" const char *prom_last_hip_error(void)

@@ -19,4 +19,10 @@ inline int check_launch()
     return PROM_EHIP;
 }
 
+// Shape checks of the single-layer entry points without pointers (PROM_OK, PROM_EINVAL or
+// PROM_EUNSUPPORTED), for entry points that chain several layers and must refuse before their
+// first launch what a later layer would refuse.
+int pw_shape_check(int n, int h, int w, int cin, int cout);
+int dw_shape_check(int n, int h, int w, int c, int stride);
+
 }  // namespace prom

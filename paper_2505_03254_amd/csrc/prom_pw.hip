@@ -635,7 +635,15 @@ static bool conflicts(const PwArgs &a, const PwArgs &b)
     // not something the single-layer entry point allows either, but stay safe
     const Range wa{(uintptr_t)a.wq, (uintptr_t)a.wq + (size_t)a.Nc * a.KW * 4};
     const Range wb{(uintptr_t)b.wq, (uintptr_t)b.wq + (size_t)b.Nc * b.KW * 4};
-    return hits(ya, wb) || hits(yb, wa);
+    if (hits(ya, wb) || hits(yb, wa)) return true;
+    // ... nor into another's requantisation parameters
+    auto writes_params = [](const Range &y, const PwArgs &p) {
+        const int32_t *arrs[4] = {p.bias, p.mult, p.shift, p.mult_neg};
+        for (const int32_t *q : arrs)
+            if (q && hits(y, Range{(uintptr_t)q, (uintptr_t)q + (size_t)p.Nc * 4})) return true;
+        return false;
+    };
+    return writes_params(ya, b) || writes_params(yb, a);
 }
 
 // Sub-chunks (64 output channels) per part if the layer is one for pw_expand_body, else 0:
@@ -890,6 +898,12 @@ extern "C" int prom_debug_timeline(unsigned long long *t_host, int *member_host,
     return PROM_OK;
 }
 #endif
+
+int prom::pw_shape_check(int n, int h, int w, int cin, int cout)
+{
+    PwLaunch L;
+    return pw_prepare(nullptr, n, h, w, cin, nullptr, cout, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true, L);
+}
 
 extern "C" int prom_pw_batchable(int n, int h, int w, int cin, int cout)
 {

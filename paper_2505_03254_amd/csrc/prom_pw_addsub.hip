@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void pw_addsub_kernel(const AddSubArgs a)
                 }
                 const v4i v = *reinterpret_cast<const v4i *>(stage + 16 * q);
                 // tile offset in the vector offset: see the note at the store of the streaming kernel
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, go + tile_off, 0, 0);
+                store_b128_guarded(v, ry, go + tile_off);
             }
         } else {
             for (int q = lane; q < 16 * RW; q += 64) {  // dword pieces

@@ -178,7 +178,7 @@ __device__ __forceinline__ void pw_expand_body(const PwArgs &a, const int lid, u
                 const v4i v = *reinterpret_cast<const v4i *>(stage + (lane >> 2) * 64 + 16 * ((lane & 3) ^ (lane >> 4)));
                 const unsigned tile_off = ytile + (unsigned)((16 * gi) * Nc + sc * 64);
                 // offset in the vector operand (see the streaming kernel's store)
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(goff + tile_off, (unsigned)kOobOffset), 0, 0);
+                store_b128_guarded(v, ry, (int)min(goff + tile_off, (unsigned)kOobOffset));
             }
         };
         for (int u = 0; u < my_units; ++u) {
@@ -337,7 +337,7 @@ __device__ __forceinline__ void pw_expand_rows_body(const PwArgs &a, const int l
             // the unit's 16*G*Nc bytes, in 16-byte pieces in memory order
             for (int p = lane; p < unit_bytes / 16; p += 64) {
                 const v4i v = *reinterpret_cast<const v4i *>(stage + 16 * p);
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(yunit + 16u * p, (unsigned)kOobOffset), 0, 0);
+                store_b128_guarded(v, ry, (int)min(yunit + 16u * p, (unsigned)kOobOffset));
             }
             xoff = min(xoff + xstep, (unsigned)kOobOffset);
             yunit = min(yunit + ystep, (unsigned)kOobOffset);

@@ -171,11 +171,13 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
             xoff = min(xoff + xstep, (unsigned)kOobOffset);
         }
     };
+    PW_STAMP(0);
     v4i ring[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_group(ring[d]);
-
+    PW_STAMP(1);
     stage_weights_rows<NT>(a, cbase, CW, nthr, prelu, frag, lpar);
+    PW_STAMP(2);
 
     v4i par[NT][4];
     const v4i *lpg = lpar + cwi * NT * 16 + g * 4;
@@ -313,16 +315,17 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
                 for (int i = 0; i < NI; ++i) {
                     const v4i v = *reinterpret_cast<const v4i *>(tile + (i * nthr + tid) * 16);
                     // tile offset in the vector offset: see the store of the streaming kernel
-                    __builtin_amdgcn_raw_buffer_store_b128(
-                        v, ry, (int)min((unsigned)goff[i] + ytile, (unsigned)kOobOffset), 0, 0);
+                    store_b128_guarded(v, ry, (int)min((unsigned)goff[i] + ytile, (unsigned)kOobOffset));
                 }
                 buf ^= 1;
                 ytile = min(ytile + ystep, (unsigned)kOobOffset);
             }
         };
+        PW_STAMP(3);
         for (int it = 0; it < full_rounds; ++it) {
 #pragma unroll
             for (int d = 0; d < D; ++d) step(ring[d], std::true_type{});
+            if (it == 0) PW_STAMP(4);
         }
 #pragma nounroll
         for (int r = 0; r < tail_steps; ++r) {
@@ -330,6 +333,11 @@ __device__ __forceinline__ void pw_rows_body(const PwArgs &a, const int lid, uns
 #pragma unroll
             for (int d = 0; d + 1 < D; ++d) ring[d] = ring[d + 1];
         }
+        PW_STAMP(5);
+#ifdef PROM_TIMELINE
+        __builtin_amdgcn_s_waitcnt(0);
+        PW_STAMP(6);
+#endif
     };
 
     using Fast = std::integral_constant<int, 0>;

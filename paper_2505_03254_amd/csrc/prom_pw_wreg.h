@@ -242,7 +242,7 @@ __device__ __forceinline__ void pw_wreg_body(const PwArgs &a, const int lid, uns
             for (int r = 0; r < SR; ++r) {
                 const v4i v = *reinterpret_cast<const v4i *>(outt + buf * (16 * GW) + so_lds[r]);
                 // offset in the vector operand (see the streaming kernel's store)
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, (int)min(so_g[r] + ytile, (unsigned)kOobOffset), 0, 0);
+                store_b128_guarded(v, ry, (int)min(so_g[r] + ytile, (unsigned)kOobOffset));
             }
             ytile = min(ytile + ystep, (unsigned)kOobOffset);
             ++s;

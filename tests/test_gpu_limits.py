@@ -83,3 +83,27 @@ def test_gconv_at_and_beyond_2_gib(P, n, mfma):
     for i in (0, 1, n // 2, n - 2, n - 1):
         want = oracle.gconv3x3(x[i:i + 1].cpu().numpy(), G.weight, 1, G.bias, G.mult, G.shift, -128, 127)
         assert_same(y[i:i + 1].cpu().numpy(), want, f"image {i} of {n}")
+
+
+def test_requant_check_reports_the_first_bad_channel(P):
+    """prom_requant_check copies the parameter arrays back and checks the documented preconditions:
+    mult in (0, 2^31), shift in [0, 31], |bias| < 2^29, 128 * cin + |bias| < 2^30."""
+    import torch
+    from workloads import make_pw_layer
+    from gpu_util import dev
+    L = make_pw_layer(9900, 1, 2, 2, 64, 48)
+    good = P.Requant(dev(L.bias), dev(L.mult), dev(L.shift), 0, 127)
+    assert P.prom_requant_check(good, 64) == -1
+    for what, arr, ch, val in (("mult", "mult", 5, 0), ("mult", "mult", 7, -3), ("shift", "shift", 11, 32),
+                               ("shift", "shift", 2, -1), ("bias", "bias", 40, 1 << 29), ("bias", "bias", 41, -(1 << 29))):
+        a = {"bias": L.bias.copy(), "mult": L.mult.copy(), "shift": L.shift.copy()}
+        a[arr][ch] = val
+        rq = P.Requant(dev(a["bias"]), dev(a["mult"]), dev(a["shift"]), 0, 127)
+        assert P.prom_requant_check(rq, 64) == ch, (what, val)
+    # the accumulator bound: a bias just below 2^29 is fine for few input channels, not for 2^22 of them
+    b = L.bias.copy()
+    b[3] = (1 << 29) - 1
+    rq = P.Requant(dev(b), dev(L.mult), dev(L.shift), 0, 127)
+    assert P.prom_requant_check(rq, 64) == -1
+    assert P.prom_requant_check(rq, 1 << 22) == 0  # 128 * 2^22 + |bias| >= 2^30 already for channel 0
+    torch.cuda.synchronize()
