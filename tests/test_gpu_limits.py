@@ -105,5 +105,5 @@ def test_requant_check_reports_the_first_bad_channel(P):
     b[3] = (1 << 29) - 1
     rq = P.Requant(dev(b), dev(L.mult), dev(L.shift), 0, 127)
     assert P.prom_requant_check(rq, 64) == -1
-    assert P.prom_requant_check(rq, 1 << 22) == 0  # 128 * 2^22 + |bias| >= 2^30 already for channel 0
+    assert P.prom_requant_check(rq, (1 << 22) + 1) == 3  # 128 * (2^22 + 1) + 2^29 - 1 >= 2^30
     torch.cuda.synchronize()
