@@ -1,9 +1,7 @@
 // Host side of the ternary pointwise convolution (argument checks, launch planning, the
 // C entry points) and the generic any-shape kernel.  The streaming kernel lives in
 // prom_pw_stream.h and is instantiated per NT in prom_pw_inst.hip.
-#include "prom_pw_rows.h"
-#include "prom_pw_expand.h"
-#include "prom_pw_wreg.h"
+#include "prom_pw_batch.h"
 #include "prom_launch.h"
 
 #include <mutex>
@@ -93,92 +91,6 @@ __global__ __launch_bounds__(256) void pw_generic_kernel(const PwArgs a)
     }
 }
 
-// ============================================================================================
-// Several independent layers in one launch: workgroups [start[i], start[i+1]) (both multiples
-// of 8) run layer i with the plan NT = 4, PT = 1 and 16-byte activation loads.  The launch,
-// prologue and write-back latencies of one layer overlap with the streaming of the others.
-constexpr int kBatchNT = 4;
-#ifndef PROM_BATCH_DEPTH
-#define PROM_BATCH_DEPTH 4
-#endif
-constexpr int kBatchDepth = PROM_BATCH_DEPTH;  // activation load groups in flight per wavefront
-// Tiles per wavefront of a batch member: kBatchNT, or half of it for a layer with many k
-// steps, whose decoded fragments would otherwise set the LDS size (and with it the number of
-// resident workgroups) of the whole launch.
-constexpr int kBatchNTDeep = 3;
-constexpr int kBatchDeepKS = 10;
-// The narrower body also takes the PReLU layers whose last chunk is ragged: the PReLU epilogue
-// with per-lane channel conditions at 4 tiles is the one combination above 168 registers, which
-// would cost every member of the launch its third wavefront per SIMD.
-__host__ __device__ constexpr int batch_nt(int ks, bool prelu_ragged)
-{
-    return ks >= kBatchDeepKS || prelu_ragged ? kBatchNTDeep : kBatchNT;
-}
-__host__ __device__ inline int batch_nt(const PwArgs &a)
-{
-    return batch_nt(a.KS, a.mult_neg != nullptr && a.Nc % (16 * kBatchNT) != 0);
-}
-// Pixel tiles per unit of pw_expand_body by number of k steps (registers: 4 per tile and k step).
-constexpr int kExpandG1 = 4, kExpandG2 = 3, kExpandG3 = 2, kExpandG5 = 1;
-__host__ __device__ constexpr int expand_g(int ks)
-{
-    return ks == 1 ? kExpandG1 : ks == 2 ? kExpandG2 : ks == 3 ? kExpandG3 : kExpandG5;
-}
-constexpr int kExpandLds = 52 * 1024;  // three workgroups per CU
-constexpr int kExpandRowsG1 = 2;       // pixel tiles per unit of the full-row form (one k step)
-
-// One member's work with the epilogue kind E (plain or PReLU) fixed at compile time.
-template <int E>
-__device__ __forceinline__ void pw_batch_member(const PwArgs &a, const int lid, unsigned char *lds_raw)
-{
-    // FULLW bodies (every chunk 16*NT channels wide) have no per-lane conditions in the epilogue;
-    // with one k step there is no branch around the epilogue either, so the waits on the prefetch
-    // ring are exact (a store in a conditional epilogue makes them conservative)
-    if (batch_nt(a) == kBatchNTDeep) {
-        if (a.Nc % (16 * kBatchNTDeep) == 0)
-            pw_stream_body<kBatchNTDeep, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
-        else
-            pw_stream_body<kBatchNTDeep, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
-    } else if (a.Nc % (16 * kBatchNT) == 0) {
-        if (a.KS == 1)
-            pw_stream_body<kBatchNT, 1, 16, true, true, kBatchDepth, E>(a, lid, lds_raw);
-        else
-            pw_stream_body<kBatchNT, 1, 16, false, true, kBatchDepth, E>(a, lid, lds_raw);
-    } else {
-        if constexpr (E == kEpiPlain)  // (a PReLU layer with a ragged last chunk has the narrow body)
-            pw_stream_body<kBatchNT, 1, 16, false, false, kBatchDepth, E>(a, lid, lds_raw);
-    }
-}
-
-template <bool PRELU>
-__device__ __forceinline__ void pw_expand_member(const PwArgs &a, const int lid, unsigned char *lds_raw)
-{
-    if (a.KS == 1)
-        pw_expand_body<1, kExpandG1, PRELU>(a, lid, lds_raw);
-    else if (a.KS == 2)
-        pw_expand_body<2, kExpandG2, PRELU>(a, lid, lds_raw);
-    else if (a.KS == 3)
-        pw_expand_body<3, kExpandG3, PRELU>(a, lid, lds_raw);
-    else
-        pw_expand_body<5, kExpandG5, PRELU>(a, lid, lds_raw);
-}
-
-// Bodies of pw_wreg_body (weights in registers) a batch member can be planned for: body id ->
-// (k steps, tiles per wavefront, pixel tiles fetched ahead).
-enum { kWreg6x1 = 1, kWreg6x2 = 2, kWreg9x2 = 3, kWreg9x3 = 4, kWreg15x3 = 5 };
-
-template <int E>
-__device__ __forceinline__ void pw_wreg_member(int body, const PwArgs &a, const int lid, unsigned char *lds_raw)
-{
-    switch (body) {
-    case kWreg6x1: pw_wreg_body<6, 1, 3, true, E>(a, lid, lds_raw); break;
-    case kWreg6x2: pw_wreg_body<6, 2, 3, true, E>(a, lid, lds_raw); break;
-    case kWreg9x2: pw_wreg_body<9, 2, 2, false, E>(a, lid, lds_raw); break;
-    case kWreg9x3: pw_wreg_body<9, 3, 2, false, E>(a, lid, lds_raw); break;
-    default: pw_wreg_body<15, 3, 1, false, E>(a, lid, lds_raw); break;
-    }
-}
-
 // EPI: kEpiPlain if no member is a PReLU layer, else kEpiBoth.  A launch of both kinds runs each
 // member through a copy of the bodies compiled for its kind alone (a body that carries both
 // epilogues needs more registers than either).
@@ -229,30 +141,13 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
 #ifdef PROM_TIMELINE
     TimelineScope timeline_scope(bid, i);
 #endif
-    // a.cw <= -10: the host planned the layer for the body that keeps the weights in registers
-    if (a.cw <= -10) {  // (never a PReLU layer: the host plans those for the other bodies)
-        pw_wreg_member<kEpiPlain>(-10 - a.cw, a, lid, lds_raw);
-        return;
-    }
-    // a.cw != 0: the host planned the layer for the body that keeps the activations of a pixel
-    // group in registers while it walks over the output channels (a.cw < 0: its full-row form)
     if constexpr (EPI != kEpiPlain) {
         if (a.mult_neg) {
-            if (a.cw < 0)
-                pw_expand_rows_body<kExpandRowsG1, 4, 16, true>(a, lid, lds_raw);
-            else if (a.cw)
-                pw_expand_member<true>(a, lid, lds_raw);
-            else
-                pw_batch_member<kEpiPrelu>(a, lid, lds_raw);
+            pw_small_member<kEpiPrelu>(a, lid, lds_raw);
             return;
         }
     }
-    if (a.cw < 0)
-        pw_expand_rows_body<kExpandRowsG1, 4, 16, false>(a, lid, lds_raw);
-    else if (a.cw)
-        pw_expand_member<false>(a, lid, lds_raw);
-    else
-        pw_batch_member<kEpiPlain>(a, lid, lds_raw);
+    pw_small_member<kEpiPlain>(a, lid, lds_raw);
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst,
@@ -683,9 +578,95 @@ static bool wreg_plan(const PwArgs &m, WregPlan *p)
     return true;
 }
 
+// A member of the launch of small layers, re-planned for the bodies of pw_small_member: PT = 1,
+// plain streaming (measured: the row-cooperative form gains nothing inside a shared launch, where
+// fixed costs per workgroup and the balance between layers decide), or one of the bodies for
+// expansion layers and deep projections.
+struct SmallPlan {
+    PwArgs a;
+    size_t lds;
+    long long work;        // bytes one chunk (part, group) moves
+    long long unit_bytes;  // bytes of one unit of a body with large units, else 0
+    int la;                // weights-in-registers body: steps per round of its prefetch ring, else 0
+};
+
+static void plan_small_shape(const PwLaunch &m, SmallPlan &sp)
+{
+    PwArgs &a = sp.a;
+    a = m.a;
+    a.cw = 0;
+    sp.unit_bytes = 0;
+    sp.la = 0;
+    const int n_tiles = (a.Nc + 15) / 16;
+    const int nt = batch_nt(a);
+    int parts = 0;
+    const int nsc = expand_plan(a, &parts);
+    const bool full_rows = nsc && parts == 1 && a.KS == 1 &&
+                           lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc) <= (size_t)kExpandLds;
+    WregPlan wp;
+    if (wreg_plan(a, &wp)) {
+        // weights in registers: a workgroup belongs to one group of 64*ntw channels and walks
+        // over 16-pixel tiles, all four wavefronts on the same tile
+        a.cw = -10 - wp.body;
+        a.n_chunks = wp.groups;
+        a.units = (a.M + 15) / 16;
+        const int gw = 64 * wp.ntw < a.Nc ? 64 * wp.ntw : a.Nc;
+        sp.work = (long long)a.M * (a.K + gw);
+        sp.lds = lds_bytes_wreg(a.K, wp.ntw);
+        sp.la = wp.la;
+    } else if (full_rows) {
+        // all output channels in one part and a unit's rows small enough for LDS: whole rows
+        a.cw = -1;
+        a.n_chunks = 1;
+        a.units = (a.M + 16 * kExpandRowsG1 - 1) / (16 * kExpandRowsG1);
+        sp.work = (long long)a.M * (a.K + a.Nc);
+        sp.lds = lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc);
+        sp.unit_bytes = 16LL * kExpandRowsG1 * (a.K + a.Nc);
+    } else if (nsc) {
+        a.cw = nsc;
+        a.n_chunks = parts;
+        a.units = (a.M + 16 * expand_g(a.KS) - 1) / (16 * expand_g(a.KS));
+        sp.work = (long long)a.M * (a.K + 64 * nsc);
+        sp.lds = lds_bytes_expand(nsc, a.KS);
+        sp.unit_bytes = 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
+    } else {
+        a.n_chunks = (n_tiles + nt - 1) / nt;
+        a.units = (a.M + 15) / 16;
+        sp.work = (long long)a.M * (a.K + 16 * nt);
+        sp.lds = lds_bytes_fast(nt, a.KS);
+    }
+}
+
+// Workgroups of a planned member that move about per_wg bytes each; returns its workgroups in the
+// launch (a multiple of 8).
+static int size_small_member(SmallPlan &sp, long long per_wg)
+{
+    PwArgs &a = sp.a;
+    const bool wreg = a.cw <= -10;
+    const long long wg_units = wreg ? a.units : (a.units + 3) / 4;
+    long long wgs = (sp.work + per_wg - 1) / per_wg;
+    if (wreg) {
+        // whole rounds of the prefetch ring: every workgroup the same number of steps
+        long long tiles_per_wg = (a.units + wgs - 1) / wgs;
+        tiles_per_wg = (tiles_per_wg + sp.la - 1) / sp.la * sp.la;
+        wgs = (a.units + tiles_per_wg - 1) / tiles_per_wg;
+    } else if (sp.unit_bytes) {
+        // units are large here (16*G pixels x all channels of the part): give every wavefront
+        // the same whole number of them
+        long long upw = (per_wg + 2 * sp.unit_bytes) / (4 * sp.unit_bytes);
+        if (upw < 1) upw = 1;
+        wgs = (a.units + 4 * upw - 1) / (4 * upw);
+    }
+    if (wgs < 1) wgs = 1;
+    if (wgs > wg_units) wgs = wg_units;
+    a.wg_per_chunk = (int)wgs;
+    return (int)((wgs * a.n_chunks + 7) / 8 * 8);
+}
+
 static int launch_batch(const PwLaunch *const *members, int count, hipStream_t st)
 {
     static thread_local PwBatchArgs b;
+    static thread_local SmallPlan plans[kMaxBatch];
     b.count = count;
     size_t lds = 0;
     int start = 0;
@@ -695,89 +676,20 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     // that the chip drains evenly at the end of the launch.
     long long total_work = 0, done_work = 0;
     for (int i = 0; i < count; ++i) {
-        const PwArgs &m = members[i]->a;
-        const int nt = batch_nt(m);
-        int parts = 0;
-        const int nsc = expand_plan(m, &parts);
-        WregPlan wp;
-        if (wreg_plan(m, &wp))
-            total_work += (long long)m.M * ((long long)m.K * wp.groups + m.Nc);
-        else if (nsc)
-            total_work += (long long)m.M * ((long long)m.K * parts + m.Nc);
-        else
-            total_work += (long long)m.M * (m.K + 16 * nt) * (((m.Nc + 15) / 16 + nt - 1) / nt);
+        plan_small_shape(*members[i], plans[i]);
+        total_work += plans[i].work * plans[i].a.n_chunks;
     }
     for (int i = 0; i < count; ++i) {
-        // re-planned for the batch body: PT = 1, plain streaming (measured: the row-cooperative
-        // form gains nothing inside a batch, where fixed costs per workgroup and the balance
-        // between layers decide)
-        PwArgs a = members[i]->a;
-        a.cw = 0;
-        const int n_tiles = (a.Nc + 15) / 16;
-        const int nt = batch_nt(a);
-        int parts = 0;
-        const int nsc = expand_plan(a, &parts);
-        long long work;  // bytes one chunk (or part) moves
-        size_t l;
-        const bool full_rows = nsc && parts == 1 && a.KS == 1 &&
-                               lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc) <= (size_t)kExpandLds;
-        WregPlan wp;
-        const bool wreg = wreg_plan(a, &wp);
-        if (wreg) {
-            a.cw = -10 - wp.body;
-            // weights in registers: a workgroup belongs to one group of 64*ntw channels and walks
-            // over 16-pixel tiles, all four wavefronts on the same tile
-            a.n_chunks = wp.groups;
-            a.units = (a.M + 15) / 16;
-            const int gw = 64 * wp.ntw < a.Nc ? 64 * wp.ntw : a.Nc;
-            work = (long long)a.M * (a.K + gw);
-            l = lds_bytes_wreg(a.K, wp.ntw);
-        } else if (full_rows) {
-            // all output channels in one part and a unit's rows small enough for LDS: whole rows
-            a.cw = -1;
-            a.n_chunks = 1;
-            a.units = (a.M + 16 * kExpandRowsG1 - 1) / (16 * kExpandRowsG1);
-            work = (long long)a.M * (a.K + a.Nc);
-            l = lds_bytes_expand_rows(nsc, 4, kExpandRowsG1, a.Nc);
-        } else if (nsc) {
-            a.cw = nsc;
-            a.n_chunks = parts;
-            a.units = (a.M + 16 * expand_g(a.KS) - 1) / (16 * expand_g(a.KS));
-            work = (long long)a.M * (a.K + 64 * nsc);
-            l = lds_bytes_expand(nsc, a.KS);
-        } else {
-            a.n_chunks = (n_tiles + nt - 1) / nt;
-            a.units = (a.M + 15) / 16;
-            work = (long long)a.M * (a.K + 16 * nt);
-            l = lds_bytes_fast(nt, a.KS);
-        }
-        const long long wg_units = wreg ? a.units : (a.units + 3) / 4;
+        SmallPlan &sp = plans[i];
         const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
                                  : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
                                                                    : kBatchBytesPerWg / 4;
-        done_work += work * a.n_chunks;
-        long long wgs = (work + per_wg - 1) / per_wg;
-        if (wreg) {
-            // whole rounds of the prefetch ring: every workgroup the same number of steps
-            long long tiles_per_wg = (a.units + wgs - 1) / wgs;
-            tiles_per_wg = (tiles_per_wg + wp.la - 1) / wp.la * wp.la;
-            wgs = (a.units + tiles_per_wg - 1) / tiles_per_wg;
-        } else if (nsc) {
-            // units are large here (16*G pixels x all channels of the part): give every wavefront
-            // the same whole number of them
-            const long long unit_bytes = full_rows ? 16LL * kExpandRowsG1 * (a.K + a.Nc) : 16LL * expand_g(a.KS) * (a.K + 64 * nsc);
-            long long upw = (per_wg + 2 * unit_bytes) / (4 * unit_bytes);
-            if (upw < 1) upw = 1;
-            wgs = (a.units + 4 * upw - 1) / (4 * upw);
-        }
-        if (wgs < 1) wgs = 1;
-        if (wgs > wg_units) wgs = wg_units;
-        a.wg_per_chunk = (int)wgs;
-        const int nblk = (int)((wgs * a.n_chunks + 7) / 8 * 8);
-        b.layer[i] = a;
+        done_work += sp.work * sp.a.n_chunks;
+        const int nblk = size_small_member(sp, per_wg);
+        b.layer[i] = sp.a;
         b.start[i] = start;
         start += nblk;
-        if (l > lds) lds = l;
+        if (sp.lds > lds) lds = sp.lds;
     }
     b.start[count] = start;
     bool any_prelu = false;

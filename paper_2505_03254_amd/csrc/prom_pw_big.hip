@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b
     int i = 0;
     while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
     const int lid = logical_block_id(bid - b.start[i], b.start[i + 1] - b.start[i]);
-    const PwArgs &a = b.layer[i];
+    const PwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
     if constexpr (EPI != kEpiPlain) {
         if (a.mult_neg) {
             pw_big_member<kEpiPrelu>(b.body[i], a, lid, lds_raw);
