@@ -53,6 +53,18 @@ def measured_traffic(name):
     return None
 
 
+def settle(torch, launch, ms=20.0):
+    """Untimed launches for `ms` before a measurement: the step time of an idle GPU settles only
+    after some tens of milliseconds of load (see the preconditioning of the timed region)."""
+    t0 = time.perf_counter()
+    k = 0
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(20):
+            launch(k)
+            k += 1
+        torch.cuda.synchronize()
+
+
 def layer_bytes(m, k, nc, residual=False):
     """Algorithmic HBM bytes of one layer: activations in + out (+ residual), 2-bit weights,
     12 bytes of requantisation parameters per output channel."""
@@ -250,7 +262,8 @@ def main():
     # back-to-back launches after 10 warm-ups, median of 5 repeats; cache-cold: the launches rotate
     # over enough input/output sets that more than 512 MB are touched between two uses of a set
     # (the Infinity Cache holds 256 MB).  "hot" is the same on one set (cache-assisted, not a
-    # roofline figure). --------------------------------------------------------------------------
+    # roofline figure).  20 ms of untimed launches of the layer come before its warm-ups, so that
+    # every row is taken at the GPU's sustained rate. ----------------------------------------------
     per_layer = []
     log(f"{'layer':<13}{'HW':>4}{'Cin':>5}{'Cout':>6} {'plan(NT,PT,ld)':>15} {'cold us':>8} {'GB/s':>8} "
         f"{'%HBM':>6} {'Gop/s':>9} {'%MFMA':>6} {'bound':>6} {'%roof':>6} {'hot us':>7}")
@@ -263,6 +276,7 @@ def main():
         seqs = [P.PwSequence([(xs[k], l["wp"], s.cout, l["rq"], None, ys[k])]) for k in range(nsets)]
 
         def timed(sq_list):
+            settle(torch, lambda k: sq_list[k % len(sq_list)].run())
             for k in range(WARM):
                 sq_list[k % len(sq_list)].run()
             torch.cuda.synchronize()
@@ -401,6 +415,11 @@ def main():
     # ---- extra legs: depthwise sweep and the fused block of config 4 ---------------------------
     if not args.no_extra:
         result["extra"] = extra_legs(P, torch, dev, args.batch, log)
+        from workloads import regnetx_400mf_pointwise_layers, resnext50_32x4d_pointwise_layers
+        result["extra"]["pw_regnetx_400mf"] = family_leg(P, torch, dev, args.batch, regnetx_400mf_pointwise_layers(),
+                                                         log, "pw_regnetx_400mf")
+        result["extra"]["pw_resnext50"] = family_leg(P, torch, dev, args.batch, resnext50_32x4d_pointwise_layers(),
+                                                     log, "pw_resnext50")
         # the sweep at other batch sizes and weight zero fractions (the paper: 31 % of the ternary
         # weights are zero at initialisation, up to 55 % in a trained layer; the kernels are dense)
         for key, b_, z_ in (("sweep_batch32", 32, 0.5), ("sweep_batch256", 256, 0.5),
@@ -479,7 +498,7 @@ def quick_sweep(P, torch, dev, batch, zero_fraction, steps=20):
         nbytes += layer_bytes(m, s.cin, s.cout)
         ops += 2 * m * s.cin * s.cout
     seq = P.PwSequence(seq_layers)
-    for _ in range(3):
+    for _ in range(60):  # (to the sustained rate, as the main timed region)
         seq.run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -490,6 +509,79 @@ def quick_sweep(P, torch, dev, batch, zero_fraction, steps=20):
     return {"batch": batch, "weight_zero_fraction": zero_fraction, "us": round(us, 1),
             "gops": round(ops / (us * 1e-6) / 1e9, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1),
             "frac_hbm_roofline": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def family_leg(P, torch, dev, batch, shapes, log, tag):
+    """The pointwise layers of another architecture family (RegNetX-400MF, ResNeXt-50 32x4d) at the
+    benchmark's batch: every unique shape timed by the per-layer protocol (one launch per layer,
+    100 launches after 10 warm-ups, median of 5, rotating over enough buffer sets to stay
+    cache-cold) against the roofline that binds it (HBM at 8 TB/s or the int8 matrix units at
+    5 Pop/s), and all layers of the network in one prom_pw_conv_sequence call.  Seeded weights and
+    parameters, random activations (the parity tests cover these shapes, full outputs)."""
+    from workloads import make_pw_layer
+    uniq = {}
+    for sh in shapes:
+        uniq.setdefault((sh.hw, sh.cin, sh.cout, sh.residual), []).append(sh.name)
+    rows, tensors = [], {}
+    log(f"[bench] {tag}: {len(shapes)} pointwise layers, {len(uniq)} unique shapes, batch {batch}")
+    for i, ((hw, k, n, res), names) in enumerate(uniq.items()):
+        L = make_pw_layer(SEED + 9000 + i, 1, 1, 1, k, n)
+        wp = torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev)
+        rq = P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
+                       torch.from_numpy(L.shift).to(dev), -128 if res else 0, 127)
+        m = batch * hw * hw
+        nbytes, ops = layer_bytes(m, k, n, res), 2 * m * k * n
+        nsets = min(64, int(512e6 // nbytes) + 2)
+        xs = [torch.randint(0, 128, (batch, hw, hw, k), dtype=torch.int8, device=dev) for _ in range(nsets)]
+        ys = [torch.empty((batch, hw, hw, n), dtype=torch.int8, device=dev) for _ in range(nsets)]
+        r = torch.randint(-64, 64, (batch, hw, hw, n), dtype=torch.int8, device=dev) if res else None
+        seqs = [P.PwSequence([(xs[j], wp, n, rq, r, ys[j])]) for j in range(nsets)]
+        settle(torch, lambda j: seqs[j % nsets].run())
+        for j in range(10):
+            seqs[j % nsets].run()
+        torch.cuda.synchronize()
+        reps = []
+        for _ in range(5):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for j in range(100):
+                seqs[j % nsets].run()
+            e1.record()
+            torch.cuda.synchronize()
+            reps.append(e0.elapsed_time(e1) * 1e3 / 100)
+        us = sorted(reps)[len(reps) // 2]
+        t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e3), ops / (MFMA_I8_PEAK_TOPS * 1e6)
+        rows.append({"hw": hw, "cin": k, "cout": n, "residual": res, "count": len(names), "us": round(us, 2),
+                     "bound": "hbm" if t_hbm >= t_mfma else "mfma",
+                     "frac_roofline": round(max(t_hbm, t_mfma) / us, 4),
+                     "gbs": round(nbytes / us / 1e3, 1), "tops": round(ops / us / 1e6, 1),
+                     "roofline_us": max(t_hbm, t_mfma)})
+        log(f"  {hw:>4}x{hw:<4}{k:>5} ->{n:>5} res={int(res)} x{len(names):<2} {us:8.2f} us  "
+            f"{rows[-1]['bound']:>4}-bound  {100 * rows[-1]['frac_roofline']:5.1f} % of its roofline")
+        tensors[(hw, k, n, res)] = (xs[0], wp, n, rq, r, ys[0])
+        del xs, ys, seqs
+    # the whole network's layers in one call (independent here: the library may share launches)
+    # (own outputs per layer: layers that write the same buffer are ordered, not concurrent)
+    seq_layers = []
+    for sh in shapes:
+        x, wp, n, rq, r, y = tensors[(sh.hw, sh.cin, sh.cout, sh.residual)]
+        seq_layers.append((x, wp, n, rq, r, torch.empty_like(y)))
+    seq = P.PwSequence(seq_layers)
+    settle(torch, lambda j: seq.run(), ms=40.0)
+    t0 = time.perf_counter()
+    for _ in range(20):
+        seq.run()
+    torch.cuda.synchronize()
+    seq_us = (time.perf_counter() - t0) * 1e6 / 20
+    sum_us = sum(r["us"] * r["count"] for r in rows)
+    roof_us = sum(r.pop("roofline_us") * r["count"] for r in rows)
+    log(f"[bench] {tag}: one launch per layer {sum_us:.1f} us ({100 * roof_us / sum_us:.1f} % of the per-layer "
+        f"rooflines' sum {roof_us:.1f} us); one sequence call {seq_us:.1f} us ({100 * roof_us / seq_us:.1f} %)")
+    return {"batch": batch, "layers": len(shapes), "sum_layer_us": round(sum_us, 1),
+            "roofline_us": round(roof_us, 1), "frac_roofline": round(roof_us / sum_us, 4),
+            "one_sequence_call_us": round(seq_us, 1), "one_sequence_call_frac_roofline": round(roof_us / seq_us, 4),
+            "per_shape": rows}
 
 
 def prelu_leg(P, torch, dev, layers, args, total_bytes, check, log):

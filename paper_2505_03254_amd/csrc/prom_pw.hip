@@ -373,10 +373,14 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
         a.cw = cw;
         nt = rnt;
         pt = 1;
-    } else if (fast && !(plan && (plan->tiles_per_wave || plan->pixel_tiles)) &&
+    } else if (fast && !(plan && (plan->tiles_per_wave || plan->pixel_tiles)) && a.KS == 1 &&
                ((n_tiles + nt - 1) / nt > 1 || nt >= 8)) {
         // also instead of one chunk of 8 or more tiles, whose kernel needs so many registers that
-        // only one wavefront per SIMD is resident
+        // only one wavefront per SIMD is resident.  Only for layers of one k step (expansions from
+        // at most 64 channels): with more input channels the plain kernel with wide chunks is the
+        // faster one (56x56 at batch 128: 128 -> 256 39 us against 49, 256 -> 128 33 against 65,
+        // 256 -> 256 52 against 84), since the rows a workgroup shares grow with the k steps while
+        // the write-back this form coalesces stays the same.
         int cw = 0, rnt = 0;
         if (plan_rows(cin, cout, a.KS, &cw, &rnt)) {
             L.rows = true;

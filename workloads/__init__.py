@@ -14,4 +14,7 @@ from .mobilenetv2 import (  # noqa: F401
     mobilenetv2_blocks,
     mobilenetv2_param_counts, BASELINE_CONFIGS,
 )
-from .grouped import GconvShape, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers  # noqa: F401,E402
+from .grouped import (  # noqa: F401,E402
+    GconvShape, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers,
+    regnetx_400mf_pointwise_layers, resnext50_32x4d_pointwise_layers,
+)
