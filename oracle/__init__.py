@@ -9,4 +9,4 @@ from .prom_oracle import (  # noqa: F401
     set_threads,
 )
 from .quant_oracle import (quantize_pw_absmean, quantize_dw_absmax, quantize_gconv_absmax,
-                           quantize_activation_absmax)  # noqa: F401,E402
+                           quantize_activation_absmax, pw_conv_dynamic_quant)  # noqa: F401,E402

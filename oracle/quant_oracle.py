@@ -78,3 +78,43 @@ def quantize_activation_absmax(x: np.ndarray, eps: float = 1e-5):
     scale = (np.float32(127.0) / np.maximum(amax, np.float32(eps))).astype(np.float32)
     q = np.rint((flat * scale[:, None]).astype(np.float32))
     return np.clip(q, -128, 127).astype(np.int8).reshape(x.shape), scale
+
+
+def pw_conv_dynamic_quant(x, weight, x_step, w_scale, bias=None, relu: bool = False, eps: float = 1e-5):
+    """A ternary pointwise layer followed by the paper's activation quantiser (Section 3.1:
+    Eq. 1-3 give the weight scale, Eq. 6-7 the per-image activation scale, with the factor 127 and
+    the eps clamp of the pseudocode), from integer inputs to integer outputs:
+
+        acc[m][co] = sum_k x[m][k] * weight[co][k]                    (exact integers)
+        z[m][co]   = (float(acc) * w_scale[co]) * x_step[i] + bias[co]  i = image of pixel m;
+                     each of the three operations rounded once to float32, in this order
+        z          = max(z, 0) if relu
+        amax[i]    = max over the image's pixels and channels |z|
+        scale[i]   = 127 / max(amax[i], eps)                           (one float32 division)
+        q[m][co]   = clamp(round_half_even(z * scale[i]), -128, 127)   (one float32 product)
+
+    x int8 [n][h][w][cin] with real value x * x_step[i] (x_step = amax_in / 127, the reciprocal
+    of the scale the quantiser of the previous layer returned); weight int8 [cout][cin] in
+    {-1,0,1} with real value weight * w_scale[co] (w_scale = the absmean of Eq. 1);
+    bias float32 [cout] or None (a folded normalisation shift).
+    Returns (q int8 [n][h][w][cout], amax float32 [n], scale float32 [n]).
+    Needs |acc| < 2^24 so that float(acc) is exact (cin <= 132104 for int8 activations)."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    weight = np.ascontiguousarray(weight, dtype=np.int8)
+    n, h, w, cin = x.shape
+    cout = weight.shape[0]
+    assert weight.shape == (cout, cin) and 128 * cin < (1 << 24)
+    x_step = np.asarray(x_step, dtype=np.float32).reshape(n)
+    w_scale = np.asarray(w_scale, dtype=np.float32).reshape(cout)
+    acc = x.reshape(n, h * w, cin).astype(np.int64) @ weight.T.astype(np.int64)      # [n][hw][cout]
+    t = (acc.astype(np.float32) * w_scale[None, None, :]).astype(np.float32)
+    z = (t * x_step[:, None, None]).astype(np.float32)
+    if bias is not None:
+        z = (z + np.asarray(bias, dtype=np.float32).reshape(1, 1, cout)).astype(np.float32)
+    if relu:
+        z = np.maximum(z, np.float32(0.0))
+    amax = np.max(np.abs(z).reshape(n, -1), axis=1).astype(np.float32)
+    scale = (np.float32(127.0) / np.maximum(amax, np.float32(eps))).astype(np.float32)
+    q = np.rint((z * scale[:, None, None]).astype(np.float32))
+    q = np.clip(q, -128, 127).astype(np.int8).reshape(n, h, w, cout)
+    return q, amax, scale
