@@ -850,6 +850,41 @@ def extra_legs(P, torch, dev, batch, log):
     log(f"[bench] activation quantiser {list(xa.shape)}: {da * 1e6:.1f} us, {alg / da / 1e9:.0f} GB/s algorithmic")
     del xa, qa
 
+    # The same quantiser fused into the layer that produces the activations (b3.expand of MobileNetV2,
+    # 24 -> 144 at 56x56): int8 in, int8 out with one dynamic scale per image, the float32 tensor
+    # never written.  Algorithmic bytes: the layer's input and output once.
+    from workloads import make_pw_layer
+    Lf = make_pw_layer(SEED + 8000, 1, 1, 1, 24, 144)
+    xf = torch.randint(-127, 128, (batch, 56, 56, 24), dtype=torch.int8, device=dev)
+    wpf = torch.from_numpy(P.prom_pack_ternary(Lf.weight)).to(dev)
+    gen = torch.Generator(device="cpu").manual_seed(SEED)
+    x_step = (torch.rand(batch, generator=gen) * 0.05 + 0.002).to(dev)
+    w_scale = (torch.rand(144, generator=gen) * 0.2 + 0.01).to(dev)
+    fbias = torch.randn(144, generator=gen).to(dev)
+    qf = torch.empty((batch, 56, 56, 144), dtype=torch.int8, device=dev)
+    amaxf = torch.empty(batch, dtype=torch.float32, device=dev)
+    scalef = torch.empty(batch, dtype=torch.float32, device=dev)
+
+    def fused():
+        P.prom_pw_conv_dynq(xf, wpf, 144, x_step, w_scale, fbias, True, q=qf, amax=amaxf, scale=scalef)
+    settle(torch, lambda k: fused())
+    tf0 = time.perf_counter()
+    for _ in range(20):
+        fused()
+    torch.cuda.synchronize()
+    df = (time.perf_counter() - tf0) / 20
+    algf = batch * 56 * 56 * (24 + 144)
+    out["activation_quant_fused"] = {
+        "layer": "24 -> 144 at 56x56 (b3.expand), ReLU, dynamic per-image output scale", "batch": batch,
+        "us": round(df * 1e6, 1), "algorithmic_gbs": round(algf / df / 1e9, 1),
+        "frac_hbm_roofline": round(algf / df / 1e9 / HBM_PEAK_GBS, 4),
+        "unfused_bytes_per_output": 13, "fused_bytes_per_output": round(2 * 24 / 144 + 1, 2),
+        "note": "three launches: clear, layer with maximum-only epilogue, layer with quantising epilogue; "
+                "bit-exact against the oracle in tests/test_gpu_dynq.py"}
+    log(f"[bench] layer with fused dynamic activation scale (24->144 at 56x56): {df * 1e6:.1f} us, "
+        f"{algf / df / 1e9:.0f} GB/s algorithmic ({100 * algf / df / 1e9 / HBM_PEAK_GBS:.1f} % of the HBM roofline)")
+    del xf, qf
+
     out["block_chain_batch8"] = {"us": round(dt8 * 1e6, 1), "us_as_hip_graph": round(dt8_graph * 1e6, 1),
                                  "fused_blocks": fused8}
     log(f"[bench] 17-block chain at batch 8: {dt8 * 1e6:.1f} us per pass, {dt8_graph * 1e6:.1f} us replayed from a "

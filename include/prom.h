@@ -169,6 +169,27 @@ int prom_quantize_gconv_absmax(const float *w, int c, int group_size, float eps,
 int prom_quantize_activation_absmax(const float *x, int n, long long per_image, float eps, int8_t *q,
                                     float *scale, void *stream);
 
+/* Ternary pointwise layer whose int8 output takes the dynamic per-image activation scale of the
+ * paper (Section 3.1: the layer's real-valued output is the integer accumulator times the weight
+ * scale of Eq. 1 and the input's activation step; Eq. 6-7 with the factor 127 and the eps clamp of
+ * the pseudocode quantise it with one absmax scale per batch element), fused: the real-valued
+ * tensor is never written.  With i the image of pixel m:
+ *   z[m][co]  = (float(acc[m][co]) * w_scale[co]) * x_step[i] + bias[co]   three float32 operations,
+ *               each rounded once, in this order;  z = max(z, 0) if relu != 0
+ *   amax[i]   = max |z| over the image;  scale[i] = 127 / max(amax[i], eps)
+ *   q[m][co]  = clamp(round_half_even(z * scale[i]), -128, 127)
+ *   x        dev int8 [n][h][w][cin], 16-byte aligned; real value x * x_step[i]
+ *   w_packed dev, prom_pack_ternary output for [cout][cin]; real value code * w_scale[co]
+ *   x_step   dev float32 [n];  w_scale dev float32 [cout];  bias dev float32 [cout] or NULL
+ *   q        dev int8 [n][h][w][cout], 16-byte aligned;  amax, scale dev float32 [n] (outputs)
+ * Three launches on `stream`: clear amax, the layer with a maximum-only epilogue (one atomic
+ * maximum per wavefront and image), the layer again with the quantising epilogue.
+ * PROM_EINVAL for null or misaligned pointers, non-positive sizes or eps; PROM_EUNSUPPORTED unless
+ * cin % 4 == 0, cout % 16 == 0 and cin <= 1024, or if a tensor reaches 2 GiB. */
+int prom_pw_conv_dynq(const int8_t *x, int n, int h, int w, int cin, const void *w_packed, int cout,
+                      const float *x_step, const float *w_scale, const float *bias, int relu, float eps,
+                      int8_t *q, float *amax, float *scale, void *stream);
+
 /* ---- pointwise 1x1 convolution with ternary weights ------------------------------------
  * y[m][co] = requant_co( sum_k x[m][k] * W[co][k] ),  m over n*h*w pixels.
  *   x         dev int8 [n][h][w][cin]

@@ -115,6 +115,8 @@ def load_library():
     lib.prom_quantize_pw_absmean.argtypes = [vp, ci, ci, ctypes.c_float, vp, sz, vp, vp, vp]
     lib.prom_quantize_activation_absmax.restype = ci
     lib.prom_quantize_activation_absmax.argtypes = [vp, ci, ctypes.c_longlong, ctypes.c_float, vp, vp, vp]
+    lib.prom_pw_conv_dynq.restype = ci
+    lib.prom_pw_conv_dynq.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, ci, ctypes.c_float, vp, vp, vp, vp]
     lib.prom_quantize_dw_absmax.restype = ci
     lib.prom_quantize_dw_absmax.argtypes = [vp, ci, ctypes.c_float, vp, vp, vp]
     lib.prom_quantize_gconv_absmax.restype = ci
@@ -466,6 +468,32 @@ def prom_quantize_activation_absmax(x, eps: float = 1e-5, q=None, scale=None, st
                                                           scale.data_ptr(), _stream_ptr(stream)),
            "prom_quantize_activation_absmax")
     return q, scale
+
+
+def prom_pw_conv_dynq(x, w_packed, cout: int, x_step, w_scale, bias=None, relu: bool = False,
+                      eps: float = 1e-5, q=None, amax=None, scale=None, stream=None):
+    """x: int8 [n,h,w,cin] device; x_step float32 [n], w_scale float32 [cout], bias float32 [cout]
+    or None (device).  Returns (q int8 [n,h,w,cout], amax float32 [n], scale float32 [n])."""
+    import torch
+    _dev_i8(x, "x")
+    n, h, w, cin = x.shape
+    for name, t, cnt in (("x_step", x_step, n), ("w_scale", w_scale, cout), ("bias", bias, cout)):
+        if t is None and name == "bias":
+            continue
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == cnt):
+            raise TypeError(f"{name} must be a contiguous float32 device tensor of {cnt} elements")
+    if q is None:
+        q = torch.empty((n, h, w, cout), dtype=torch.int8, device=x.device)
+    _dev_i8(q, "q")
+    if amax is None:
+        amax = torch.empty(n, dtype=torch.float32, device=x.device)
+    if scale is None:
+        scale = torch.empty(n, dtype=torch.float32, device=x.device)
+    _check(load_library().prom_pw_conv_dynq(
+        x.data_ptr(), n, h, w, cin, w_packed.data_ptr(), int(cout), x_step.data_ptr(), w_scale.data_ptr(),
+        bias.data_ptr() if bias is not None else None, int(bool(relu)), float(eps), q.data_ptr(),
+        amax.data_ptr(), scale.data_ptr(), _stream_ptr(stream)), "prom_pw_conv_dynq")
+    return q, amax, scale
 
 
 def prom_quantize_dw_absmax(w, eps: float = 1e-5, stream=None):
