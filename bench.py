@@ -82,6 +82,10 @@ def main():
     ap.add_argument("--batch", type=int, default=BATCH, help="images per layer (metric is quoted at 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
+    ap.add_argument("--dw-only", action="store_true",
+                    help="run the depthwise sweep leg alone and print its record (for profiling)")
+    ap.add_argument("--dw-filter", default=None,
+                    help="with --dw-only: HW,C,STRIDE of the one depthwise layer to run, e.g. 56,144,1")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--zero-fraction", type=float, default=0.5,
                     help="P(weight == 0) of the synthetic ternary weights (the paper reports about 0.31 at "
@@ -112,6 +116,10 @@ def main():
     torch.cuda.set_device(dev)
     if args.ab:
         print(json.dumps(ab_study(P, torch, dev, args.ab, args.batch)), flush=True)
+        return
+    if args.dw_only:
+        only = tuple(int(v) for v in args.dw_filter.split(",")) if args.dw_filter else None
+        print(json.dumps({"depthwise_sweep": depthwise_leg(P, torch, dev, args.batch, log, only)}), flush=True)
         return
     t_setup = time.time()
 
@@ -664,13 +672,15 @@ def ab_study(P, torch, dev, which, batch):
     return out
 
 
-def extra_legs(P, torch, dev, batch, log):
-    """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
-    import numpy as np
-    from workloads import make_dw_layer, make_block, mobilenetv2_depthwise_layers
-    out = {}
+def depthwise_leg(P, torch, dev, batch, log, only=None):
+    """The 17 depthwise 3x3 layers of MobileNetV2 at the benchmark's batch: the whole sweep through
+    one prom_dw_conv_sequence call (independent layers), and every layer alone by the per-layer
+    protocol (cache-cold, one launch per layer)."""
+    from workloads import make_dw_layer, mobilenetv2_depthwise_layers
     dws = []
     for i, d in enumerate(mobilenetv2_depthwise_layers()):
+        if only is not None and (d.hw_in, d.c, d.stride) != only:
+            continue
         D = make_dw_layer(SEED + 1000 + i, 1, d.hw_in, d.hw_in, d.c, d.stride)
         x = torch.randint(0, 128, (batch, d.hw_in, d.hw_in, d.c), dtype=torch.int8, device=dev)
         w = torch.from_numpy(D.weight).to(dev)
@@ -679,23 +689,52 @@ def extra_legs(P, torch, dev, batch, log):
         ho = (d.hw_in - 1) // d.stride + 1
         y = torch.empty((batch, ho, ho, d.c), dtype=torch.int8, device=dev)
         dws.append((d, x, w, rq, y, batch * d.c * (d.hw_in ** 2 + ho ** 2)))
-    for _ in range(2):
-        for d, x, w, rq, y, _b in dws:
-            P.prom_dw_conv(x, w, d.stride, rq, y)
-    torch.cuda.synchronize()
-    reps = 5
+
+    # all layers with one host call (independent layers: the library may share a launch)
+    seq = P.DwSequence([(x, w, d.stride, rq, y) for d, x, w, rq, y, _b in dws])
+    settle(torch, lambda k: seq.run(), ms=40.0)
+    reps = 20
     t0 = time.perf_counter()
     for _ in range(reps):
-        for d, x, w, rq, y, _b in dws:
-            P.prom_dw_conv(x, w, d.stride, rq, y)
+        seq.run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
     nbytes = sum(b for *_, b in dws)
-    out["depthwise_sweep"] = {"layers": len(dws), "us": round(dt * 1e6, 1),
-                              "gbs": round(nbytes / dt / 1e9, 1),
-                              "frac_hbm_roofline": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)}
-    log(f"[bench] depthwise sweep: {dt * 1e6:.1f} us, {nbytes / dt / 1e9:.0f} GB/s")
-    del dws
+    per_layer = []
+    for d, x, w, rq, y, nb in dws:
+        nsets = min(64, int(512e6 // nb) + 2)
+        xs = [x] + [x.clone() for _ in range(nsets - 1)]
+        ys = [y] + [torch.empty_like(y) for _ in range(nsets - 1)]
+        seqs = [P.DwSequence([(xs[k], w, d.stride, rq, ys[k])]) for k in range(nsets)]
+        settle(torch, lambda k: seqs[k % nsets].run(), ms=10.0)
+        reps_us = []
+        for _ in range(5):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for k in range(100):
+                seqs[k % nsets].run()
+            e1.record()
+            torch.cuda.synchronize()
+            reps_us.append(e0.elapsed_time(e1) * 1e3 / 100)
+        us = sorted(reps_us)[2]
+        per_layer.append({"layer": d.name, "hw": d.hw_in, "c": d.c, "stride": d.stride, "us": round(us, 2),
+                          "gbs": round(nb / us / 1e3, 1), "frac_hbm_roofline": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)})
+        del xs, ys, seqs
+    res = {"layers": len(dws), "us": round(dt * 1e6, 1), "gbs": round(nbytes / dt / 1e9, 1),
+           "frac_hbm_roofline": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4),
+           "sum_layer_us": round(sum(p["us"] for p in per_layer), 1), "per_layer": per_layer}
+    log(f"[bench] depthwise sweep: {dt * 1e6:.1f} us, {nbytes / dt / 1e9:.0f} GB/s "
+        f"({100 * res['frac_hbm_roofline']:.1f} % of the HBM roofline); per layer (cold): "
+        + ", ".join(f"{p['hw']}x{p['c']}s{p['stride']} {p['us']:.1f}" for p in per_layer))
+    return res
+
+
+def extra_legs(P, torch, dev, batch, log):
+    """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
+    import numpy as np
+    from workloads import make_dw_layer, make_block
+    out = {"depthwise_sweep": depthwise_leg(P, torch, dev, batch, log)}
 
     B = make_block(SEED + 2000, 64, 28, 28, 32, 6)
     e, d, p = B.expand, B.dw, B.project

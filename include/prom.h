@@ -273,6 +273,26 @@ int prom_dw_conv(const int8_t *x, int n, int h, int w, int c,
                  const int8_t *w_dw, int stride, const prom_requant_t *rq,
                  int8_t *y, void *stream);
 
+/* One layer of a sequence for prom_dw_conv_sequence: the arguments of prom_dw_conv. */
+typedef struct {
+    const int8_t *x;
+    int32_t n, h, w, c;
+    const int8_t *w_dw;
+    int32_t stride;
+    prom_requant_t rq;
+    int8_t *y;
+} prom_dw_layer_t;
+
+/* Enqueue `count` depthwise layers (the operation of prom_dw_conv, paper Section 3.1 "Depthwise
+ * Convolutions") on `stream` with one host call.  The results are those of running the layers one
+ * after the other in the given order.  Consecutive layers that do not touch each other's data (no
+ * layer's output overlaps another's input, weights, parameters or output) share one kernel launch
+ * and run concurrently, which hides the launch, first-load and write-back latencies of the small
+ * layers; anything else is launched layer by layer.  All layers are validated first; on an
+ * argument error nothing is enqueued and the index of the offending layer is stored in *bad_layer
+ * when bad_layer is not NULL.  PROM_EHIP if a launch fails (earlier launches stay enqueued). */
+int prom_dw_conv_sequence(const prom_dw_layer_t *layers, int count, int *bad_layer, void *stream);
+
 /* ---- grouped 3x3 convolution, pad 1, stride 1 or 2 --------------------------------------
  * RegNet and ResNeXt have group sizes above one where MobileNetV2 has the depthwise convolution
  * (paper Section 2); the weights are 8-bit with one scale per output channel like the depthwise

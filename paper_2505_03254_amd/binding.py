@@ -37,6 +37,12 @@ class _PwLayerC(ctypes.Structure):
                 ("y", ctypes.c_void_p)]
 
 
+class _DwLayerC(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("n", ctypes.c_int32), ("h", ctypes.c_int32),
+                ("w", ctypes.c_int32), ("c", ctypes.c_int32), ("w_dw", ctypes.c_void_p),
+                ("stride", ctypes.c_int32), ("rq", _RequantC), ("y", ctypes.c_void_p)]
+
+
 class _PlanC(ctypes.Structure):
     _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
                 ("workgroups", ctypes.c_int32), ("row_waves", ctypes.c_int32)]
@@ -111,6 +117,8 @@ def load_library():
     lib.prom_pw_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(_PlanC), ctypes.POINTER(ci)]
     lib.prom_pw_conv_sequence.restype = ci
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_dw_conv_sequence.restype = ci
+    lib.prom_dw_conv_sequence.argtypes = [ctypes.POINTER(_DwLayerC), ci, ctypes.POINTER(ci), vp]
     lib.prom_quantize_pw_absmean.restype = ci
     lib.prom_quantize_pw_absmean.argtypes = [vp, ci, ci, ctypes.c_float, vp, sz, vp, vp, vp]
     lib.prom_quantize_activation_absmax.restype = ci
@@ -587,6 +595,36 @@ class PwSequence:
 
 def prom_pw_conv_sequence(layers, stream=None):
     PwSequence(layers).run(stream)
+
+
+class DwSequence:
+    """A prebuilt array of prom_dw_layer_t; run() enqueues all layers with one C call.
+    Keeps references to every tensor it points at."""
+
+    def __init__(self, layers):
+        """layers: iterable of (x, w_dw, stride, Requant, y) device tensors."""
+        layers = list(layers)
+        self._keep = layers
+        self._arr = (_DwLayerC * len(layers))()
+        for i, (x, w_dw, stride, rq, y) in enumerate(layers):
+            _dev_i8(x, "x")
+            _dev_i8(y, "y")
+            _dev_i8(w_dw, "w_dw")
+            n, h, w, c = x.shape
+            l = self._arr[i]
+            l.x, l.n, l.h, l.w, l.c = x.data_ptr(), n, h, w, c
+            l.w_dw, l.stride, l.rq, l.y = w_dw.data_ptr(), int(stride), rq._c(), y.data_ptr()
+        self.count = len(layers)
+
+    def run(self, stream=None):
+        bad = ctypes.c_int(-1)
+        rc = load_library().prom_dw_conv_sequence(self._arr, self.count, ctypes.byref(bad), _stream_ptr(stream))
+        if rc != PROM_OK:
+            raise PromError(rc, f"prom_dw_conv_sequence (layer {bad.value})")
+
+
+def prom_dw_conv_sequence(layers, stream=None):
+    DwSequence(layers).run(stream)
 
 
 def prom_copy_bytes(src, dst, nbytes: Optional[int] = None, stream=None):

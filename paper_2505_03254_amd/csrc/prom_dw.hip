@@ -22,6 +22,7 @@
 #include "prom_device.h"
 #include "prom_launch.h"
 #include <type_traits>
+#include <vector>
 
 namespace prom {
 
@@ -60,20 +61,21 @@ __device__ __forceinline__ void transpose4x4(const uint32_t (&in)[4], uint32_t (
 // the image is addressed through a buffer resource of its own, which makes rows above and below
 // it read as zero (and such output rows vanish) without a test, and a column outside the image
 // gets an offset beyond the resource.
+// (bx, by, bz): the workgroup's place in that grid.
 template <int S, int ROWS = 4>
-__global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
+__device__ __forceinline__ void dw_body_v4(const DwArgs &a, const int bx, const int by, const int bz)
 {
     constexpr int NPIX = S * (ROWS - 1) + 3;  // input rows feeding ROWS output rows
     constexpr int NB = (NPIX + 3) / 4;        // transposed dwords per channel
     constexpr int kFlags = 0x00020000;
     constexpr int kOob = 0x7ffff000;
     const int C4 = a.C >> 2;
-    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int t = bx * 256 + threadIdx.x;
     if (t >= a.Wo * C4) return;
     const int ox = t / C4;
     const int c = (t - ox * C4) * 4;
-    const int oy0 = blockIdx.y * ROWS;
-    const int n = blockIdx.z;
+    const int oy0 = by * ROWS;
+    const int n = bz;
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(a.x) + (long long)n * a.H * a.W * a.C, 0, a.H * a.W * a.C, kFlags);
@@ -205,6 +207,42 @@ __global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
         epilogue(std::false_type{});
 }
 
+template <int S, int ROWS = 4>
+__global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
+{
+    dw_body_v4<S, ROWS>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Several independent depthwise layers in one launch: workgroups [start[i], start[i+1]) run layer i
+// with the grid (xblocks, strips, images) it would have on its own.  The launch, first-load and
+// write-back latencies of a small layer (5 us of a 7 us launch at 14x14 and 7x7) overlap with the
+// other layers' work.
+constexpr int kDwMaxBatch = 32;
+struct DwBatchArgs {
+    int count;
+    int start[kDwMaxBatch + 1];
+    int xblocks[kDwMaxBatch];
+    DwArgs layer[kDwMaxBatch];
+};
+
+__global__ __launch_bounds__(256) void dw_batch_kernel(const DwBatchArgs b)
+{
+    const int bid = blockIdx.x;
+    int i = 0;
+    while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
+    const DwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
+    const int l = bid - b.start[i];
+    const int xb = b.xblocks[i];
+    const int bx = l % xb, r = l / xb;
+    const int by = r % a.strips, bz = r / a.strips;
+    if (a.stride == 2)
+        dw_body_v4<2, 4>(a, bx, by, bz);
+    else if (a.strip_rows == 8)
+        dw_body_v4<1, 8>(a, bx, by, bz);
+    else
+        dw_body_v4<1, 4>(a, bx, by, bz);
+}
+
 // Any C and alignment: one thread per output element.
 __global__ __launch_bounds__(256) void dw_kernel_generic(const DwArgs a)
 {
@@ -253,30 +291,38 @@ int prom::dw_shape_check(int n, int h, int w, int c, int stride)
     return PROM_OK;
 }
 
-extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const int8_t *w_dw, int stride,
-                            const prom_requant_t *rq, int8_t *y, void *stream)
+namespace prom {
+
+struct DwLaunch {
+    DwArgs a;
+    bool fast;
+    dim3 grid;
+    size_t xbytes, ybytes;
+};
+
+// Validate the arguments of one depthwise layer and fill its launch description; launches nothing.
+static int dw_prepare(const int8_t *x, int n, int h, int w, int c, const int8_t *w_dw, int stride,
+                      const prom_requant_t *rq, int8_t *y, DwLaunch &L)
 {
-    using namespace prom;
     if (!x || !w_dw || !rq || !rq->bias || !rq->mult || !rq->shift || !y) return PROM_EINVAL;
     if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || (stride != 1 && stride != 2)) return PROM_EINVAL;
     if (rq->act_min < -128 || rq->act_max > 127 || rq->act_min > rq->act_max) return PROM_EINVAL;
-    DwArgs a;
+    DwArgs &a = L.a;
     a.x = x; a.w = w_dw; a.bias = rq->bias; a.mult = rq->mult; a.mult_neg = rq->mult_neg; a.shift = rq->shift; a.y = y;
     a.N = n; a.H = h; a.W = w; a.C = c; a.stride = stride;
     a.Ho = (h - 1) / stride + 1;
     a.Wo = (w - 1) / stride + 1;
     a.lo = rq->act_min;
     a.hi = rq->act_max;
-    const size_t xbytes = (size_t)n * h * w * c, ybytes = (size_t)n * a.Ho * a.Wo * c;
-    if (xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
-    if (overlaps(y, ybytes, x, xbytes) || overlaps(y, ybytes, w_dw, (size_t)9 * c)) return PROM_EALIAS;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    clear_hip_error();
+    L.xbytes = (size_t)n * h * w * c;
+    L.ybytes = (size_t)n * a.Ho * a.Wo * c;
+    if (L.xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
+    if (overlaps(y, L.ybytes, x, L.xbytes) || overlaps(y, L.ybytes, w_dw, (size_t)9 * c)) return PROM_EALIAS;
     // the fast kernel addresses one image with 32-bit offsets and reads the parameters 16 bytes at a time
-    const bool fast = (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 3) == 0) &&
-                      ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg | (uintptr_t)rq->shift) & 15) == 0) &&
-                      (long long)h * w * c < (1LL << 31) - (1LL << 24) && n <= 65535;
-    if (fast) {
+    L.fast = (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_dw) & 3) == 0) &&
+             ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg | (uintptr_t)rq->shift) & 15) == 0) &&
+             (long long)h * w * c < (1LL << 31) - (1LL << 24) && n <= 65535;
+    if (L.fast) {
         // stride 1: 8 output rows per thread where the map is high enough (fewer instructions per
         // output: the transposes and the weights are shared by twice as many rows)
         const int rows = (stride == 1 && a.Ho >= 8) ? 8 : 4;
@@ -285,19 +331,115 @@ extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const i
         a.total = 0;
         const long long xblocks = ((long long)a.Wo * (c / 4) + 255) / 256;
         if (xblocks > (1LL << 31) - 1 || a.strips > 65535 || n > 65535) return PROM_EUNSUPPORTED;
-        const dim3 grid((unsigned)xblocks, (unsigned)a.strips, (unsigned)n);
-        if (stride == 1 && rows == 8)
-            hipLaunchKernelGGL((dw_kernel_v4<1, 8>), grid, dim3(256), 0, st, a);
-        else if (stride == 1)
-            hipLaunchKernelGGL(dw_kernel_v4<1>, grid, dim3(256), 0, st, a);
-        else
-            hipLaunchKernelGGL(dw_kernel_v4<2>, grid, dim3(256), 0, st, a);
+        L.grid = dim3((unsigned)xblocks, (unsigned)a.strips, (unsigned)n);
     } else {
         a.strips = a.strip_rows = 0;
-        a.total = (long long)ybytes;
+        a.total = (long long)L.ybytes;
         const long long blocks = (a.total + 255) / 256;
         if (blocks > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
-        hipLaunchKernelGGL(dw_kernel_generic, dim3((unsigned)blocks), dim3(256), 0, st, a);
+        L.grid = dim3((unsigned)blocks);
     }
+    return PROM_OK;
+}
+
+static void dw_launch(const DwLaunch &L, hipStream_t st)
+{
+    const DwArgs &a = L.a;
+    if (!L.fast)
+        hipLaunchKernelGGL(dw_kernel_generic, L.grid, dim3(256), 0, st, a);
+    else if (a.stride == 1 && a.strip_rows == 8)
+        hipLaunchKernelGGL((dw_kernel_v4<1, 8>), L.grid, dim3(256), 0, st, a);
+    else if (a.stride == 1)
+        hipLaunchKernelGGL(dw_kernel_v4<1>, L.grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(dw_kernel_v4<2>, L.grid, dim3(256), 0, st, a);
+}
+
+// true if running `b` concurrently with `a` could change a result
+static bool dw_conflicts(const DwLaunch &p, const DwLaunch &q)
+{
+    const DwArgs &a = p.a, &b = q.a;
+    if (overlaps(a.y, p.ybytes, b.y, q.ybytes) || overlaps(a.y, p.ybytes, b.x, q.xbytes) ||
+        overlaps(b.y, q.ybytes, a.x, p.xbytes))
+        return true;
+    auto writes_inputs = [](const DwArgs &w, size_t wn, const DwArgs &r) {
+        if (overlaps(w.y, wn, r.w, (size_t)9 * r.C)) return true;
+        const int32_t *arrs[4] = {r.bias, r.mult, r.shift, r.mult_neg};
+        for (const int32_t *q4 : arrs)
+            if (q4 && overlaps(w.y, wn, q4, (size_t)r.C * 4)) return true;
+        return false;
+    };
+    return writes_inputs(a, p.ybytes, b) || writes_inputs(b, q.ybytes, a);
+}
+
+}  // namespace prom
+
+extern "C" int prom_dw_conv(const int8_t *x, int n, int h, int w, int c, const int8_t *w_dw, int stride,
+                            const prom_requant_t *rq, int8_t *y, void *stream)
+{
+    using namespace prom;
+    DwLaunch L;
+    const int rc = dw_prepare(x, n, h, w, c, w_dw, stride, rq, y, L);
+    if (rc != PROM_OK) return rc;
+    clear_hip_error();
+    dw_launch(L, static_cast<hipStream_t>(stream));
     return check_launch();
+}
+
+extern "C" int prom_dw_conv_sequence(const prom_dw_layer_t *layers, int count, int *bad_layer, void *stream)
+{
+    using namespace prom;
+    if (bad_layer) *bad_layer = -1;
+    if (count < 0 || (count > 0 && !layers)) return PROM_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    static thread_local std::vector<DwLaunch> prepared;
+    prepared.resize((size_t)count);
+    for (int i = 0; i < count; ++i) {
+        const prom_dw_layer_t &l = layers[i];
+        const int rc = dw_prepare(l.x, l.n, l.h, l.w, l.c, l.w_dw, l.stride, &l.rq, l.y, prepared[(size_t)i]);
+        if (rc != PROM_OK) {
+            if (bad_layer) *bad_layer = i;
+            return rc;
+        }
+    }
+    // Consecutive layers the vector kernel takes and that do not touch each other's data share a
+    // launch (at most kDwMaxBatch of them, and workgroup counts that fit a 1-D grid).
+    static thread_local DwBatchArgs b;
+    clear_hip_error();
+    int i = 0;
+    while (i < count) {
+        int j = i;
+        long long blocks = 0;
+        while (j < count && j - i < kDwMaxBatch && prepared[(size_t)j].fast) {
+            const DwLaunch &L = prepared[(size_t)j];
+            bool clash = false;
+            for (int k = i; k < j && !clash; ++k) clash = dw_conflicts(prepared[(size_t)k], L);
+            const long long nb = (long long)L.grid.x * L.grid.y * L.grid.z;
+            if (clash || blocks + nb > (1LL << 30)) break;
+            blocks += nb;
+            ++j;
+        }
+        if (j - i >= 2) {
+            b.count = j - i;
+            int start = 0;
+            for (int k = i; k < j; ++k) {
+                const DwLaunch &L = prepared[(size_t)k];
+                b.layer[k - i] = L.a;
+                b.xblocks[k - i] = (int)L.grid.x;
+                b.start[k - i] = start;
+                start += (int)(L.grid.x * L.grid.y * L.grid.z);
+            }
+            b.start[j - i] = start;
+            hipLaunchKernelGGL(dw_batch_kernel, dim3((unsigned)start), dim3(256), 0, st, b);
+            i = j;
+        } else {
+            dw_launch(prepared[(size_t)i], st);
+            ++i;
+        }
+        if (check_launch() != PROM_OK) {
+            if (bad_layer) *bad_layer = i - 1;
+            return PROM_EHIP;
+        }
+    }
+    return PROM_OK;
 }
