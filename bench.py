@@ -733,7 +733,7 @@ def depthwise_leg(P, torch, dev, batch, log, only=None):
 def extra_legs(P, torch, dev, batch, log):
     """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
     import numpy as np
-    from workloads import make_dw_layer, make_block
+    from workloads import make_dw_layer, make_block, mobilenetv2_depthwise_layers
     out = {"depthwise_sweep": depthwise_leg(P, torch, dev, batch, log)}
 
     B = make_block(SEED + 2000, 64, 28, 28, 32, 6)
@@ -811,10 +811,8 @@ def extra_legs(P, torch, dev, batch, log):
                 else:
                     _, xi, _m, yo, b, chid, we_, wd_, wp_, rq3, addres = st
                     P.prom_block(xi, chid, b.cout, b.stride, we_, rq3[0], wd_, rq3[1], wp_, rq3[2], addres, ws, yo)
-        for _ in range(2):
-            chain()
-        torch.cuda.synchronize()
-        reps = 5
+        settle(torch, lambda k: chain(), ms=40.0)
+        reps = 10
         t0 = time.perf_counter()
         for _ in range(reps):
             chain()
@@ -831,9 +829,7 @@ def extra_legs(P, torch, dev, batch, log):
                 with torch.cuda.graph(graph, stream=side):
                     chain()
             torch.cuda.current_stream().wait_stream(side)
-            for _ in range(2):
-                graph.replay()
-            torch.cuda.synchronize()
+            settle(torch, lambda k: graph.replay(), ms=40.0)
             tg = time.perf_counter()
             for _ in range(20):
                 graph.replay()
@@ -904,12 +900,12 @@ def extra_legs(P, torch, dev, batch, log):
     amaxf = torch.empty(batch, dtype=torch.float32, device=dev)
     scalef = torch.empty(batch, dtype=torch.float32, device=dev)
 
-    def fused():
+    def run_dynq():
         P.prom_pw_conv_dynq(xf, wpf, 144, x_step, w_scale, fbias, True, q=qf, amax=amaxf, scale=scalef)
-    settle(torch, lambda k: fused())
+    settle(torch, lambda k: run_dynq())
     tf0 = time.perf_counter()
     for _ in range(20):
-        fused()
+        run_dynq()
     torch.cuda.synchronize()
     df = (time.perf_counter() - tf0) / 20
     algf = batch * 56 * 56 * (24 + 144)
