@@ -351,7 +351,7 @@ size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cou
  * measured faster for the shape.  PROM_BLOCK_FUSED returns PROM_EUNSUPPORTED where the fused kernel
  * does not apply (prom_block_can_fuse, and x, y, w_dw 8-byte aligned), PROM_BLOCK_DWPROJ where
  * prom_dw_pw_can_fuse says no. */
-enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2, PROM_BLOCK_DWPROJ = 3 };
+enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2, PROM_BLOCK_DWPROJ = 3, PROM_BLOCK_PLANES = 4 };
 int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
                   const void *w_expand_packed, const prom_requant_t *rq_expand,
                   const int8_t *w_dw, const prom_requant_t *rq_dw,
@@ -367,6 +367,12 @@ int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int st
 /* 1 if the fused kernel applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
  * cout <= 160, chid <= 192, a band of rows fits in LDS), 0 if not. */
 int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride);
+
+/* 1 if PROM_BLOCK_PLANES applies to the shape (one kernel; a band of the expanded tensor stays in
+ * LDS as 16-channel planes and no weight matrix passes through LDS: cin % 8 == 0, cin <= 192,
+ * chid % 16 == 0, cout % 4 == 0, tensors below 2 GiB, a band of one output row fits 160 KB of LDS;
+ * pointers assumed 8-byte aligned), 0 if not, PROM_EINVAL for bad dimensions.  Host only. */
+int prom_block_planes_applies(int n, int h, int w, int cin, int chid, int cout, int stride);
 
 /* ---- depthwise 3x3 and the pointwise projection behind it, in one kernel ---------------------
  * The second half of the block (Section 2; Figure 4: depthwise, then the projecting pointwise

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     prom_packed_size, prom_pack_ternary, prom_unpack_ternary,
     prom_pw_conv, prom_pw_conv_ex, prom_pw_conv_addsub, prom_pw_accum_i32, prom_dw_conv, prom_gconv3x3, prom_gconv_pack, prom_gconv_frag_size,
     prom_block, prom_block_workspace_size, prom_block_is_fused, prom_block_can_fuse, prom_strerror,
-    BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ, prom_dw_pw_conv, prom_dw_pw_can_fuse, prom_block_noalloc, prom_block_noalloc_max_workspace,
+    BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ, BLOCK_PLANES, prom_block_planes_applies, prom_dw_pw_conv, prom_dw_pw_can_fuse, prom_block_noalloc, prom_block_noalloc_max_workspace,
     prom_quantize_pw_absmean, prom_quantize_dw_absmax, prom_quantize_gconv_absmax,
     prom_quantize_activation_absmax, prom_pw_conv_dynq,
     prom_pw_plan_query, prom_pw_batchable, prom_pw_batch_class, prom_pw_conv_sequence, PwSequence, prom_dw_conv_sequence, DwSequence, prom_copy_bytes,

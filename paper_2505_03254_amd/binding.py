@@ -111,6 +111,8 @@ def load_library():
     lib.prom_dw_pw_can_fuse.argtypes = [ci] * 6
     lib.prom_block_can_fuse.restype = ci
     lib.prom_block_can_fuse.argtypes = [ci] * 7
+    lib.prom_block_planes_applies.restype = ci
+    lib.prom_block_planes_applies.argtypes = [ci] * 7
     lib.prom_block_workspace_size.restype = sz
     lib.prom_block_workspace_size.argtypes = [ci] * 7
     lib.prom_pw_plan_query.restype = ci
@@ -381,7 +383,7 @@ def prom_block(x, chid: int, cout: int, stride: int, w_expand_packed, rq_expand:
     return y
 
 
-BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ = 0, 1, 2, 3
+BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ, BLOCK_PLANES = 0, 1, 2, 3, 4
 
 
 def prom_dw_pw_conv(x, w_dw, stride: int, rq_dw: Requant, w_project_packed, cout: int, rq_project: Requant,
@@ -434,6 +436,13 @@ def prom_block_noalloc(x, chid: int, cout: int, stride: int, w_expand_packed, rq
 
 def prom_block_noalloc_max_workspace() -> int:
     return int(load_library().prom_block_noalloc_max_workspace())
+
+
+def prom_block_planes_applies(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:
+    rc = load_library().prom_block_planes_applies(n, h, w, cin, chid, cout, stride)
+    if rc < 0:
+        raise PromError(rc, "prom_block_planes_applies")
+    return bool(rc)
 
 
 def prom_block_can_fuse(n: int, h: int, w: int, cin: int, chid: int, cout: int, stride: int) -> bool:

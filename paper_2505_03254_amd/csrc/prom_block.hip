@@ -21,6 +21,7 @@
 // Shapes the fused kernel does not take run as three launches through the caller's workspace.
 #include "prom_pw_stream.h"
 #include "prom_launch.h"
+#include "prom_block_planes.h"
 
 #include <mutex>
 #include <vector>
@@ -427,6 +428,19 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid, bool f
 // graph is slower with it (316 against 291 us at batch 8), because two short kernels cost less there
 // than the serial chunk loop.  The form stays available through PROM_BLOCK_DWPROJ and
 // prom_dw_pw_conv: it moves one intermediate tensor less through HBM.
+// Whether PROM_BLOCK_AUTO takes the plane-resident kernel where it applies.  Measured (GPU time per
+// call, MobileNetV2 blocks): with at least 12 planes of hidden channels on maps up to 28x28 the one
+// kernel beats the three launches and the chunk-interleaved fused kernel (batch 128: 28x28x192
+// 26 against 27 us fused, stride 2 18 against 28; 14x14x384 15 against 29; 14x14x576 21 against 34;
+// 7x7x960 21 to 23 against 29).  On larger maps the band's halo rows and the vector ALU's
+// requantisation of the expanded tensor cost more than the three streaming kernels (56x56x144: 89
+// against 66 us; 112x112x96: 109 against 88).
+static bool planes_is_faster(int n, int h, int w, int cin, int chid, int cout, int stride)
+{
+    (void)n; (void)cin; (void)cout; (void)stride;
+    return chid >= 192 && (long long)h * w <= 28 * 28;
+}
+
 static bool dwproj_is_faster(int n, int h, int w, int chid, int cout, int stride)
 {
     (void)n; (void)h; (void)w; (void)chid; (void)cout; (void)stride;
@@ -465,6 +479,19 @@ extern "C" int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int c
     return fused_query(n, h, w, cin, chid, cout, stride, true);
 }
 
+extern "C" int prom_block_planes_applies(int n, int h, int w, int cin, int chid, int cout, int stride)
+{
+    using namespace prom;
+    if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || chid <= 0 || cout <= 0 || (stride != 1 && stride != 2))
+        return PROM_EINVAL;
+    PlanesArgs a = {};
+    a.N = n; a.H = h; a.W = w; a.Ho = (h - 1) / stride + 1; a.Wo = (w - 1) / stride + 1;
+    a.cin = cin; a.chid = chid; a.cout = cout; a.stride = stride;
+    size_t lds = 0;
+    int grid = 0, kse = 0;
+    return plan_planes(a, lds, grid, kse) ? 1 : 0;
+}
+
 extern "C" int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
                           const void *w_expand_packed, const prom_requant_t *rq_expand,
                           const int8_t *w_dw, const prom_requant_t *rq_dw,
@@ -485,7 +512,8 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
                              int path, void *stream)
 {
     using namespace prom;
-    if (path != PROM_BLOCK_AUTO && path != PROM_BLOCK_FUSED && path != PROM_BLOCK_UNFUSED && path != PROM_BLOCK_DWPROJ)
+    if (path != PROM_BLOCK_AUTO && path != PROM_BLOCK_FUSED && path != PROM_BLOCK_UNFUSED &&
+        path != PROM_BLOCK_DWPROJ && path != PROM_BLOCK_PLANES)
         return PROM_EINVAL;
     if (!x || !y || !w_expand_packed || !w_dw || !w_project_packed || !rq_expand || !rq_dw || !rq_project)
         return PROM_EINVAL;
@@ -527,6 +555,29 @@ extern "C" int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int 
     a.lo_e = rq_expand->act_min; a.hi_e = rq_expand->act_max;
     a.lo_d = rq_dw->act_min; a.hi_d = rq_dw->act_max;
     a.lo_p = rq_project->act_min; a.hi_p = rq_project->act_max;
+    if (path == PROM_BLOCK_PLANES || path == PROM_BLOCK_AUTO) {
+        // one kernel, the expanded band resident in LDS as 16-channel planes
+        PlanesArgs pa = {};
+        pa.x = x; pa.y = y;
+        pa.we = a.we; pa.wd = a.wd; pa.wp = a.wp;
+        pa.be = a.be; pa.me = a.me; pa.se = a.se;
+        pa.bd = a.bd; pa.md = a.md; pa.sd = a.sd;
+        pa.bp = a.bp; pa.mp = a.mp; pa.sp = a.sp;
+        pa.ne = a.ne; pa.nd = a.nd; pa.np = a.np;
+        pa.N = n; pa.H = h; pa.W = w; pa.Ho = ho; pa.Wo = wo;
+        pa.cin = cin; pa.chid = chid; pa.cout = cout; pa.stride = stride;
+        pa.add_res = add_residual;
+        pa.lo_e = a.lo_e; pa.hi_e = a.hi_e; pa.lo_d = a.lo_d; pa.hi_d = a.hi_d; pa.lo_p = a.lo_p; pa.hi_p = a.hi_p;
+        size_t plds = 0;
+        int pgrid = 0, kse = 0;
+        // (the per-channel arrays of the first two layers are read four channels at a time)
+        uintptr_t par_bits = (uintptr_t)pa.be | (uintptr_t)pa.me | (uintptr_t)pa.se | (uintptr_t)pa.bd |
+                             (uintptr_t)pa.md | (uintptr_t)pa.sd | (uintptr_t)pa.ne | (uintptr_t)pa.nd;
+        const bool ok = aligned && (par_bits & 15) == 0 && plan_planes(pa, plds, pgrid, kse) &&
+                        (path == PROM_BLOCK_PLANES || planes_is_faster(n, h, w, cin, chid, cout, stride));
+        if (path == PROM_BLOCK_PLANES && !ok) return PROM_EUNSUPPORTED;
+        if (ok) return launch_planes(pa, plds, pgrid, kse, stream);
+    }
     BlockFn fn = nullptr;
     size_t lds = 0;
     int grid = 0;

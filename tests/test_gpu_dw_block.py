@@ -155,6 +155,13 @@ def test_block_shapes(P, shape):
         with pytest.raises(P.PromError) as e:
             _run_block(P, B, P.BLOCK_DWPROJ)
         assert e.value.code == -2
+    # one kernel with the expanded band resident in LDS as 16-channel planes
+    if P.prom_block_planes_applies(n, h, w, cin, cin * t, cout, stride):
+        assert_same(_run_block(P, B, P.BLOCK_PLANES), want, f"block {shape} plane-resident kernel")
+    else:
+        with pytest.raises(P.PromError) as e:
+            _run_block(P, B, P.BLOCK_PLANES)
+        assert e.value.code == -2
     assert_same(_run_block(P, B), want, f"block {shape}")
 
 
