@@ -344,13 +344,15 @@ int prom_block(const int8_t *x, int n, int h, int w, int cin, int chid, int cout
 
 size_t prom_block_workspace_size(int n, int h, int w, int cin, int chid, int cout, int stride);
 
-/* The same with the choice between the forms of the block made by the caller: as one fused kernel
- * (the expanded tensor stays on chip), as three launches through the workspace, or as two launches
- * (expand, then depthwise and projection fused: prom_dw_pw_conv; only the expanded tensor goes
- * through the workspace).  prom_block is prom_block_ex with PROM_BLOCK_AUTO, which takes the form
- * measured faster for the shape.  PROM_BLOCK_FUSED returns PROM_EUNSUPPORTED where the fused kernel
- * does not apply (prom_block_can_fuse, and x, y, w_dw 8-byte aligned), PROM_BLOCK_DWPROJ where
- * prom_dw_pw_can_fuse says no. */
+/* The same with the choice between the forms of the block made by the caller: as one kernel whose
+ * expanded band stays in LDS as 16-channel planes (PROM_BLOCK_PLANES: any number of hidden
+ * channels that is a multiple of 16), as one chunk-interleaved kernel with every weight decoded in
+ * LDS (PROM_BLOCK_FUSED: up to 192 hidden channels), as three launches through the workspace, or as
+ * two launches (expand, then depthwise and projection fused: prom_dw_pw_conv; only the expanded
+ * tensor goes through the workspace).  prom_block is prom_block_ex with PROM_BLOCK_AUTO, which takes
+ * the form measured faster for the shape.  A form returns PROM_EUNSUPPORTED where it does not apply
+ * (prom_block_planes_applies with 16-byte aligned parameter arrays of the first two layers,
+ * prom_block_can_fuse, prom_dw_pw_can_fuse; x, y, w_dw 8-byte aligned). */
 enum { PROM_BLOCK_AUTO = 0, PROM_BLOCK_FUSED = 1, PROM_BLOCK_UNFUSED = 2, PROM_BLOCK_DWPROJ = 3, PROM_BLOCK_PLANES = 4 };
 int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int cout, int stride,
                   const void *w_expand_packed, const prom_requant_t *rq_expand,
@@ -359,12 +361,12 @@ int prom_block_ex(const int8_t *x, int n, int h, int w, int cin, int chid, int c
                   int add_residual, void *workspace, size_t workspace_bytes,
                   int8_t *y, int path, void *stream);
 
-/* 1 if prom_block (PROM_BLOCK_AUTO) runs this shape as one fused kernel (pointers assumed 8-byte
- * aligned), 0 if as three launches through the workspace, PROM_EINVAL for bad dimensions.  Host
- * only, launches nothing. */
+/* 1 if prom_block (PROM_BLOCK_AUTO) runs this shape as one kernel of either kind (pointers
+ * assumed aligned), 0 if as three launches through the workspace, PROM_EINVAL for bad dimensions.
+ * Host only, launches nothing. */
 int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride);
 
-/* 1 if the fused kernel applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
+/* 1 if the chunk-interleaved fused kernel (PROM_BLOCK_FUSED) applies to the shape at all (cin % 8 == 0, chid % 4 == 0, cout % 4 == 0,
  * cout <= 160, chid <= 192, a band of rows fits in LDS), 0 if not. */
 int prom_block_can_fuse(int n, int h, int w, int cin, int chid, int cout, int stride);
 

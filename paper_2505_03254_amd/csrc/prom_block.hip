@@ -432,13 +432,17 @@ static bool plan_fused(BlockArgs &a, BlockFn &fn, size_t &lds, int &grid, bool f
 // call, MobileNetV2 blocks): with at least 12 planes of hidden channels on maps up to 28x28 the one
 // kernel beats the three launches and the chunk-interleaved fused kernel (batch 128: 28x28x192
 // 26 against 27 us fused, stride 2 18 against 28; 14x14x384 15 against 29; 14x14x576 21 against 34;
-// 7x7x960 21 to 23 against 29).  On larger maps the band's halo rows and the vector ALU's
+// 7x7x960 20 to 25 against 29).  On larger maps the band's halo rows and the vector ALU's
 // requantisation of the expanded tensor cost more than the three streaming kernels (56x56x144: 89
 // against 66 us; 112x112x96: 109 against 88).
 static bool planes_is_faster(int n, int h, int w, int cin, int chid, int cout, int stride)
 {
-    (void)n; (void)cin; (void)cout; (void)stride;
-    return chid >= 192 && (long long)h * w <= 28 * 28;
+    (void)cin; (void)cout; (void)stride;
+    if (chid >= 192 && (long long)h * w <= 28 * 28) return true;
+    // small problems are bound by launches, not by work: one kernel instead of three (the 17-block
+    // chain at batch 8 replayed from a HIP graph: 201 us with this kernel throughout, 230 with it on
+    // the deep blocks only, 281 with three launches per block)
+    return (long long)n * h * w * chid <= (48LL << 20);
 }
 
 static bool dwproj_is_faster(int n, int h, int w, int chid, int cout, int stride)
@@ -471,6 +475,9 @@ static int fused_query(int n, int h, int w, int cin, int chid, int cout, int str
 
 extern "C" int prom_block_is_fused(int n, int h, int w, int cin, int chid, int cout, int stride)
 {
+    const int planes = prom_block_planes_applies(n, h, w, cin, chid, cout, stride);
+    if (planes < 0) return planes;
+    if (planes == 1 && planes_is_faster(n, h, w, cin, chid, cout, stride)) return 1;
     return fused_query(n, h, w, cin, chid, cout, stride, false);
 }
 

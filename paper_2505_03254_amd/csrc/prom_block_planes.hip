@@ -165,10 +165,10 @@ __global__ __launch_bounds__(64 * NW, 1) void block_planes_kernel(const PlanesAr
     for (int q = 0; q < NWD; ++q) wdv[q] = wd4[min(tid + q * kPlThreads, nwd - 1)];
 
     {
+        // (pixels beyond the band land in a spare cell behind the plane's rows)
         for (int p = tid; p < nt1 * 16; p += kPlThreads) {
-            const int pc = min(p, np1 - 1);
-            const int row = pc / W, col = pc - row * W;
-            o1[p] = (uint16_t)((rv0 + row) * W2 + col + 1);
+            const int row = p / W, col = p - row * W;
+            o1[p] = (uint16_t)(p < np1 ? (rv0 + row) * W2 + col + 1 : a.RI * W2);
         }
         for (int p = tid; p < nt2 * 16; p += kPlThreads) {
             const int pc = min(p, np2 - 1);
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(64 * NW, 1) void block_planes_kernel(const PlanesAr
 #pragma unroll
                 for (int i = 0; i < NTL; ++i) {
                     p[i] = (pt + i) * 16 + j;
-                    const int8_t *xp = xs + __umul24(min(p[i], np1 - 1), cinp) + 16 * g;
+                    const int8_t *xp = xs + __umul24(p[i], cinp) + 16 * g;
                     cell[i] = o1[p[i]];
                     d[i] = zero4;
 #pragma unroll
@@ -265,8 +265,7 @@ __global__ __launch_bounds__(64 * NW, 1) void block_planes_kernel(const PlanesAr
                     int v[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) v[r] = requant_mode<MODE>(d[i][r], par[r], lo_e, hi_e);
-                    if (p[i] < np1)
-                        *reinterpret_cast<uint32_t *>(t1p + cell[i] * 16) = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<uint32_t *>(t1p + cell[i] * 16) = pack4_low_bytes(v[0], v[1], v[2], v[3]);
                 }
             };
             auto run = [&](auto mode) __attribute__((always_inline)) {
@@ -546,10 +545,10 @@ bool plan_planes(PlanesArgs &a, size_t &lds, int &grid, int &kse)
             for (int R = 1; R <= a.Ho; ++R) {
                 const int RI = (R - 1) * s + 3;
                 const long long np1 = (long long)RI * a.W, np2 = (long long)R * a.Wo;
-                if (np1 > 8192 || (long long)RI * W2 >= 65536) break;
+                if (np1 > 8192 || (long long)RI * W2 >= 65535) break;
                 const int nt1 = (int)((np1 + 15) / 16), nt2 = (int)((np2 + 15) / 16);
-                const int plane1 = RI * W2 * 16, plane2 = nt2 * 256;
-                long long bytes = align16i((int)np1 * cinp + 64 * kse + 64);  // xs
+                const int plane1 = (RI * W2 + 1) * 16, plane2 = nt2 * 256;
+                long long bytes = align16i(nt1 * 16 * cinp + 64 * kse + 64);  // xs
                 bytes += align16i(nt1 * 32) + align16i(nt2 * 32);             // o1, o2
                 bytes += COT * 256;                                           // pp
                 bytes += 16LL * COT * s3 * 4;                                 // w3l
@@ -604,8 +603,8 @@ bool plan_planes(PlanesArgs &a, size_t &lds, int &grid, int &kse)
     a.TPG3 = best.TPG3;
     const int np1 = a.RI * a.W, np2 = R * a.Wo;
     const int nt1 = (np1 + 15) / 16, nt2 = (np2 + 15) / 16;
-    const int plane1 = a.RI * W2 * 16, plane2 = nt2 * 256;
-    int off = align16i(np1 * cinp + 64 * kse + 64);
+    const int plane1 = (a.RI * W2 + 1) * 16, plane2 = nt2 * 256;
+    int off = align16i(nt1 * 16 * cinp + 64 * kse + 64);
     a.off_o1 = off; off += align16i(nt1 * 32);
     a.off_o2 = off; off += align16i(nt2 * 32);
     a.off_pp = off; off += COT * 256;

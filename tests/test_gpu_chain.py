@@ -89,6 +89,43 @@ def test_mobilenetv2_block_chain(P, p_zero, input_hw, n):
     assert_same(y_dev.cpu().numpy(), oracle.pw_conv(x_host, H.weight, H.bias, H.mult, H.shift, 0, 127), "head")
 
 
+@pytest.mark.parametrize("n", [32, 128])
+def test_mobilenetv2_block_chain_full_size_auto(P, n):
+    """The 16 expanding blocks at the network's own sizes (224x224 input) through prom_block with
+    PROM_BLOCK_AUTO, at batches where the library picks different forms: at 32 images every block
+    is one kernel; at 128 the three blocks on the large maps are three launches and the thirteen
+    behind them one kernel each.  Every output of every block against the oracle."""
+    torch = torch_cuda()
+    blocks = [b for b in mobilenetv2_blocks() if b.t != 1]
+    seed = 8800 + n
+    b0 = blocks[0]
+    x_host = SplitMix64(seed).bytes_masked(n * b0.hw_in * b0.hw_in * b0.cin, 0x7F).view(np.int8)
+    x_host = x_host.reshape(n, b0.hw_in, b0.hw_in, b0.cin)
+    x_dev = dev(x_host)
+    one_kernel = []
+    for i, b in enumerate(blocks):
+        hw = b.hw_in
+        B = make_block(seed + 10 * i, 1, hw, hw, b.cin, b.t, b.cout, b.stride, expand_shift=_pw_shift(b.cin),
+                       dw_shift=DW_SHIFT, project_shift=_pw_shift(b.cin * b.t))
+        ws = torch.empty(P.prom_block_workspace_size(n, hw, hw, b.cin, B.chid, b.cout, b.stride),
+                         dtype=torch.int8, device="cuda")
+        one_kernel.append(P.prom_block_is_fused(n, hw, hw, b.cin, B.chid, b.cout, b.stride))
+        y_dev = P.prom_block(x_dev, B.chid, b.cout, b.stride,
+                             dev(P.prom_pack_ternary(B.expand.weight)), requant_dev(P, B.expand),
+                             dev(B.dw.weight), requant_dev(P, B.dw),
+                             dev(P.prom_pack_ternary(B.project.weight)), requant_dev(P, B.project),
+                             B.add_residual, ws)
+        y_host, _, _ = oracle.block(x_host, _tup(B.expand), _tup(B.dw), _tup(B.project), b.stride, B.add_residual)
+        torch.cuda.synchronize()
+        assert_same(y_dev.cpu().numpy(), y_host, f"full-size chain batch {n} {b.name}")
+        del ws
+        x_dev, x_host = y_dev, y_host
+    if n == 32:
+        assert all(one_kernel)
+    else:
+        assert one_kernel == [False] * 3 + [True] * 13
+
+
 def test_chain_replays_from_a_captured_graph(P):
     """The library's calls on a stream can be captured in a HIP graph (no allocation, no memset,
     no host synchronisation inside a call once a shape has run): the 16 prom_block calls of the

@@ -166,14 +166,21 @@ def test_block_shapes(P, shape):
 
 
 def test_block_forms_and_queries(P):
-    """What prom_block picks: mid-sized hidden tensors fused, small, large and deep ones not; the
-    fused kernel's own limits."""
+    """What prom_block picks: one kernel for deep blocks on small maps and for small problems, three
+    launches for large maps at a large batch; the limits of the two one-kernel forms."""
     assert P.prom_block_is_fused(64, 28, 28, 32, 192, 32, 1) and P.prom_block_is_fused(128, 28, 28, 32, 192, 64, 2)
-    assert not P.prom_block_is_fused(2, 9, 9, 16, 96, 16, 1) and P.prom_block_can_fuse(2, 9, 9, 16, 96, 16, 1)
+    assert P.prom_block_is_fused(128, 14, 14, 64, 384, 64, 1) and P.prom_block_is_fused(128, 7, 7, 160, 960, 320, 1)
+    assert P.prom_block_is_fused(2, 9, 9, 16, 96, 16, 1) and P.prom_block_can_fuse(2, 9, 9, 16, 96, 16, 1)
     assert not P.prom_block_is_fused(128, 112, 112, 16, 96, 24, 2) and P.prom_block_can_fuse(128, 112, 112, 16, 96, 24, 2)
+    assert P.prom_block_planes_applies(128, 112, 112, 16, 96, 24, 2)
     assert not P.prom_block_can_fuse(2, 14, 14, 64, 384, 64, 1)      # 6 chunks of hidden channels
+    assert P.prom_block_planes_applies(2, 14, 14, 64, 384, 64, 1)
     assert not P.prom_block_can_fuse(2, 7, 7, 32, 192, 320, 1)       # 320 output channels
+    assert P.prom_block_planes_applies(2, 7, 7, 32, 192, 320, 1)
     assert not P.prom_block_can_fuse(2, 7, 7, 12, 72, 16, 1)         # cin % 8 != 0
+    assert not P.prom_block_planes_applies(2, 7, 7, 12, 72, 16, 1)
+    assert not P.prom_block_planes_applies(1, 14, 14, 24, 168, 136, 1)  # hidden channels not a multiple of 16
+    assert not P.prom_block_planes_applies(1, 14, 14, 200, 1600, 200, 1)  # more than 192 input channels
     assert P.prom_block_can_fuse(1, 28, 28, 24, 144, 24, 1)          # 24 input channels: padded pixels
 
 
