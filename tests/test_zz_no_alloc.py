@@ -40,10 +40,11 @@ def _run_both(P, B):
 
 
 def test_noalloc_block_two_calls_second_smaller(P):
-    """Both shapes take the three-launch form (the one whose kernels use the scratch array): the
-    first has a hidden tensor of 384 channels, the second is smaller in every dimension, so it
-    finds the first call's bytes in the array."""
-    shapes = [(7001, 3, 14, 14, 64, 6, 64, 1), (7002, 2, 9, 7, 16, 6, 24, 2)]
+    """Both shapes take the three-launch form (the one whose kernels use the scratch array; their
+    hidden widths, 360 and 72 channels, are not a multiple of 16, which the one-kernel forms
+    need): the second is smaller in every dimension, so it finds the first call's bytes in the
+    array."""
+    shapes = [(7001, 3, 14, 14, 60, 6, 60, 1), (7002, 2, 9, 7, 12, 6, 24, 2)]
     for seed, n, h, w, cin, t, cout, stride in shapes:
         B = make_block(seed, n, h, w, cin, t, cout, stride, signed_x=True)
         assert not P.prom_block_is_fused(n, h, w, cin, cin * t, cout, stride)
