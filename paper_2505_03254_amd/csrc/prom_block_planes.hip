@@ -537,7 +537,7 @@ bool plan_planes(PlanesArgs &a, size_t &lds, int &grid, int &kse)
     for (int nw : {8, 12, 16}) {
         if (only_nw && nw != only_nw) continue;
         if (cout > 64 * nw) continue;
-        const double cpi = nw == 8 ? 4.6 : nw == 12 ? 4.2 : 4.0;
+        const double cpi = nw == 8 ? 4.9 : nw == 12 ? 4.45 : 3.95;  // measured: phases 1 and 2 of 14x14x384
         // few planes: spread the pixel tiles of a plane over wavefronts (about 3 units per wavefront)
         const int G = NP >= nw ? 1 : (3 * nw + NP - 1) / NP;
         for (int pad : {4, 0}) {
@@ -569,14 +569,13 @@ bool plan_planes(PlanesArgs &a, size_t &lds, int &grid, int &kse)
                         tpg3 = t;
                     }
                 }
-                // phases 1 and 2: the SIMDs share the units' instructions; the last unit of the
-                // slowest wavefront is the tail; spread planes pay a barrier and uneven halves
+                // phases 1 and 2: the SIMDs share the units' instructions (a wavefront that is done
+                // leaves its SIMD to the others, so uneven plane counts cost little); spread planes
+                // pay a barrier
                 const double per1 = 60.0 + ((nt1 + G - 1) / G) * (38.0 + 3.0 * kse);
                 const double per2 = 80.0 + ((nt2 + G - 1) / G) * 42.0;
                 const double units = (double)NP * G;
-                const double rounds12 = (double)((NP * G + nw - 1) / nw);
-                double work = cpi * (units * (per1 + per2) / 4.0 + (rounds12 * nw > units ? 0.5 * (per1 + per2) : 0.0)) +
-                              (nw / 4) * cpi * c3;
+                double work = cpi * units * (per1 + per2) / 4.0 + (nw / 4) * cpi * c3;
                 if (G > 1) work *= 1.15;
                 const int bands = (a.Ho + R - 1) / R;
                 const long long rounds = ((long long)a.N * bands + 255) / 256;
