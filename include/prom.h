@@ -96,12 +96,18 @@ int prom_requant_check(const prom_requant_t *rq, int channels, int cin, int *bad
  * workgroup).  row_waves = 2, 3 or 4 asks for the row-cooperative kernel: that many wavefronts
  * of a workgroup share a pixel group and write whole rows of 16*tiles_per_wave*row_waves
  * channels together; it needs tiles_per_wave in 1..6, pixel_tiles 0 or 1 and
- * cout % (16*tiles_per_wave*row_waves) == 0 (and, like the fast path in general, cin % 8 == 0). */
+ * cout % (16*tiles_per_wave*row_waves) == 0 (and, like the fast path in general, cin % 8 == 0).
+ * k_outer = 1 asks for the kernel of wide layers (the k loop outermost over a workgroup tile of 128
+ * output channels x 256 pixels, weights decoded per k step): it needs cin % 64 == 0,
+ * cout % 16 == 0, 16-byte aligned x, y, residual, 8-byte aligned packed weights and every other
+ * field zero; k_outer = -1 keeps it off; 0 leaves the choice to the library (it takes this kernel
+ * from 1024 input and 256 output channels on). */
 typedef struct {
     int32_t tiles_per_wave;  /* NT: 16-channel output tiles each wavefront owns (1..10)       */
     int32_t pixel_tiles;     /* PT: 16-pixel tiles a wavefront processes per iteration (1,2,4)*/
     int32_t workgroups;      /* workgroups launched per output-channel chunk (per row piece)  */
     int32_t row_waves;       /* 0, 2, 3 or 4: wavefronts per pixel group, see above           */
+    int32_t k_outer;         /* 1: the kernel of wide layers, -1: never, 0: library default   */
 } prom_pw_plan_t;
 
 /* ---- ternary weight packing (host side, once per layer: the paper notes that weights are

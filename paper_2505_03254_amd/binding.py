@@ -45,7 +45,7 @@ class _DwLayerC(ctypes.Structure):
 
 class _PlanC(ctypes.Structure):
     _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
-                ("workgroups", ctypes.c_int32), ("row_waves", ctypes.c_int32)]
+                ("workgroups", ctypes.c_int32), ("row_waves", ctypes.c_int32), ("k_outer", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -192,9 +192,10 @@ class PwPlan:
     pixel_tiles: int = 0
     workgroups: int = 0
     row_waves: int = 0
+    k_outer: int = 0
 
     def _c(self) -> _PlanC:
-        return _PlanC(self.tiles_per_wave, self.pixel_tiles, self.workgroups, self.row_waves)
+        return _PlanC(self.tiles_per_wave, self.pixel_tiles, self.workgroups, self.row_waves, self.k_outer)
 
 
 def _stream_ptr(stream) -> int:
@@ -556,7 +557,7 @@ def prom_pw_plan_query(n: int, h: int, w: int, cin: int, cout: int) -> dict:
     _check(load_library().prom_pw_plan_query(n, h, w, cin, cout, ctypes.byref(p), ctypes.byref(lb)),
            "prom_pw_plan_query")
     return {"tiles_per_wave": p.tiles_per_wave, "pixel_tiles": p.pixel_tiles,
-            "workgroups": p.workgroups, "row_waves": p.row_waves, "load_bytes": lb.value}
+            "workgroups": p.workgroups, "row_waves": p.row_waves, "k_outer": p.k_outer, "load_bytes": lb.value}
 
 
 def prom_pw_batch_class(n: int, h: int, w: int, cin: int, cout: int) -> int:

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 BUILD_DIR = os.path.join(_HERE, "_build")
 LIB_PATH = os.path.join(_HERE, "libprom.so")
-SOURCES = ["prom_host.cpp", "prom_pw.hip", "prom_pw_rows.hip", "prom_pw_big.hip", "prom_pw_addsub.hip", "prom_dw.hip", "prom_gconv.hip", "prom_block.hip", "prom_block_planes.hip", "prom_dwproj.hip", "prom_quant.hip", "prom_pw_dynq.hip", "prom_bench.hip"]
+SOURCES = ["prom_host.cpp", "prom_pw.hip", "prom_pw_rows.hip", "prom_pw_big.hip", "prom_pw_gemm.hip", "prom_pw_addsub.hip", "prom_dw.hip", "prom_gconv.hip", "prom_block.hip", "prom_block_planes.hip", "prom_dwproj.hip", "prom_quant.hip", "prom_pw_dynq.hip", "prom_bench.hip"]
 PW_MAX_NT = 10  # prom_pw_inst.hip is compiled once per NT = 1..PW_MAX_NT (kMaxNT in prom_pw_stream.h)
 
 HIPCC_FLAGS = [

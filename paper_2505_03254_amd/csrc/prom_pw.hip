@@ -2,8 +2,10 @@
 // C entry points) and the generic any-shape kernel.  The streaming kernel lives in
 // prom_pw_stream.h and is instantiated per NT in prom_pw_inst.hip.
 #include "prom_pw_batch.h"
+#include "prom_pw_gemm.h"
 #include "prom_launch.h"
 
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -266,6 +268,7 @@ struct PwLaunch {
     bool rows;  // row-cooperative kernel (a.cw != 0)
     int big_body;  // body of pw_bigbatch_kernel that runs this plan, or -1
     int mode;
+    bool gemm;  // the kernel of wide layers (k loop outermost); never a member of a shared launch
 };
 
 // Validate the arguments and fill the launch description.  mode: 0 = requantised int8
@@ -431,6 +434,44 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     const long long total = wgs * a.n_chunks;
     if (total > (1LL << 30)) return PROM_EUNSUPPORTED;
     L.grid = (int)((total + 7) / 8 * 8);
+
+    // Wide layers: the kernel with the k loop outermost.  With a thousand input channels the decoded
+    // weights of all k steps fit LDS only for two to four channel tiles per chunk, and every chunk
+    // streams the activations again; the tile kernel decodes per k step and does 32 MFMAs per 4
+    // activation loads.  Measured (batch 128, one launch per layer, cache-cold, us against the
+    // streaming kernel): 14x14 1024 -> 512 33 against 37, 1024 -> 1024 56 against 63; 7x7
+    // 1024 -> 2048 31 against 36, 2048 -> 1024 32 against 58.  With 512 and fewer input channels the
+    // streaming kernel is the faster one (14x14 512 -> 1024 26 against 43 us, 28x28 512 -> 512 45
+    // against 76), so the library takes the tile kernel from 1024 input channels on.
+    L.gemm = false;
+    const int k_outer = plan ? plan->k_outer : 0;
+    if (k_outer != 0 && k_outer != 1 && k_outer != -1) return PROM_EINVAL;
+    const bool aligned16 = shape_only || ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)residual) & 15) == 0 &&
+                                          ((uintptr_t)w_packed & 7) == 0);
+    const bool gemm_ok = fast && cin % 64 == 0 && cout % 16 == 0 && aligned16;
+    if (k_outer == 1) {
+        if (!gemm_ok || plan->tiles_per_wave || plan->pixel_tiles || plan->row_waves || plan->workgroups)
+            return PROM_EINVAL;
+    }
+    const bool explicit_stream = plan && (plan->tiles_per_wave || plan->pixel_tiles || plan->row_waves);
+    if (gemm_ok && (k_outer == 1 || (k_outer == 0 && !explicit_stream && cin >= 1024 && cout >= 256))) {
+        L.gemm = true;
+        L.rows = false;
+        a.cw = 0;
+        L.nt = 8;
+        L.pt = 4;
+        L.xmode = 16;
+        L.threads = 256;
+        L.lds = pw_gemm_lds_bytes();
+        L.fn = pw_gemm_select(a.mult_neg != nullptr);
+        L.big_body = -1;
+        a.n_chunks = (cout + 127) / 128;
+        a.units = (int)((M + 63) / 64);
+        a.wg_per_chunk = (int)((M + 255) / 256);
+        const long long tot = (long long)a.n_chunks * a.wg_per_chunk;
+        if (tot > (1LL << 30)) return PROM_EUNSUPPORTED;
+        L.grid = (int)((tot + 7) / 8 * 8);
+    }
     return PROM_OK;
 }
 
@@ -496,6 +537,7 @@ extern "C" int prom_pw_plan_query(int n, int h, int w, int cin, int cout, prom_p
     plan_out->pixel_tiles = L.pt;
     plan_out->workgroups = L.a.wg_per_chunk;
     plan_out->row_waves = L.a.cw;
+    plan_out->k_outer = L.gemm ? 1 : 0;
     if (load_bytes_out) *load_bytes_out = L.xmode;
     return PROM_OK;
 }
@@ -511,7 +553,7 @@ constexpr long long kBatchBytesPerWg = 256LL << 10;  // bytes the first workgrou
 static bool batchable(const PwLaunch &L)
 {
     const PwArgs &a = L.a;
-    if (!L.fast || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
+    if (!L.fast || L.gemm || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
     if (batch_nt(a) * a.KS * 1024 > kLdsBudget) return false;
     return (long long)a.M * (a.K + a.Nc) <= kBatchMaxBytes;
 }
@@ -716,7 +758,7 @@ constexpr long long kBigBytesPerWg = 768LL << 10;  // measured best of 128 KB ..
 constexpr double kBigWgMicros = 60.0;              // workgroup time aimed at where the body's speed is known
 static bool big_batchable(const PwLaunch &L)
 {
-    return L.fast && L.mode == 0 && L.big_body >= 0 && !batchable(L) && L.lds <= (size_t)kLdsBudget;
+    return L.fast && !L.gemm && L.mode == 0 && L.big_body >= 0 && !batchable(L) && L.lds <= (size_t)kLdsBudget;
 }
 
 static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
