@@ -251,7 +251,7 @@ def main():
     torch.cuda.synchronize()
     # Events bracket the dominant launch on every EVENT_EVERY-th timed step only: a pair of event
     # records costs the step about 6 us (measured: 229 us with them on every step, 223 without).
-    EVENT_EVERY = 4
+    EVENT_EVERY = 10
     events = []
     t0 = time.perf_counter()
     for k in range(args.steps):
