@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the depthwise / block legs")
     ap.add_argument("--dw-only", action="store_true",
                     help="run the depthwise sweep leg alone and print its record (for profiling)")
+    ap.add_argument("--chain-only", action="store_true",
+                    help="run the 17-block chain leg alone and print its record (for profiling)")
     ap.add_argument("--dw-filter", default=None,
                     help="with --dw-only: HW,C,STRIDE of the one depthwise layer to run, e.g. 56,144,1")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
@@ -116,6 +118,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.ab:
         print(json.dumps(ab_study(P, torch, dev, args.ab, args.batch)), flush=True)
+        return
+    if args.chain_only:
+        print(json.dumps(chain_leg(P, torch, dev, args.batch, log)), flush=True)
         return
     if args.dw_only:
         only = tuple(int(v) for v in args.dw_filter.split(",")) if args.dw_filter else None
@@ -730,46 +735,14 @@ def depthwise_leg(P, torch, dev, batch, log, only=None):
     return res
 
 
-def extra_legs(P, torch, dev, batch, log):
-    """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
+def chain_leg(P, torch, dev, batch, log):
+    """The 17 inverted-residual blocks of MobileNetV2 in network order (4 stride-2 depthwise layers),
+    each fed with the previous block's output, at `batch` and at batch 8 (also replayed from a HIP
+    graph); block 1 (no expansion) is a depthwise + a projection call."""
     import numpy as np
-    from workloads import make_dw_layer, make_block, mobilenetv2_depthwise_layers
-    out = {"depthwise_sweep": depthwise_leg(P, torch, dev, batch, log)}
-
-    B = make_block(SEED + 2000, 64, 28, 28, 32, 6)
-    e, d, p = B.expand, B.dw, B.project
+    from workloads import make_dw_layer, make_pw_layer, make_block, mobilenetv2_blocks
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    rqs = [P.Requant(t(l.bias), t(l.mult), t(l.shift), l.act_min, l.act_max) for l in (e, d, p)]
-    ws = torch.empty(P.prom_block_workspace_size(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
-                     dtype=torch.int8, device=dev)
-    # rotate over enough input/output sets that the footprint between reuses exceeds the cache
-    xs = [t(B.x) for _ in range(8)]
-    ys = [torch.empty_like(xs[0]) for _ in range(8)]
-    we, wd, wp = t(P.prom_pack_ternary(e.weight)), t(d.weight), t(P.prom_pack_ternary(p.weight))
-
-    def run(i):
-        P.prom_block(xs[i % 8], B.chid, B.cout, 1, we, rqs[0], wd, rqs[1], wp, rqs[2], True, ws, ys[i % 8])
-    for i in range(8):
-        run(i)
-    torch.cuda.synchronize()
-    reps = 40
-    t0 = time.perf_counter()
-    for i in range(reps):
-        run(i)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
-    m = B.n * B.h * B.w
-    compulsory = m * (B.cin + B.cout)
-    out["block_config4"] = {"us": round(dt * 1e6, 1),
-                            "fused": P.prom_block_is_fused(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
-                            "compulsory_gbs": round(compulsory / dt / 1e9, 1),
-                            "pw_gops": round(2 * m * B.cin * B.chid * 2 / dt / 1e9, 1)}
-    log(f"[bench] block (config 4): {dt * 1e6:.1f} us per call")
-    del xs, ys
-
-    # the whole body as a chain: 17 blocks in network order (4 stride-2 depthwise layers), each fed
-    # with the previous block's output; block 1 (no expansion) is a depthwise + a projection call
-    from workloads import make_pw_layer, mobilenetv2_blocks
+    out = {}
 
     def time_chain(batch):
         blocks = mobilenetv2_blocks()
@@ -839,6 +812,58 @@ def extra_legs(P, torch, dev, batch, log):
 
     dt, fused, io_bytes, mid_bytes, _g = time_chain(batch)
     dt8, fused8, _io8, _mid8, dt8_graph = time_chain(8)
+    out["block_chain_batch8"] = {"us": round(dt8 * 1e6, 1), "us_as_hip_graph": round(dt8_graph * 1e6, 1),
+                                 "one_kernel_blocks": fused8}
+    log(f"[bench] 17-block chain at batch 8: {dt8 * 1e6:.1f} us per pass, {dt8_graph * 1e6:.1f} us replayed from a "
+        f"HIP graph; one kernel: {', '.join(fused8)}")
+    out["block_chain"] = {"blocks": 17, "us": round(dt * 1e6, 1), "one_kernel_blocks": fused,
+                          "block_io_mb": round(io_bytes / 1e6, 1),
+                          "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),
+                          "gbs_incl_intermediates": round((io_bytes + mid_bytes) / dt / 1e9, 1),
+                          "frac_hbm_roofline_of_block_io": round(io_bytes / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    log(f"[bench] 17-block chain: {dt * 1e6:.1f} us per pass, one kernel: {', '.join(fused)}; "
+        f"{io_bytes / 1e6:.0f} MB block inputs+outputs, {mid_bytes / 1e6:.0f} MB intermediates of unfused blocks")
+    return out
+
+
+def extra_legs(P, torch, dev, batch, log):
+    """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
+    import numpy as np
+    from workloads import make_dw_layer, make_block, mobilenetv2_depthwise_layers
+    out = {"depthwise_sweep": depthwise_leg(P, torch, dev, batch, log)}
+
+    B = make_block(SEED + 2000, 64, 28, 28, 32, 6)
+    e, d, p = B.expand, B.dw, B.project
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rqs = [P.Requant(t(l.bias), t(l.mult), t(l.shift), l.act_min, l.act_max) for l in (e, d, p)]
+    ws = torch.empty(P.prom_block_workspace_size(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
+                     dtype=torch.int8, device=dev)
+    # rotate over enough input/output sets that the footprint between reuses exceeds the cache
+    xs = [t(B.x) for _ in range(8)]
+    ys = [torch.empty_like(xs[0]) for _ in range(8)]
+    we, wd, wp = t(P.prom_pack_ternary(e.weight)), t(d.weight), t(P.prom_pack_ternary(p.weight))
+
+    def run(i):
+        P.prom_block(xs[i % 8], B.chid, B.cout, 1, we, rqs[0], wd, rqs[1], wp, rqs[2], True, ws, ys[i % 8])
+    for i in range(8):
+        run(i)
+    torch.cuda.synchronize()
+    reps = 40
+    t0 = time.perf_counter()
+    for i in range(reps):
+        run(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    m = B.n * B.h * B.w
+    compulsory = m * (B.cin + B.cout)
+    out["block_config4"] = {"us": round(dt * 1e6, 1),
+                            "fused": P.prom_block_is_fused(B.n, B.h, B.w, B.cin, B.chid, B.cout, 1),
+                            "compulsory_gbs": round(compulsory / dt / 1e9, 1),
+                            "pw_gops": round(2 * m * B.cin * B.chid * 2 / dt / 1e9, 1)}
+    log(f"[bench] block (config 4): {dt * 1e6:.1f} us per call")
+    del xs, ys
+
+    out.update(chain_leg(P, torch, dev, batch, log))
 
     # weight preparation: float32 weights of all 34 pointwise and 17 depthwise layers through the
     # device quantisers (ternary absmean straight into the packed layout, 8-bit absmax)
@@ -919,17 +944,6 @@ def extra_legs(P, torch, dev, batch, log):
     log(f"[bench] layer with fused dynamic activation scale (24->144 at 56x56): {df * 1e6:.1f} us, "
         f"{algf / df / 1e9:.0f} GB/s algorithmic ({100 * algf / df / 1e9 / HBM_PEAK_GBS:.1f} % of the HBM roofline)")
     del xf, qf
-
-    out["block_chain_batch8"] = {"us": round(dt8 * 1e6, 1), "us_as_hip_graph": round(dt8_graph * 1e6, 1),
-                                 "fused_blocks": fused8}
-    log(f"[bench] 17-block chain at batch 8: {dt8 * 1e6:.1f} us per pass, {dt8_graph * 1e6:.1f} us replayed from a "
-        f"HIP graph; fused: {', '.join(fused8)}")
-    out["block_chain"] = {"blocks": 17, "us": round(dt * 1e6, 1), "fused_blocks": fused,
-                          "block_io_mb": round(io_bytes / 1e6, 1),
-                          "intermediate_traffic_of_unfused_blocks_mb": round(mid_bytes / 1e6, 1),
-                          "gbs_incl_intermediates": round((io_bytes + mid_bytes) / dt / 1e9, 1)}
-    log(f"[bench] 17-block chain: {dt * 1e6:.1f} us per pass, fused: {', '.join(fused)}; "
-        f"{io_bytes / 1e6:.0f} MB block inputs+outputs, {mid_bytes / 1e6:.0f} MB intermediates of unfused blocks")
 
     # grouped 3x3 convolutions of RegNetX-400MF and ResNeXt-50 32x4d at the same batch
     from workloads import make_gconv_layer, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers

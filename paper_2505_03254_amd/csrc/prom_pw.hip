@@ -6,6 +6,7 @@
 #include "prom_launch.h"
 
 #include <cstdlib>
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -716,24 +717,35 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     b.count = count;
     size_t lds = 0;
     int start = 0;
-    // Work of a member = bytes its chunks move (activations are read once per chunk).  Workgroups
-    // are dispatched in table order: the first ones get large pieces (each workgroup pays one cold
-    // round trip for its weights and first loads before it streams), the last ones small pieces so
-    // that the chip drains evenly at the end of the launch.
+    // Work of a member = bytes its chunks move (activations are read once per chunk).  The members
+    // are independent, so their order in the table is the library's: ascending by work.  The smallest
+    // layers are bound by latency (every workgroup pays 2 to 4 us for its weights before it moves
+    // 64 to 256 KB); dispatched last they leave the memory system idle while the launch drains,
+    // dispatched first their latencies hide behind the streaming layers that follow (the MobileNetV2
+    // sweep at batch 128: 213.6 us per step against 221.5 in network order, where the 7x7 layers
+    // come last; descending order 222.7).  Workgroups are dispatched in table order: the first ones
+    // get large pieces (each workgroup pays one cold round trip for its weights and first loads
+    // before it streams), the last ones small pieces so that the chip drains evenly at the end of
+    // the launch.
     long long total_work = 0, done_work = 0;
+    int order[kMaxBatch];
     for (int i = 0; i < count; ++i) {
         plan_small_shape(*members[i], plans[i]);
         total_work += plans[i].work * plans[i].a.n_chunks;
+        order[i] = i;
     }
-    for (int i = 0; i < count; ++i) {
-        SmallPlan &sp = plans[i];
+    std::stable_sort(order, order + count, [&](int p, int q) {
+        return plans[p].work * plans[p].a.n_chunks < plans[q].work * plans[q].a.n_chunks;
+    });
+    for (int k = 0; k < count; ++k) {
+        SmallPlan &sp = plans[order[k]];
         const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
                                  : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
                                                                    : kBatchBytesPerWg / 4;
         done_work += sp.work * sp.a.n_chunks;
         const int nblk = size_small_member(sp, per_wg);
-        b.layer[i] = sp.a;
-        b.start[i] = start;
+        b.layer[k] = sp.a;
+        b.start[k] = start;
         start += nblk;
         if (sp.lds > lds) lds = sp.lds;
     }
