@@ -115,6 +115,37 @@ def test_argument_errors_are_reported_before_any_launch(P):
     assert P.prom_block_workspace_size(1, 8, 8, 16, 96, 16, 3) == 0
 
 
+def test_host_side_queries_of_the_launch_forms(P):
+    """The planning queries run on the host alone: which form prom_block takes, where the two
+    one-kernel forms apply, and where prom_pw_conv takes the kernel for wide layers."""
+    # plane-resident block kernel: hidden channels a multiple of 16, cin % 8 == 0 and <= 192, cout % 4 == 0
+    assert P.prom_block_planes_applies(128, 14, 14, 64, 384, 64, 1)
+    assert P.prom_block_planes_applies(1, 1, 1, 8, 16, 4, 1)
+    assert P.prom_block_planes_applies(2, 7, 7, 160, 960, 320, 2)
+    assert not P.prom_block_planes_applies(2, 7, 7, 12, 72, 16, 1)        # cin % 8
+    assert not P.prom_block_planes_applies(2, 7, 7, 16, 72, 16, 1)        # hidden % 16
+    assert not P.prom_block_planes_applies(2, 7, 7, 16, 96, 18, 1)        # cout % 4
+    assert not P.prom_block_planes_applies(2, 7, 7, 200, 1600, 200, 1)    # cin > 192
+    assert not P.prom_block_planes_applies(1, 4, 6000, 16, 96, 16, 1)     # rows wider than the kernel takes
+    with pytest.raises(P.PromError):
+        P.prom_block_planes_applies(0, 7, 7, 16, 96, 16, 1)
+    with pytest.raises(P.PromError):
+        P.prom_block_planes_applies(1, 7, 7, 16, 96, 16, 3)
+    # what prom_block picks: one kernel for deep blocks on small maps and for small problems
+    assert P.prom_block_is_fused(128, 14, 14, 96, 576, 96, 1)
+    assert P.prom_block_is_fused(8, 112, 112, 16, 96, 24, 2)
+    assert not P.prom_block_is_fused(128, 56, 56, 24, 144, 24, 1)
+    assert not P.prom_block_is_fused(4, 14, 14, 60, 360, 60, 1)
+    # pointwise plans: the kernel for wide layers from 1024 input and 256 output channels on
+    q = P.prom_pw_plan_query(128, 7, 7, 2048, 1024)
+    assert q["k_outer"] == 1
+    assert P.prom_pw_plan_query(128, 7, 7, 1024, 128)["k_outer"] == 0
+    assert P.prom_pw_plan_query(128, 14, 14, 960, 320)["k_outer"] == 0
+    assert P.prom_pw_plan_query(128, 14, 14, 1032, 512)["k_outer"] == 0   # cin % 64
+    # wide layers never join a shared launch
+    assert P.prom_pw_batch_class(16, 7, 7, 1024, 512) == 0
+
+
 def test_binding_fails_loudly_without_library(P, monkeypatch):
     import paper_2505_03254_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
