@@ -446,19 +446,37 @@ __global__ __launch_bounds__(64 * NW, 1) void block_planes_kernel(const PlanesAr
             for (int i = 0; i < TPG; ++i) acc[i] = zero4;
             const unsigned char *bq = t2 + (pt0 * 16 + j) * 16;
             const uint32_t *wrow = w3l + (16 * ct + j) * S3;
-            for (int gi = 0; gi < ng3; ++gi) {
-                const int wo = 16 * gi + 4 * g;
+            // One k step ahead: the B operands of the next step and the codes of the next group are
+            // on their way while this step's codes are decoded and its MFMAs issue.  Steps past the
+            // last plane read the last plane against zero codes (the rows are zero-padded to R4 and
+            // groups past R4 take zeros), the reads past the last step go nowhere.
+            auto load_b = [&](v4i(&B)[TPG], int plane) __attribute__((always_inline)) {
+                const unsigned char *bp = bq + min(plane, NP - 1) * slot2;
+#pragma unroll
+                for (int i = 0; i < TPG; ++i) B[i] = *reinterpret_cast<const v4i *>(bp + i * 256);
+            };
+            auto load_w = [&](int wo) __attribute__((always_inline)) {
                 v4i wv = *reinterpret_cast<const v4i *>(wrow + min(wo, R4 - 4));
                 if (wo >= R4) wv = zero4;
+                return wv;
+            };
+            v4i Bn[TPG];
+            load_b(Bn, 4 * g);
+            v4i wn = load_w(4 * g);
+            for (int gi = 0; gi < ng3; ++gi) {
+                const int wo = 16 * gi + 4 * g;
+                const v4i wv = wn;
+                wn = load_w(wo + 16);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (16 * gi + e < KWp) {
-                        const v4i A = decode_word((uint32_t)wv[e]);
-                        const unsigned char *bp = bq + min(wo + e, NP - 1) * slot2;
+                    v4i Bc[TPG];
 #pragma unroll
-                        for (int i = 0; i < TPG; ++i)
-                            acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, *reinterpret_cast<const v4i *>(bp + i * 256), acc[i], 0, 0, 0);
-                    }
+                    for (int i = 0; i < TPG; ++i) Bc[i] = Bn[i];
+                    load_b(Bn, e < 3 ? wo + e + 1 : wo + 16);
+                    const v4i A = decode_word((uint32_t)wv[e]);
+#pragma unroll
+                    for (int i = 0; i < TPG; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, Bc[i], acc[i], 0, 0, 0);
                 }
             }
             const int c = 16 * ct + 4 * g;
