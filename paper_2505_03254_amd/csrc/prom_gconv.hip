@@ -188,6 +188,9 @@ struct GconvBand {
     int bands;       // bands per image
     int G;           // images per unit of work (above 1 only when a band is the whole image)
     int units;       // units of work per channel block
+    // floor(2^31 / d) + 1 for d = Wo and d = R * Wo: n / d = (n * this) >> 31 for every n with
+    // n * d < 2^31 (the pixels of a unit are a few thousand at most)
+    unsigned magic_wo, magic_img;
 };
 
 constexpr int kGconvFragBytes = 4 * 9 * 64 * 16;
@@ -391,6 +394,272 @@ __global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, c
         run(std::false_type{});
 }
 
+// ---- gconv_tapk_kernel: group sizes 4, 8, 16 with the kernel taps in the k dimension -------------
+// A tile of 16 output channels of such a layer sees only the 16 input channels at the same
+// positions (its groups lie inside them), so its contraction is 9 taps x 16 channels = 144 long:
+// three k steps of v_mfma_i32_16x16x64_i8 in which k group kg of step s is tap 4s + kg (taps 9..11
+// have zero weights), instead of the nine of the kernel above, and 12 KB of fragments per block of
+// 64 channels instead of 36.  The B operand of a lane is then the 16-byte piece `t` of the pixel
+// under its tap, so the band is staged as four planes of 16-byte pieces ([piece][pixel]): lanes of
+// consecutive pixels read consecutive pieces.  Tile t holds channels 16t .. 16t+15 in their own
+// order; a lane's four dwords (one per tile) are exchanged between the four lanes of a pixel with
+// two pairs of lane-row swaps, after which lane (j, g) holds channels 16g .. 16g+15 of its pixel
+// and stores them as one 16-byte piece, as above.  Band geometry, staging through registers and
+// units of work are those of gconv_mfma_kernel.
+#ifdef PROM_TIMELINE
+// Developer build: workgroups 0 .. 255 record the 100 MHz clock at entry, after the prologue and
+// per band (pieces in LDS, barrier passed, band computed), then after the last store is acknowledged.
+__device__ unsigned long long g_gc_stamps[256 * 16];
+#define GC_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 256 && (i) < 16) g_gc_stamps[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define GC_STAMP(i) do { } while (0)
+#endif
+
+constexpr int kTapkFragBytes = 4 * 3 * 64 * 16;
+constexpr int kTapkParBytes = kGconvParBytes + 16;  // the parameters and the flag of the epilogue form
+constexpr int kTapkPT = 2;          // pixel tiles per wavefront iteration
+constexpr int kTapkThreads = 256;   // 4 wavefronts, two workgroups per compute unit
+constexpr int kTapkPieces = 9;      // 16-byte pieces of a staged band per thread
+
+// Rows of 16 lanes, registers o[0..3]: o[t] of row g  <->  o[g] of row t.
+__device__ __forceinline__ void transpose_rows4(uint32_t (&o)[4])
+{
+    // rows 2, 3 of o[t] <-> rows 0, 1 of o[t + 2]: the off-diagonal 2x2 blocks change places
+    auto a02 = __builtin_amdgcn_permlane32_swap(o[0], o[2], false, false);
+    auto a13 = __builtin_amdgcn_permlane32_swap(o[1], o[3], false, false);
+    // rows 1, 3 of the first <-> rows 0, 2 of the second: each 2x2 block is transposed
+    auto b01 = __builtin_amdgcn_permlane16_swap(a02[0], a13[0], false, false);
+    auto b23 = __builtin_amdgcn_permlane16_swap(a02[1], a13[1], false, false);
+    o[0] = b01[0];
+    o[1] = b01[1];
+    o[2] = b23[0];
+    o[3] = b23[1];
+}
+
+template <int PT>
+__global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const GconvArgs a, const GconvBand bd)
+{
+    constexpr int kFlags = 0x00020000;
+    constexpr int kOob = 0x7ffff000;
+    constexpr int NK = kTapkPieces;
+    constexpr int NT = kTapkThreads;
+    extern __shared__ __align__(16) unsigned char lds[];
+    v4i *frag = reinterpret_cast<v4i *>(lds);                                  // [tile t][step s][lane]
+    v4i *lpar = reinterpret_cast<v4i *>(lds + kTapkFragBytes);                 // [64] parameters, then a flag
+    unsigned char *xt = lds + kTapkFragBytes + kTapkParBytes;                  // [piece 4][G][RI][W+2][16]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15, g = lane >> 4;
+    const int cb = blockIdx.x % bd.ncb;
+    const int wg = blockIdx.x / bd.ncb;
+    const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
+    const int W2 = W + 2;
+    const int cbase = cb * 64;
+    const bool prelu = a.mult_neg != nullptr;
+    const int row_items = W2 * 4;
+    const int img_items = bd.RI * row_items;
+    const int PS = bd.G * bd.RI * W2 * 16;  // bytes of a plane of pieces
+    GC_STAMP(0);
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a.x), 0, a.N * a.H * W * C, kFlags);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.N * a.Ho * Wo * C, kFlags);
+
+    struct Unit { int img0, count, ro0, rows_out; };
+    auto unit_of = [&](int u) {
+        Unit q;
+        if (bd.G > 1) {
+            q.img0 = u * bd.G;
+            q.count = min(bd.G, a.N - q.img0);
+            q.ro0 = 0;
+        } else {
+            q.img0 = u / bd.bands;
+            q.count = 1;
+            q.ro0 = (u - q.img0 * bd.bands) * bd.R;
+        }
+        q.rows_out = min(bd.R, a.Ho - q.ro0);
+        return q;
+    };
+    // piece pc of a unit = piece (pc & 3) of staged pixel pc >> 2 (images, rows, columns in order)
+    v4i piece[NK];
+    auto fetch_band = [&](int u) {
+        const Unit q = unit_of(u);
+        const int ri0 = q.ro0 * S - 1;
+        const int npiece = q.count * img_items;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+            const int pc = k * NT + tid;
+            const int gi = pc / img_items;
+            const int rem = pc - gi * img_items;
+            const int row = rem / row_items;
+            const int it = rem - row * row_items;
+            const int col = it >> 2, qd = it & 3;
+            const int iy = ri0 + row;
+            const bool ok = pc < npiece && iy >= 0 && iy < a.H && col >= 1 && col <= W && cbase + 16 * qd < C;
+            const int off = (((q.img0 + gi) * a.H + iy) * W + col - 1) * C + cbase + 16 * qd;
+            piece[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off : kOob, 0, 0);
+        }
+    };
+    // the first band is requested before anything else: one memory latency for it, the weights and
+    // the parameters together
+    if (wg < bd.units) fetch_band(wg);
+    // ---- fragments: lane (i, kg) of tile t, step s holds, for output channel 16t + i of the block and
+    // tap 4s + kg, the weights on input channels 16t .. 16t+15 (zero outside the channel's group)
+    if (a.wfrag) {
+        const v4i *src = a.wfrag + (long long)cb * (4 * 3 * 64);
+        for (int idx = tid; idx < 4 * 3 * 64; idx += NT) frag[idx] = src[idx];
+    } else
+    for (int idx = tid; idx < 4 * 3 * 64; idx += NT) {
+        const int l = idx & 63, ts = idx >> 6, s = ts % 3, t = ts / 3;
+        const int i = l & 15, kg = l >> 4;
+        const int tap = 4 * s + kg;
+        const int oc = cbase + 16 * t + i;
+        v4i e = {0, 0, 0, 0};
+        if (oc < C && tap < 9) {
+            const int gfirst = (oc / GS) * GS;
+            const int8_t *wrow = a.w + ((long long)tap * C + oc) * GS;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int ic = cbase + 16 * t + 4 * d;
+                if (ic >= gfirst && ic < gfirst + GS) e[d] = *reinterpret_cast<const int *>(wrow + (ic - gfirst));
+            }
+        }
+        frag[idx] = e;
+    }
+    if (tid < 64) {
+        const int c = cbase + tid;
+        int shift = 1;
+        v4i p = {0, 0, 0, 1};
+        if (c < C) {
+            shift = a.shift[c];
+            p = requant_params(a.bias[c], a.mult[c], prelu ? a.mult_neg[c] : 0, shift, prelu);
+        }
+        lpar[tid] = p;
+        // every shift of the block >= 1 (the usual case): the quotient comes from the high half of the
+        // 64-bit sum and one 32-bit shift by shift - 1
+        const bool all_ge1 = __builtin_amdgcn_ballot_w64(shift >= 1) == ~0ull;
+        if (tid == 0) *reinterpret_cast<int *>(lpar + 64) = all_ge1 ? 1 : 0;
+    }
+    __syncthreads();
+
+    const bool general = prelu || __builtin_amdgcn_readfirstlane(*reinterpret_cast<const int *>(lpar + 64)) == 0;
+    v4i par[4][4];  // [tile t][r]: channel 16t + 4g + r; the fast form shifts by shift - 1
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            par[t][r] = lpar[16 * t + 4 * g + r];
+            if (!general) par[t][r][3] -= 1;
+        }
+    GC_STAMP(1);
+    int band_no = 0;
+    const bool full_block = cbase + 64 <= C;
+    // n / d by the band's magic numbers
+    auto div_wo = [&](int n) { return (int)(((unsigned long long)(unsigned)n * bd.magic_wo) >> 31); };
+    auto div_img = [&](int n) { return (int)(((unsigned long long)(unsigned)n * bd.magic_img) >> 31); };
+    const int lo = in_vgpr(a.lo), hi = in_vgpr(a.hi);
+    const int cl = cbase + 16 * g;  // the lane's first output channel after the exchange
+    int toff[3];                    // the lane's tap of each k step, as a byte offset in a plane
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        const int tap = min(4 * s + g, 8);
+        toff[s] = ((tap / 3) * W2 + tap % 3) * 16;
+    }
+
+    auto run = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        for (int u = wg; u < bd.units; u += bd.wgs_per_cb) {
+            const Unit q = unit_of(u);
+            const int npiece = q.count * img_items;
+            __syncthreads();  // the readers of the previous band are done
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int pc = k * NT + tid;
+                if (pc < npiece) *reinterpret_cast<v4i *>(xt + (pc & 3) * PS + (pc >> 2) * 16) = piece[k];
+            }
+            GC_STAMP(2 + 3 * band_no);
+            __syncthreads();
+            GC_STAMP(3 + 3 * band_no);
+            if (u + bd.wgs_per_cb < bd.units) fetch_band(u + bd.wgs_per_cb);
+            const int img_pix = q.rows_out * Wo;
+            const int npix = q.count * img_pix;
+            const int ngrp = (npix + 16 * PT - 1) / (16 * PT);
+            for (int grp = wave; grp < ngrp; grp += NT / 64) {
+                int pix[PT], yo[PT];
+                bool valid[PT];
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    const int idx = (grp * PT + p) * 16 + j;
+                    valid[p] = idx < npix;
+                    const int ii = valid[p] ? idx : 0;
+                    // img_pix = R * Wo except in an image's last band, where a unit is one image and idx < img_pix
+                    const int gi = div_img(ii);
+                    const int rem = ii - gi * img_pix;
+                    const int r = div_wo(rem);
+                    const int ox = rem - r * Wo;
+                    pix[p] = ((gi * bd.RI + r * S) * W2 + ox * S) * 16;  // tap (0, 0) of the pixel
+                    yo[p] = (((q.img0 + gi) * a.Ho + q.ro0 + r) * Wo + ox) * C + cl;
+                }
+                v4i acc[PT][4];
+#pragma unroll
+                for (int p = 0; p < PT; ++p)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[p][t] = v4i{0, 0, 0, 0};
+                int fo = lane;
+                asm volatile("" : "+v"(fo));  // keeps the fragment reads inside the loop
+                const v4i *fl = frag + fo;
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const v4i wf = fl[(t * 3 + s) * 64];
+#pragma unroll
+                        for (int p = 0; p < PT; ++p) {
+                            const v4i b = *reinterpret_cast<const v4i *>(xt + t * PS + pix[p] + toff[s]);
+                            acc[p][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, b, acc[p][t], 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < PT; ++p) {
+                    uint32_t out[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        int v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = requant_mode<MODE>(acc[p][t][r], par[t][r], lo, hi);
+                        out[t] = pack4_low_bytes(v[0], v[1], v[2], v[3]);
+                    }
+                    transpose_rows4(out);  // now channels cl .. cl+15 of the lane's pixel
+                    if (full_block) {
+                        store_b128_guarded(v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]}, ry,
+                                           valid[p] ? yo[p] : kOob);
+                    } else if (valid[p]) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (cl + 4 * t < C)
+                                __builtin_amdgcn_raw_buffer_store_b32((int)out[t], ry, yo[p] + 4 * t, 0, 0);
+                    }
+                }
+            }
+            GC_STAMP(4 + 3 * band_no);
+            ++band_no;
+
+        }
+    };
+    if (prelu)
+        run(std::integral_constant<int, 2>{});
+    else if (general)
+        run(std::integral_constant<int, 1>{});
+    else
+        run(std::integral_constant<int, 0>{});
+#ifdef PROM_TIMELINE
+    __builtin_amdgcn_s_waitcnt(0);
+    GC_STAMP(15);
+#endif
+}
+
 // Any C, group size and alignment: one thread per output element.
 __global__ __launch_bounds__(256) void gconv_kernel_generic(const GconvArgs a)
 {
@@ -478,8 +747,9 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
     if (w_frag && ranges_overlap(y, ybytes, w_frag, prom_gconv_frag_size(c, group_size))) return PROM_EALIAS;
     if (mfma) {
         a.wfrag = static_cast<const v4i *>(w_frag);
-        // band height: as many output rows as keep the staged input rows within kBandBytes
-        constexpr int kBandBytes = kGconvPieces * 256 * 16;
+        // band height: as many output rows as keep the staged input rows within the band's bytes
+        const bool tapk = group_size <= 16;
+        const int kBandBytes = tapk ? kTapkPieces * kTapkThreads * 16 : kGconvPieces * 256 * 16;
         const int row_bytes = (w + 2) * 64;
         int ri = kBandBytes / row_bytes;
         if (ri < 3) {
@@ -489,6 +759,11 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
             bd.ncb = (c + 63) / 64;
             bd.R = (ri - 3) / stride + 1;
             if (bd.R > a.Ho) bd.R = a.Ho;
+            if (bd.R < a.Ho) {
+                // bands of equal height rather than a short last one
+                const int nb = (a.Ho + bd.R - 1) / bd.R;
+                bd.R = (a.Ho + nb - 1) / nb;
+            }
             bd.RI = (bd.R - 1) * stride + 3;
             bd.bands = (a.Ho + bd.R - 1) / bd.R;
             bd.G = 1;
@@ -504,18 +779,25 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
             }
             const long long units = bd.G > 1 ? ((long long)n + bd.G - 1) / bd.G : (long long)n * bd.bands;
             bd.units = (int)units;
+            const unsigned d_img = (unsigned)bd.R * (unsigned)a.Wo;
+            bd.magic_wo = (unsigned)((1ull << 31) / (unsigned)a.Wo) + 1u;
+            bd.magic_img = (unsigned)((1ull << 31) / d_img) + 1u;
             // two workgroups per compute unit, and not one more: a workgroup that does not fit in the
             // first round starts when another has finished all its units and doubles the run time
             long long per_cb = (2 * 256) / bd.ncb;
             if (per_cb > units) per_cb = units;
             if (per_cb < 1) per_cb = 1;
             bd.wgs_per_cb = (int)per_cb;
-            const size_t lds = (size_t)kGconvFragBytes + kGconvParBytes + (size_t)bd.G * bd.RI * row_bytes;
+            const size_t lds = (size_t)(tapk ? kTapkFragBytes + kTapkParBytes : kGconvFragBytes + kGconvParBytes) +
+                               (size_t)bd.G * bd.RI * row_bytes;
             static std::once_flag once;
             static hipError_t attr_err = hipSuccess;
             std::call_once(once, [] {
                 attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gconv_mfma_kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                if (attr_err == hipSuccess)  // both limits cover frag + parameters + the largest band
+                    attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gconv_tapk_kernel<kTapkPT>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
             });
             if (attr_err != hipSuccess) {
                 last_hip_error() = attr_err;
@@ -523,7 +805,10 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
                 return PROM_EHIP;
             }
             clear_hip_error();
-            hipLaunchKernelGGL(gconv_mfma_kernel, dim3((unsigned)(per_cb * bd.ncb)), dim3(256), lds, st, a, bd);
+            if (tapk)
+                hipLaunchKernelGGL((gconv_tapk_kernel<kTapkPT>), dim3((unsigned)(per_cb * bd.ncb)), dim3(kTapkThreads), lds, st, a, bd);
+            else
+                hipLaunchKernelGGL(gconv_mfma_kernel, dim3((unsigned)(per_cb * bd.ncb)), dim3(256), lds, st, a, bd);
             return check_launch();
         }
     }
@@ -540,3 +825,11 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
     }
     return check_launch();
 }
+
+#ifdef PROM_TIMELINE
+extern "C" int prom_debug_gc_stamps(unsigned long long *host)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return PROM_EHIP;
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(prom::g_gc_stamps), sizeof(unsigned long long) * 256 * 16) == hipSuccess ? PROM_OK : PROM_EHIP;
+}
+#endif

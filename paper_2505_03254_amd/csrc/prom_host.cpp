@@ -64,17 +64,23 @@ extern "C" int prom_unpack_ternary(const void *packed_host, size_t packed_bytes,
     return PROM_OK;
 }
 
-// ---- grouped 3x3 convolution: weights in the operand order of the matrix-core kernel ------------
-// [block of 64 channels][tile t: 4][tap s: 9][lane: 64] entries of 16 bytes.  Lane (i = lane & 15,
-// kg = lane >> 4) of tile t holds, for output channel oc = 64*block + 16*(i >> 2) + 4*t + (i & 3)
-// and tap s, the weights that multiply input channels 64*block + 16*kg + 0..15: w[s][oc][...] where
-// the input channel belongs to oc's group, zero elsewhere.
+// ---- grouped 3x3 convolution: weights in the operand order of the matrix-core kernels -----------
+// Group sizes 32 and 64: [block of 64 channels][tile t: 4][tap s: 9][lane: 64] entries of 16 bytes.
+// Lane (i = lane & 15, kg = lane >> 4) of tile t holds, for output channel
+// oc = 64*block + 16*(i >> 2) + 4*t + (i & 3) and tap s, the weights that multiply input channels
+// 64*block + 16*kg + 0..15: w[s][oc][...] where the input channel belongs to oc's group, zero
+// elsewhere.
+// Group sizes 4, 8 and 16 (a tile of 16 output channels sees the 16 input channels at the same
+// positions, so the taps go into the k dimension): [block][tile t: 4][step s: 3][lane: 64] entries.
+// Lane (i, kg) of tile t holds, for output channel oc = 64*block + 16*t + i and tap 4*s + kg, the
+// weights on input channels 64*block + 16*t + 0..15, zero outside oc's group and for taps 9..11.
 extern "C" size_t prom_gconv_frag_size(int c, int group_size)
 {
     if (c <= 0 || c % 4 != 0) return 0;
     if (group_size != 4 && group_size != 8 && group_size != 16 && group_size != 32 && group_size != 64) return 0;
     if (c % group_size != 0) return 0;
-    return (size_t)((c + 63) / 64) * 4 * 9 * 64 * 16;
+    const size_t per_block = group_size <= 16 ? 4 * 3 * 64 * 16 : 4 * 9 * 64 * 16;
+    return (size_t)((c + 63) / 64) * per_block;
 }
 
 extern "C" int prom_gconv_pack(const int8_t *w_host, int c, int group_size, void *frag_host, size_t frag_bytes)
@@ -86,19 +92,22 @@ extern "C" int prom_gconv_pack(const int8_t *w_host, int c, int group_size, void
     int8_t *out = static_cast<int8_t *>(frag_host);
     std::memset(out, 0, need);
     const int ncb = (c + 63) / 64;
+    const bool taps_in_k = group_size <= 16;
+    const int steps = taps_in_k ? 3 : 9;
     for (int cb = 0; cb < ncb; ++cb)
         for (int t = 0; t < 4; ++t)
-            for (int s = 0; s < 9; ++s)
+            for (int s = 0; s < steps; ++s)
                 for (int lane = 0; lane < 64; ++lane) {
                     const int i = lane & 15, kg = lane >> 4;
-                    const int oc = 64 * cb + 16 * (i >> 2) + 4 * t + (i & 3);
-                    if (oc >= c) continue;
+                    const int oc = taps_in_k ? 64 * cb + 16 * t + i : 64 * cb + 16 * (i >> 2) + 4 * t + (i & 3);
+                    const int tap = taps_in_k ? 4 * s + kg : s;
+                    if (oc >= c || tap >= 9) continue;
                     const int gfirst = (oc / group_size) * group_size;
-                    int8_t *e = out + ((((size_t)cb * 4 + t) * 9 + s) * 64 + lane) * 16;
+                    int8_t *e = out + ((((size_t)cb * 4 + t) * steps + s) * 64 + lane) * 16;
                     for (int b = 0; b < 16; ++b) {
-                        const int ic = 64 * cb + 16 * kg + b;
+                        const int ic = 64 * cb + 16 * (taps_in_k ? t : kg) + b;
                         if (ic >= gfirst && ic < gfirst + group_size)
-                            e[b] = w_host[((size_t)s * c + oc) * group_size + (ic - gfirst)];
+                            e[b] = w_host[((size_t)tap * c + oc) * group_size + (ic - gfirst)];
                     }
                 }
     return PROM_OK;
