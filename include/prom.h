@@ -323,6 +323,28 @@ int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c,
                   const int8_t *w_g, const void *w_frag, int group_size, int stride,
                   const prom_requant_t *rq, int8_t *y, void *stream);
 
+/* One layer of a sequence for prom_gconv3x3_sequence: the arguments of prom_gconv3x3. */
+typedef struct {
+    const int8_t *x;
+    int32_t n, h, w, c;
+    const int8_t *w_g;
+    const void *w_frag; /* or NULL */
+    int32_t group_size, stride;
+    prom_requant_t rq;
+    int8_t *y;
+} prom_gconv_layer_t;
+
+/* Enqueue `count` grouped 3x3 layers (the operation of prom_gconv3x3; paper Section 2 for the
+ * layer, Section 3.1 and Eq. 4-5 for its quantisation) on `stream` with one host call.  The
+ * results are those of running the layers one after the other in the given order.  Consecutive
+ * layers that run on the same matrix-core kernel (group sizes 4, 8, 16; group sizes 32, 64) and do
+ * not touch each other's data (no layer's output overlaps another's input, weights, parameters or
+ * output) share one kernel launch, up to 24 of them, and run concurrently; anything else is
+ * launched layer by layer.  All layers are validated first; on an argument error nothing is
+ * enqueued and the index of the offending layer is stored in *bad_layer when bad_layer is not
+ * NULL.  PROM_EHIP if a launch fails (earlier launches stay enqueued). */
+int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int count, int *bad_layer, void *stream);
+
 /* Bytes of the prepared form of prom_gconv_pack; 0 if the matrix-core kernel does not take this
  * layer (group_size not 4, 8, 16, 32 or 64, c % 4 != 0 or c % group_size != 0). */
 size_t prom_gconv_frag_size(int c, int group_size);

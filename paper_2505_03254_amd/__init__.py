@@ -13,6 +13,6 @@ from .binding import (  # noqa: F401
     BLOCK_AUTO, BLOCK_FUSED, BLOCK_UNFUSED, BLOCK_DWPROJ, BLOCK_PLANES, prom_block_planes_applies, prom_dw_pw_conv, prom_dw_pw_can_fuse, prom_block_noalloc, prom_block_noalloc_max_workspace,
     prom_quantize_pw_absmean, prom_quantize_dw_absmax, prom_quantize_gconv_absmax,
     prom_quantize_activation_absmax, prom_pw_conv_dynq,
-    prom_pw_plan_query, prom_pw_batchable, prom_pw_batch_class, prom_pw_conv_sequence, PwSequence, prom_dw_conv_sequence, DwSequence, prom_copy_bytes,
+    prom_pw_plan_query, prom_pw_batchable, prom_pw_batch_class, prom_pw_conv_sequence, PwSequence, prom_dw_conv_sequence, DwSequence, prom_gconv3x3_sequence, GconvSequence, prom_copy_bytes,
     prom_stream_read, prom_stream_write, prom_mfma_i8_loop, prom_requant_check,
 )

@@ -43,6 +43,13 @@ class _DwLayerC(ctypes.Structure):
                 ("stride", ctypes.c_int32), ("rq", _RequantC), ("y", ctypes.c_void_p)]
 
 
+class _GconvLayerC(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("n", ctypes.c_int32), ("h", ctypes.c_int32),
+                ("w", ctypes.c_int32), ("c", ctypes.c_int32), ("w_g", ctypes.c_void_p),
+                ("w_frag", ctypes.c_void_p), ("group_size", ctypes.c_int32), ("stride", ctypes.c_int32),
+                ("rq", _RequantC), ("y", ctypes.c_void_p)]
+
+
 class _PlanC(ctypes.Structure):
     _fields_ = [("tiles_per_wave", ctypes.c_int32), ("pixel_tiles", ctypes.c_int32),
                 ("workgroups", ctypes.c_int32), ("row_waves", ctypes.c_int32), ("k_outer", ctypes.c_int32)]
@@ -121,6 +128,8 @@ def load_library():
     lib.prom_pw_conv_sequence.argtypes = [ctypes.POINTER(_PwLayerC), ci, ctypes.POINTER(ci), vp]
     lib.prom_dw_conv_sequence.restype = ci
     lib.prom_dw_conv_sequence.argtypes = [ctypes.POINTER(_DwLayerC), ci, ctypes.POINTER(ci), vp]
+    lib.prom_gconv3x3_sequence.restype = ci
+    lib.prom_gconv3x3_sequence.argtypes = [ctypes.POINTER(_GconvLayerC), ci, ctypes.POINTER(ci), vp]
     lib.prom_quantize_pw_absmean.restype = ci
     lib.prom_quantize_pw_absmean.argtypes = [vp, ci, ci, ctypes.c_float, vp, sz, vp, vp, vp]
     lib.prom_quantize_activation_absmax.restype = ci
@@ -635,6 +644,41 @@ class DwSequence:
 
 def prom_dw_conv_sequence(layers, stream=None):
     DwSequence(layers).run(stream)
+
+
+class GconvSequence:
+    """A prebuilt array of prom_gconv_layer_t; run() enqueues all layers with one C call.
+    Keeps references to every tensor it points at."""
+
+    def __init__(self, layers):
+        """layers: iterable of (x, w_g, stride, Requant, y, w_frag or None) device tensors;
+        w_g is [3][3][c][group_size]."""
+        layers = list(layers)
+        self._keep = layers
+        self._arr = (_GconvLayerC * len(layers))()
+        for i, (x, w_g, stride, rq, y, w_frag) in enumerate(layers):
+            _dev_i8(x, "x")
+            _dev_i8(y, "y")
+            _dev_i8(w_g, "w_g")
+            n, h, w, c = x.shape
+            if w_g.dim() != 4 or tuple(w_g.shape[:3]) != (3, 3, c):
+                raise ValueError("w_g must be [3][3][c][group_size]")
+            l = self._arr[i]
+            l.x, l.n, l.h, l.w, l.c = x.data_ptr(), n, h, w, c
+            l.w_g, l.group_size, l.stride = w_g.data_ptr(), int(w_g.shape[3]), int(stride)
+            l.w_frag = w_frag.data_ptr() if w_frag is not None else None
+            l.rq, l.y = rq._c(), y.data_ptr()
+        self.count = len(layers)
+
+    def run(self, stream=None):
+        bad = ctypes.c_int(-1)
+        rc = load_library().prom_gconv3x3_sequence(self._arr, self.count, ctypes.byref(bad), _stream_ptr(stream))
+        if rc != PROM_OK:
+            raise PromError(rc, f"prom_gconv3x3_sequence (layer {bad.value})")
+
+
+def prom_gconv3x3_sequence(layers, stream=None):
+    GconvSequence(layers).run(stream)
 
 
 def prom_copy_bytes(src, dst, nbytes: Optional[int] = None, stream=None):

@@ -17,8 +17,10 @@
 #include "prom_device.h"
 #include "prom_launch.h"
 
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace prom {
 
@@ -197,7 +199,7 @@ constexpr int kGconvFragBytes = 4 * 9 * 64 * 16;
 constexpr int kGconvParBytes = 64 * 16;
 constexpr int kGconvPieces = 9;  // 16-byte pieces of a staged band per thread
 
-__global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, const GconvBand bd)
+__device__ __forceinline__ void gconv_mfma_body(const GconvArgs &a, const GconvBand &bd, const int block)
 {
     constexpr int kFlags = 0x00020000;
     constexpr int kOob = 0x7ffff000;
@@ -211,8 +213,8 @@ __global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, c
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
-    const int cb = blockIdx.x % bd.ncb;
-    const int wg = blockIdx.x / bd.ncb;
+    const int cb = block % bd.ncb;
+    const int wg = block / bd.ncb;
     const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
     const int W2 = W + 2;
     const int cbase = cb * 64;
@@ -394,6 +396,11 @@ __global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, c
         run(std::false_type{});
 }
 
+__global__ __launch_bounds__(256, 2) void gconv_mfma_kernel(const GconvArgs a, const GconvBand bd)
+{
+    gconv_mfma_body(a, bd, (int)blockIdx.x);
+}
+
 // ---- gconv_tapk_kernel: group sizes 4, 8, 16 with the kernel taps in the k dimension -------------
 // A tile of 16 output channels of such a layer sees only the 16 input channels at the same
 // positions (its groups lie inside them), so its contraction is 9 taps x 16 channels = 144 long:
@@ -437,7 +444,7 @@ __device__ __forceinline__ void transpose_rows4(uint32_t (&o)[4])
 }
 
 template <int PT>
-__global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const GconvArgs a, const GconvBand bd)
+__device__ __forceinline__ void gconv_tapk_body(const GconvArgs &a, const GconvBand &bd, const int block)
 {
     constexpr int kFlags = 0x00020000;
     constexpr int kOob = 0x7ffff000;
@@ -451,8 +458,8 @@ __global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const Gconv
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
-    const int cb = blockIdx.x % bd.ncb;
-    const int wg = blockIdx.x / bd.ncb;
+    const int cb = block % bd.ncb;
+    const int wg = block / bd.ncb;
     const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
     const int W2 = W + 2;
     const int cbase = cb * 64;
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const Gconv
             if (!general) par[t][r][3] -= 1;
         }
     GC_STAMP(1);
-    int band_no = 0;
+    [[maybe_unused]] int band_no = 0;
     const bool full_block = cbase + 64 <= C;
     // n / d by the band's magic numbers
     auto div_wo = [&](int n) { return (int)(((unsigned long long)(unsigned)n * bd.magic_wo) >> 31); };
@@ -660,6 +667,46 @@ __global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const Gconv
 #endif
 }
 
+template <int PT>
+__global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_kernel(const GconvArgs a, const GconvBand bd)
+{
+    gconv_tapk_body<PT>(a, bd, (int)blockIdx.x);
+}
+
+// ---- several layers in one launch (prom_gconv3x3_sequence) ----------------------------------------
+// The kernel argument is a table of layers and of the first workgroup of each; a workgroup finds
+// its layer and runs that layer's body with its index inside the layer.
+constexpr int kGconvMaxBatch = 24;
+constexpr int kGconvBatchSlots = 512;  // workgroups of a shared launch: two per compute unit
+struct GconvBatchArgs {
+    GconvArgs a[kGconvMaxBatch];
+    GconvBand bd[kGconvMaxBatch];
+    int start[kGconvMaxBatch + 1];
+    int count;
+};
+static_assert(sizeof(GconvBatchArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+__device__ __forceinline__ int gconv_batch_member(const GconvBatchArgs &b)
+{
+    int m = 0;
+    for (int k = 1; k < b.count; ++k)
+        if ((int)blockIdx.x >= b.start[k]) m = k;
+    return m;
+}
+
+template <int PT>
+__global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_batch_kernel(const GconvBatchArgs b)
+{
+    const int m = gconv_batch_member(b);
+    gconv_tapk_body<PT>(b.a[m], b.bd[m], (int)blockIdx.x - b.start[m]);
+}
+
+__global__ __launch_bounds__(256, 2) void gconv_mfma_batch_kernel(const GconvBatchArgs b)
+{
+    const int m = gconv_batch_member(b);
+    gconv_mfma_body(b.a[m], b.bd[m], (int)blockIdx.x - b.start[m]);
+}
+
 // Any C, group size and alignment: one thread per output element.
 __global__ __launch_bounds__(256) void gconv_kernel_generic(const GconvArgs a)
 {
@@ -709,10 +756,23 @@ static bool ranges_overlap(const void *p, size_t pn, const void *q, size_t qn)
 
 }  // namespace prom
 
-extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const int8_t *w_g, const void *w_frag,
-                             int group_size, int stride, const prom_requant_t *rq, int8_t *y, void *stream)
+namespace prom {
+
+// A validated, planned layer.
+struct GconvLaunch {
+    enum Kind { DEPTHWISE, TAPK, MFMA, V4, GENERIC } kind;
+    GconvArgs a;
+    GconvBand bd;       // TAPK, MFMA
+    size_t lds;         // TAPK, MFMA
+    unsigned grid;      // TAPK, MFMA: workgroups
+    const prom_requant_t *rq;  // DEPTHWISE: the caller's struct, valid during the call
+    size_t xbytes, ybytes, wbytes, fbytes;
+    const void *w_frag;
+};
+
+static int gconv_prepare(const int8_t *x, int n, int h, int w, int c, const int8_t *w_g, const void *w_frag,
+                         int group_size, int stride, const prom_requant_t *rq, int8_t *y, GconvLaunch &L)
 {
-    using namespace prom;
     if (!x || !w_g || !rq || !rq->bias || !rq->mult || !rq->shift || !y) return PROM_EINVAL;
     if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || (stride != 1 && stride != 2)) return PROM_EINVAL;
     if (group_size <= 0 || c % group_size != 0) return PROM_EINVAL;
@@ -720,8 +780,7 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
     // |acc| <= 9 * gs * 128 * 128 must stay well inside the int32 accumulator and the
     // precondition |acc + bias| < 2^30 of the requantisation
     if (group_size > 4096) return PROM_EUNSUPPORTED;
-    if (group_size == 1) return prom_dw_conv(x, n, h, w, c, w_g, stride, rq, y, stream);  // same weight layout
-    GconvArgs a;
+    GconvArgs &a = L.a;
     a.x = x; a.w = w_g; a.wfrag = nullptr; a.bias = rq->bias; a.mult = rq->mult; a.mult_neg = rq->mult_neg; a.shift = rq->shift;
     a.y = y;
     a.N = n; a.H = h; a.W = w; a.C = c; a.stride = stride; a.gs = group_size;
@@ -729,33 +788,39 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
     a.Wo = (w - 1) / stride + 1;
     a.lo = rq->act_min;
     a.hi = rq->act_max;
+    L.rq = rq;
+    L.w_frag = w_frag;
     const size_t xbytes = (size_t)n * h * w * c, ybytes = (size_t)n * a.Ho * a.Wo * c;
     const size_t wbytes = (size_t)9 * c * group_size;
+    L.xbytes = xbytes; L.ybytes = ybytes; L.wbytes = wbytes; L.fbytes = 0;
+    if (group_size == 1) {  // same weight layout: prom_dw_conv validates the rest
+        L.kind = GconvLaunch::DEPTHWISE;
+        return PROM_OK;
+    }
     if (xbytes >= ((size_t)1 << 40)) return PROM_EUNSUPPORTED;
     if (ranges_overlap(y, ybytes, x, xbytes) || ranges_overlap(y, ybytes, w_g, wbytes)) return PROM_EALIAS;
     a.total = (long long)ybytes;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    clear_hip_error();
     const bool fast = (group_size % 4 == 0) && (c % 4 == 0) && ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_g) & 3) == 0) &&
                       ((((uintptr_t)rq->bias | (uintptr_t)rq->mult | (uintptr_t)rq->mult_neg |
                          (uintptr_t)rq->shift) & 15) == 0) &&
                       (long long)h * w * c < (1LL << 31) - (1LL << 24) && wbytes < ((size_t)1 << 30) && n <= 65535;
-    bool mfma = fast && (group_size == 4 || group_size == 8 || group_size == 16 || group_size == 32 ||
+    const bool mfma = fast && (group_size == 4 || group_size == 8 || group_size == 16 || group_size == 32 ||
                                group_size == 64) &&
                       xbytes < ((size_t)1 << 31) - ((size_t)1 << 24) && ybytes < ((size_t)1 << 31) - ((size_t)1 << 24);
-    if (w_frag && (((uintptr_t)w_frag & 15) != 0 || prom_gconv_frag_size(c, group_size) == 0)) return PROM_EINVAL;
-    if (w_frag && ranges_overlap(y, ybytes, w_frag, prom_gconv_frag_size(c, group_size))) return PROM_EALIAS;
+    if (w_frag) {
+        L.fbytes = prom_gconv_frag_size(c, group_size);
+        if (((uintptr_t)w_frag & 15) != 0 || L.fbytes == 0) return PROM_EINVAL;
+        if (ranges_overlap(y, ybytes, w_frag, L.fbytes)) return PROM_EALIAS;
+    }
     if (mfma) {
-        a.wfrag = static_cast<const v4i *>(w_frag);
         // band height: as many output rows as keep the staged input rows within the band's bytes
         const bool tapk = group_size <= 16;
         const int kBandBytes = tapk ? kTapkPieces * kTapkThreads * 16 : kGconvPieces * 256 * 16;
         const int row_bytes = (w + 2) * 64;
-        int ri = kBandBytes / row_bytes;
-        if (ri < 3) {
-            mfma = false;  // an image row too wide for the staged band: the dot4 kernel takes it
-        } else {
-            GconvBand bd;
+        const int ri = kBandBytes / row_bytes;
+        if (ri >= 3) {  // else an image row is too wide for the staged band: the dot4 kernel takes it
+            a.wfrag = static_cast<const v4i *>(w_frag);
+            GconvBand &bd = L.bd;
             bd.ncb = (c + 63) / 64;
             bd.R = (ri - 3) / stride + 1;
             if (bd.R > a.Ho) bd.R = a.Ho;
@@ -768,7 +833,7 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
             bd.bands = (a.Ho + bd.R - 1) / bd.R;
             bd.G = 1;
             if (bd.bands == 1) {
-                // small images: several per unit (a workgroup copies 36 KB of weights whatever it
+                // small images: several per unit (a workgroup copies its block's weights whatever it
                 // computes), as far as they fit, but no more than leaves a workgroup for every
                 // compute unit
                 bd.G = kBandBytes / (bd.RI * row_bytes);
@@ -788,42 +853,189 @@ extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const 
             if (per_cb > units) per_cb = units;
             if (per_cb < 1) per_cb = 1;
             bd.wgs_per_cb = (int)per_cb;
-            const size_t lds = (size_t)(tapk ? kTapkFragBytes + kTapkParBytes : kGconvFragBytes + kGconvParBytes) +
-                               (size_t)bd.G * bd.RI * row_bytes;
-            static std::once_flag once;
-            static hipError_t attr_err = hipSuccess;
-            std::call_once(once, [] {
-                attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gconv_mfma_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-                if (attr_err == hipSuccess)  // both limits cover frag + parameters + the largest band
-                    attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gconv_tapk_kernel<kTapkPT>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            });
-            if (attr_err != hipSuccess) {
-                last_hip_error() = attr_err;
-                (void)hipGetLastError();
-                return PROM_EHIP;
-            }
-            clear_hip_error();
-            if (tapk)
-                hipLaunchKernelGGL((gconv_tapk_kernel<kTapkPT>), dim3((unsigned)(per_cb * bd.ncb)), dim3(kTapkThreads), lds, st, a, bd);
-            else
-                hipLaunchKernelGGL(gconv_mfma_kernel, dim3((unsigned)(per_cb * bd.ncb)), dim3(256), lds, st, a, bd);
-            return check_launch();
+            L.lds = (size_t)(tapk ? kTapkFragBytes + kTapkParBytes : kGconvFragBytes + kGconvParBytes) +
+                    (size_t)bd.G * bd.RI * row_bytes;
+            L.grid = (unsigned)(per_cb * bd.ncb);
+            L.kind = tapk ? GconvLaunch::TAPK : GconvLaunch::MFMA;
+            return PROM_OK;
         }
     }
     if (fast) {
-        const GconvFn fn = stride == 1 ? pick_gconv<1>(group_size) : pick_gconv<2>(group_size);
         const long long xblocks = ((long long)a.Wo * (c / 4) + 255) / 256;
         const int strips = (a.Ho + 3) / 4;
         if (xblocks > (1LL << 31) - 1 || strips > 65535) return PROM_EUNSUPPORTED;
-        hipLaunchKernelGGL(fn, dim3((unsigned)xblocks, (unsigned)strips, (unsigned)n), dim3(256), 0, st, a);
+        L.kind = GconvLaunch::V4;
     } else {
-        const long long blocks = (a.total + 255) / 256;
-        if (blocks > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
-        hipLaunchKernelGGL(gconv_kernel_generic, dim3((unsigned)blocks), dim3(256), 0, st, a);
+        if ((a.total + 255) / 256 > (1LL << 31) - 1) return PROM_EUNSUPPORTED;
+        L.kind = GconvLaunch::GENERIC;
+    }
+    return PROM_OK;
+}
+
+// The matrix-core kernels stage up to 96 KB in LDS.
+static int gconv_set_attributes()
+{
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        const void *fns[4] = {reinterpret_cast<const void *>(&gconv_mfma_kernel),
+                              reinterpret_cast<const void *>(&gconv_tapk_kernel<kTapkPT>),
+                              reinterpret_cast<const void *>(&gconv_mfma_batch_kernel),
+                              reinterpret_cast<const void *>(&gconv_tapk_batch_kernel<kTapkPT>)};
+        for (const void *fn : fns)
+            if (attr_err == hipSuccess)
+                attr_err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    });
+    if (attr_err != hipSuccess) {
+        last_hip_error() = attr_err;
+        (void)hipGetLastError();
+        return PROM_EHIP;
+    }
+    return PROM_OK;
+}
+
+static int gconv_launch(const GconvLaunch &L, hipStream_t st)
+{
+    const GconvArgs &a = L.a;
+    if (L.kind == GconvLaunch::DEPTHWISE)
+        return prom_dw_conv(a.x, a.N, a.H, a.W, a.C, a.w, a.stride, L.rq, a.y, st);
+    if (L.kind == GconvLaunch::TAPK || L.kind == GconvLaunch::MFMA) {
+        const int rc = gconv_set_attributes();
+        if (rc != PROM_OK) return rc;
+    }
+    clear_hip_error();
+    switch (L.kind) {
+    case GconvLaunch::TAPK:
+        hipLaunchKernelGGL((gconv_tapk_kernel<kTapkPT>), dim3(L.grid), dim3(kTapkThreads), L.lds, st, a, L.bd);
+        break;
+    case GconvLaunch::MFMA:
+        hipLaunchKernelGGL(gconv_mfma_kernel, dim3(L.grid), dim3(256), L.lds, st, a, L.bd);
+        break;
+    case GconvLaunch::V4: {
+        const GconvFn fn = a.stride == 1 ? pick_gconv<1>(a.gs) : pick_gconv<2>(a.gs);
+        const long long xblocks = ((long long)a.Wo * (a.C / 4) + 255) / 256;
+        const int strips = (a.Ho + 3) / 4;
+        hipLaunchKernelGGL(fn, dim3((unsigned)xblocks, (unsigned)strips, (unsigned)a.N), dim3(256), 0, st, a);
+        break;
+    }
+    default:
+        hipLaunchKernelGGL(gconv_kernel_generic, dim3((unsigned)((a.total + 255) / 256)), dim3(256), 0, st, a);
+        break;
     }
     return check_launch();
+}
+
+// True if one of the two layers writes what the other reads or writes.
+static bool gconv_conflicts(const GconvLaunch &p, const GconvLaunch &q)
+{
+    auto reads_or_writes = [](const GconvLaunch &l, const void *y, size_t yn) {
+        const size_t pn = (size_t)l.a.C * sizeof(int32_t);
+        return ranges_overlap(y, yn, l.a.x, l.xbytes) || ranges_overlap(y, yn, l.a.y, l.ybytes) ||
+               ranges_overlap(y, yn, l.a.w, l.wbytes) || (l.w_frag && ranges_overlap(y, yn, l.w_frag, l.fbytes)) ||
+               ranges_overlap(y, yn, l.a.bias, pn) || ranges_overlap(y, yn, l.a.mult, pn) ||
+               ranges_overlap(y, yn, l.a.shift, pn) || (l.a.mult_neg && ranges_overlap(y, yn, l.a.mult_neg, pn));
+    };
+    return reads_or_writes(q, p.a.y, p.ybytes) || reads_or_writes(p, q.a.y, q.ybytes);
+}
+
+}  // namespace prom
+
+extern "C" int prom_gconv3x3(const int8_t *x, int n, int h, int w, int c, const int8_t *w_g, const void *w_frag,
+                             int group_size, int stride, const prom_requant_t *rq, int8_t *y, void *stream)
+{
+    prom::GconvLaunch L;
+    const int rc = prom::gconv_prepare(x, n, h, w, c, w_g, w_frag, group_size, stride, rq, y, L);
+    if (rc != PROM_OK) return rc;
+    return prom::gconv_launch(L, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int count, int *bad_layer, void *stream)
+{
+    using namespace prom;
+    if (bad_layer) *bad_layer = -1;
+    if (count < 0 || (count > 0 && !layers)) return PROM_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    static thread_local std::vector<GconvLaunch> prepared;
+    prepared.resize((size_t)count);
+    for (int i = 0; i < count; ++i) {
+        const prom_gconv_layer_t &l = layers[i];
+        const int rc = gconv_prepare(l.x, l.n, l.h, l.w, l.c, l.w_g, l.w_frag, l.group_size, l.stride, &l.rq, l.y,
+                                     prepared[(size_t)i]);
+        if (rc != PROM_OK) {
+            if (bad_layer) *bad_layer = i;
+            return rc;
+        }
+    }
+    // Consecutive layers of one matrix-core kernel that do not touch each other's data share a launch
+    // (at most kGconvMaxBatch of them), the members with the least work first: a small layer is one
+    // latency chain per workgroup and would otherwise end the launch alone.
+    static thread_local GconvBatchArgs b;
+    int i = 0;
+    while (i < count) {
+        const GconvLaunch::Kind kind = prepared[(size_t)i].kind;
+        int j = i;
+        if (kind == GconvLaunch::TAPK || kind == GconvLaunch::MFMA) {
+            long long blocks = 0;
+            while (j < count && j - i < kGconvMaxBatch && prepared[(size_t)j].kind == kind) {
+                const GconvLaunch &L = prepared[(size_t)j];
+                bool clash = false;
+                for (int k = i; k < j && !clash; ++k) clash = gconv_conflicts(prepared[(size_t)k], L);
+                if (clash || blocks + L.grid > (1LL << 30)) break;
+                blocks += L.grid;
+                ++j;
+            }
+        }
+        int rc;
+        if (j - i >= 2) {
+            rc = gconv_set_attributes();
+            if (rc == PROM_OK) {
+                int order[kGconvMaxBatch];
+                for (int k = 0; k < j - i; ++k) order[k] = i + k;
+                std::stable_sort(order, order + (j - i), [&](int p, int q) {
+                    return prepared[(size_t)p].xbytes + prepared[(size_t)p].ybytes <
+                           prepared[(size_t)q].xbytes + prepared[(size_t)q].ybytes;
+                });
+                b.count = j - i;
+                // The launch has as many workgroups as are resident at once (two per compute unit),
+                // shared out by the bytes the layers move: alone, a small layer spreads over the chip
+                // for the sake of latency; here that would queue thousands of workgroups that each
+                // live one latency chain long.
+                double total = 0;
+                for (int k = 0; k < j - i; ++k) total += (double)(prepared[(size_t)order[k]].xbytes + prepared[(size_t)order[k]].ybytes);
+                int start = 0;
+                size_t lds = 0;
+                for (int k = 0; k < j - i; ++k) {
+                    const GconvLaunch &L = prepared[(size_t)order[k]];
+                    b.a[k] = L.a;
+                    b.bd[k] = L.bd;
+                    const double share = (double)(L.xbytes + L.ybytes) / total;
+                    long long per_cb = (long long)(kGconvBatchSlots * share / L.bd.ncb + 0.5);
+                    if (per_cb > L.bd.units) per_cb = L.bd.units;
+                    if (per_cb < 1) per_cb = 1;
+                    b.bd[k].wgs_per_cb = (int)per_cb;
+                    b.start[k] = start;
+                    start += (int)(per_cb * L.bd.ncb);
+                    if (L.lds > lds) lds = L.lds;
+                }
+                b.start[j - i] = start;
+                clear_hip_error();
+                if (kind == GconvLaunch::TAPK)
+                    hipLaunchKernelGGL((gconv_tapk_batch_kernel<kTapkPT>), dim3((unsigned)start), dim3(kTapkThreads), lds, st, b);
+                else
+                    hipLaunchKernelGGL(gconv_mfma_batch_kernel, dim3((unsigned)start), dim3(256), lds, st, b);
+                rc = check_launch();
+            }
+            i = j;
+        } else {
+            rc = gconv_launch(prepared[(size_t)i], st);
+            ++i;
+        }
+        if (rc != PROM_OK) {
+            if (bad_layer) *bad_layer = i - 1;
+            return rc;
+        }
+    }
+    return PROM_OK;
 }
 
 #ifdef PROM_TIMELINE

@@ -122,3 +122,87 @@ def test_gconv_full_size_layer_every_output(P):
             torch.cuda.synchronize()
             bad = int((y != want).sum())
             assert bad == 0, f"stride {stride}, run {run}: {bad} outputs differ"
+
+
+def _seq_entry(P, G, window=(-128, 127), mneg=None, use_frag=False, x=None):
+    torch = torch_cuda()
+    lo, hi = window
+    rq = P.Requant(dev(G.bias), dev(G.mult), dev(G.shift), lo, hi, None if mneg is None else dev(mneg))
+    n, h, w, c = G.x.shape
+    ho, wo = (h - 1) // G.stride + 1, (w - 1) // G.stride + 1
+    y = torch.full((n, ho, wo, c), 77, dtype=torch.int8, device="cuda:0")
+    frag = dev(P.prom_gconv_pack(G.weight)) if use_frag else None
+    return (dev(G.x) if x is None else x, dev(G.weight), G.stride, rq, y, frag)
+
+
+def test_gconv_sequence_of_independent_layers(P):
+    """Layers of every kernel in one call: the matrix-core ones share launches (members of different
+    shapes, band heights, strides, epilogue forms, with and without prepared weights), the others are
+    launched one by one; every output equals the oracle's."""
+    torch = torch_cuda()
+    specs = [  # n, h, w, c, gs, stride, shift range, prelu, prepared weights
+        (4, 56, 56, 96, 16, 1, (8, 17), False, True), (2, 9, 11, 16, 4, 2, (0, 31), False, False),
+        (3, 14, 14, 64, 8, 1, (8, 17), True, True), (2, 7, 7, 128, 16, 1, (1, 12), False, True),
+        (1, 28, 28, 40, 4, 2, (8, 17), False, False), (5, 7, 7, 384, 16, 1, (8, 17), False, True),
+        (1, 9, 9, 64, 32, 1, (8, 17), False, True), (2, 5, 5, 128, 64, 2, (0, 31), True, False),
+        (1, 6, 5, 24, 12, 1, (8, 17), False, False), (1, 5, 5, 12, 1, 1, (8, 17), False, False),
+        (2, 13, 10, 64, 16, 1, (8, 17), False, True),
+    ]
+    entries, wants = [], []
+    for i, (n, h, w, c, gs, s, sr, prelu, frag) in enumerate(specs):
+        G = make_gconv_layer(15700 + i, n, h, w, c, gs, s, signed_x=True, act_window=(-128, 127), shift_range=sr)
+        mneg = prelu_mult_neg(15700 + i, G.mult) if prelu else None
+        entries.append(_seq_entry(P, G, mneg=mneg, use_frag=frag))
+        wants.append(_want(G, (-128, 127), mneg))
+    P.prom_gconv3x3_sequence(entries)
+    torch.cuda.synchronize()
+    for i, (e, want) in enumerate(zip(entries, wants)):
+        assert_same(e[4].cpu().numpy(), want, f"sequence member {i} {specs[i]}")
+    # the same array again, and through a prebuilt sequence object
+    seq = P.GconvSequence(entries)
+    for e in entries:
+        e[4].fill_(55)
+    seq.run()
+    torch.cuda.synchronize()
+    for i, (e, want) in enumerate(zip(entries, wants)):
+        assert_same(e[4].cpu().numpy(), want, f"prebuilt sequence member {i}")
+
+
+def test_gconv_sequence_keeps_the_order_of_dependent_layers(P):
+    """A layer that reads what an earlier one writes does not share its launch: the result is that
+    of running the layers one after the other."""
+    torch = torch_cuda()
+    G1 = make_gconv_layer(15800, 2, 14, 14, 64, 16, 1, signed_x=True, act_window=(-128, 127))
+    G2 = make_gconv_layer(15801, 2, 14, 14, 64, 8, 2, signed_x=True, act_window=(-128, 127))
+    G3 = make_gconv_layer(15802, 2, 14, 14, 64, 4, 1, signed_x=True, act_window=(-128, 127))
+    e1 = _seq_entry(P, G1, use_frag=True)
+    e2 = _seq_entry(P, G2, x=e1[4])           # reads the first layer's output
+    e3 = _seq_entry(P, G3, use_frag=True)     # independent of both
+    P.prom_gconv3x3_sequence([e1, e2, e3])
+    torch.cuda.synchronize()
+    y1 = _want(G1, (-128, 127))
+    assert_same(e1[4].cpu().numpy(), y1, "first layer")
+    y2 = oracle.gconv3x3(y1, G2.weight, G2.stride, G2.bias, G2.mult, G2.shift, -128, 127)
+    assert_same(e2[4].cpu().numpy(), y2, "second layer on the first one's output")
+    assert_same(e3[4].cpu().numpy(), _want(G3, (-128, 127)), "third layer")
+
+
+def test_gconv_sequence_errors_and_empty(P):
+    torch = torch_cuda()
+    P.prom_gconv3x3_sequence([])
+    G1 = make_gconv_layer(15900, 1, 6, 6, 16, 4, 1)
+    G2 = make_gconv_layer(15901, 1, 6, 6, 16, 4, 1)
+    e1 = _seq_entry(P, G1)
+    e2 = list(_seq_entry(P, G2))
+    e2[2] = 3  # no such stride
+    with pytest.raises(P.PromError) as err:
+        P.prom_gconv3x3_sequence([e1, tuple(e2)])
+    assert err.value.code == -1 and "layer 1" in str(err.value)
+    torch.cuda.synchronize()
+    assert bool((e1[4] == 77).all()), "nothing is enqueued when a layer is refused"
+    # an output that overlaps its own input
+    e3 = list(_seq_entry(P, G1))
+    e3[4] = e3[0]
+    with pytest.raises(P.PromError) as err:
+        P.prom_gconv3x3_sequence([tuple(e3)])
+    assert err.value.code == -3
