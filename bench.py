@@ -86,6 +86,8 @@ def main():
                     help="run the depthwise sweep leg alone and print its record (for profiling)")
     ap.add_argument("--chain-only", action="store_true",
                     help="run the 17-block chain leg alone and print its record (for profiling)")
+    ap.add_argument("--gconv-only", action="store_true",
+                    help="run the grouped 3x3 legs alone and print their records (for profiling)")
     ap.add_argument("--dw-filter", default=None,
                     help="with --dw-only: HW,C,STRIDE of the one depthwise layer to run, e.g. 56,144,1")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
@@ -121,6 +123,9 @@ def main():
         return
     if args.chain_only:
         print(json.dumps(chain_leg(P, torch, dev, args.batch, log)), flush=True)
+        return
+    if args.gconv_only:
+        print(json.dumps(gconv_leg(P, torch, dev, args.batch, log)), flush=True)
         return
     if args.dw_only:
         only = tuple(int(v) for v in args.dw_filter.split(",")) if args.dw_filter else None
@@ -826,6 +831,55 @@ def chain_leg(P, torch, dev, batch, log):
     return out
 
 
+def gconv_leg(P, torch, dev, batch, log):
+    """The grouped 3x3 convolutions of RegNetX-400MF and ResNeXt-50 32x4d at the given batch."""
+    out = {}
+    from workloads import make_gconv_layer, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers
+    for key, shapes in (("gconv_regnetx_400mf", regnetx_400mf_grouped_layers()),
+                        ("gconv_resnext50_32x4d", resnext50_32x4d_grouped_layers())):
+        gl = []
+        for i, g in enumerate(shapes):
+            G = make_gconv_layer(SEED + 3000 + i, 1, 4, 4, g.c, g.gs, g.stride)
+            x = torch.randint(0, 128, (batch, g.hw_in, g.hw_in, g.c), dtype=torch.int8, device=dev)
+            w = torch.from_numpy(G.weight).to(dev)
+            wf = torch.from_numpy(P.prom_gconv_pack(G.weight)).to(dev)  # weights prepared once per layer
+            rq = P.Requant(torch.from_numpy(G.bias).to(dev), torch.from_numpy(G.mult).to(dev),
+                           torch.from_numpy(G.shift).to(dev), 0, 127)
+            ho = (g.hw_in - 1) // g.stride + 1
+            y = torch.empty((batch, ho, ho, g.c), dtype=torch.int8, device=dev)
+            gl.append((g, x, (w, wf), rq, y, batch * g.c * (g.hw_in ** 2 + ho ** 2), batch * ho * ho * g.c * 9 * g.gs))
+        # the layers of the sweep are independent: one call for all (those of one matrix-core kernel
+        # share a launch), and layer by layer for comparison
+        gseq = P.GconvSequence([(x, w, g.stride, rq, y, wf) for g, x, (w, wf), rq, y, _b, _m in gl])
+        for _ in range(3):
+            gseq.run()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(10):
+            gseq.run()
+        torch.cuda.synchronize()
+        dg = (time.perf_counter() - tg0) / 10
+        for g, x, (w, wf), rq, y, _b, _m in gl:
+            P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(5):
+            for g, x, (w, wf), rq, y, _b, _m in gl:
+                P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
+        torch.cuda.synchronize()
+        dg1 = (time.perf_counter() - tg0) / 5
+        gbytes = sum(b for *_, b, _m in gl)
+        gmacs = sum(m for *_, m in gl)
+        out[key] = {"layers": len(gl), "us": round(dg * 1e6, 1), "gbs": round(gbytes / dg / 1e9, 1),
+                    "frac_hbm_roofline": round(gbytes / dg / 1e9 / HBM_PEAK_GBS, 4),
+                    "useful_gmac_per_s": round(gmacs / dg / 1e9, 1), "api": "prom_gconv3x3_sequence",
+                    "us_layer_by_layer": round(dg1 * 1e6, 1)}
+        log(f"[bench] {key}: {len(gl)} layers, {dg * 1e6:.1f} us in one call ({dg1 * 1e6:.1f} us layer by layer), "
+            f"{gbytes / dg / 1e9:.0f} GB/s, {gmacs / dg / 1e12:.1f} Tmac/s useful")
+        del gl, gseq
+    return out
+
+
 def extra_legs(P, torch, dev, batch, log):
     """Depthwise layers of MobileNetV2 at the same batch, and config 4's block."""
     import numpy as np
@@ -945,50 +999,7 @@ def extra_legs(P, torch, dev, batch, log):
         f"{algf / df / 1e9:.0f} GB/s algorithmic ({100 * algf / df / 1e9 / HBM_PEAK_GBS:.1f} % of the HBM roofline)")
     del xf, qf
 
-    # grouped 3x3 convolutions of RegNetX-400MF and ResNeXt-50 32x4d at the same batch
-    from workloads import make_gconv_layer, regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers
-    for key, shapes in (("gconv_regnetx_400mf", regnetx_400mf_grouped_layers()),
-                        ("gconv_resnext50_32x4d", resnext50_32x4d_grouped_layers())):
-        gl = []
-        for i, g in enumerate(shapes):
-            G = make_gconv_layer(SEED + 3000 + i, 1, 4, 4, g.c, g.gs, g.stride)
-            x = torch.randint(0, 128, (batch, g.hw_in, g.hw_in, g.c), dtype=torch.int8, device=dev)
-            w = torch.from_numpy(G.weight).to(dev)
-            wf = torch.from_numpy(P.prom_gconv_pack(G.weight)).to(dev)  # weights prepared once per layer
-            rq = P.Requant(torch.from_numpy(G.bias).to(dev), torch.from_numpy(G.mult).to(dev),
-                           torch.from_numpy(G.shift).to(dev), 0, 127)
-            ho = (g.hw_in - 1) // g.stride + 1
-            y = torch.empty((batch, ho, ho, g.c), dtype=torch.int8, device=dev)
-            gl.append((g, x, (w, wf), rq, y, batch * g.c * (g.hw_in ** 2 + ho ** 2), batch * ho * ho * g.c * 9 * g.gs))
-        # the layers of the sweep are independent: one call for all (those of one matrix-core kernel
-        # share a launch), and layer by layer for comparison
-        gseq = P.GconvSequence([(x, w, g.stride, rq, y, wf) for g, x, (w, wf), rq, y, _b, _m in gl])
-        for _ in range(3):
-            gseq.run()
-        torch.cuda.synchronize()
-        tg0 = time.perf_counter()
-        for _ in range(10):
-            gseq.run()
-        torch.cuda.synchronize()
-        dg = (time.perf_counter() - tg0) / 10
-        for g, x, (w, wf), rq, y, _b, _m in gl:
-            P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
-        torch.cuda.synchronize()
-        tg0 = time.perf_counter()
-        for _ in range(5):
-            for g, x, (w, wf), rq, y, _b, _m in gl:
-                P.prom_gconv3x3(x, w, g.stride, rq, y, w_frag=wf)
-        torch.cuda.synchronize()
-        dg1 = (time.perf_counter() - tg0) / 5
-        gbytes = sum(b for *_, b, _m in gl)
-        gmacs = sum(m for *_, m in gl)
-        out[key] = {"layers": len(gl), "us": round(dg * 1e6, 1), "gbs": round(gbytes / dg / 1e9, 1),
-                    "frac_hbm_roofline": round(gbytes / dg / 1e9 / HBM_PEAK_GBS, 4),
-                    "useful_gmac_per_s": round(gmacs / dg / 1e9, 1), "api": "prom_gconv3x3_sequence",
-                    "us_layer_by_layer": round(dg1 * 1e6, 1)}
-        log(f"[bench] {key}: {len(gl)} layers, {dg * 1e6:.1f} us in one call ({dg1 * 1e6:.1f} us layer by layer), "
-            f"{gbytes / dg / 1e9:.0f} GB/s, {gmacs / dg / 1e12:.1f} Tmac/s useful")
-        del gl, gseq
+    out.update(gconv_leg(P, torch, dev, batch, log))
     return out
 
 

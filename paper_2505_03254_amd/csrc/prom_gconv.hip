@@ -190,6 +190,7 @@ struct GconvBand {
     int bands;       // bands per image
     int G;           // images per unit of work (above 1 only when a band is the whole image)
     int units;       // units of work per channel block
+    int swizzle;     // XCD-aware order of the workgroups (wgs_per_cb % 8 == 0)
     // floor(2^31 / d) + 1 for d = Wo and d = R * Wo: n / d = (n * this) >> 31 for every n with
     // n * d < 2^31 (the pixels of a unit are a few thousand at most)
     unsigned magic_wo, magic_img;
@@ -213,8 +214,20 @@ __device__ __forceinline__ void gconv_mfma_body(const GconvArgs &a, const GconvB
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
-    const int cb = block % bd.ncb;
-    const int wg = block / bd.ncb;
+    // Workgroups go round-robin over the 8 XCDs, each with an L2 of its own.  A pixel's channel
+    // blocks are neighbours in memory (two of them share a 128-byte line), so the workgroups of all
+    // channel blocks with the same units sit on one XCD (grids that are a multiple of 8 per channel
+    // block); otherwise every line comes from HBM once per channel block.
+    int cb, wg;
+    if (bd.swizzle) {
+        const int k = block >> 3;
+        cb = k % bd.ncb;
+        wg = (k / bd.ncb) * 8 + (block & 7);
+    } else {
+        cb = block % bd.ncb;
+        wg = block / bd.ncb;
+    }
+    if (wg >= bd.wgs_per_cb) return;  // padding of a shared launch
     const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
     const int W2 = W + 2;
     const int cbase = cb * 64;
@@ -458,8 +471,20 @@ __device__ __forceinline__ void gconv_tapk_body(const GconvArgs &a, const GconvB
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
-    const int cb = block % bd.ncb;
-    const int wg = block / bd.ncb;
+    // Workgroups go round-robin over the 8 XCDs, each with an L2 of its own.  A pixel's channel
+    // blocks are neighbours in memory (two of them share a 128-byte line), so the workgroups of all
+    // channel blocks with the same units sit on one XCD (grids that are a multiple of 8 per channel
+    // block); otherwise every line comes from HBM once per channel block.
+    int cb, wg;
+    if (bd.swizzle) {
+        const int k = block >> 3;
+        cb = k % bd.ncb;
+        wg = (k / bd.ncb) * 8 + (block & 7);
+    } else {
+        cb = block % bd.ncb;
+        wg = block / bd.ncb;
+    }
+    if (wg >= bd.wgs_per_cb) return;  // padding of a shared launch
     const int C = a.C, GS = a.gs, S = a.stride, W = a.W, Wo = a.Wo;
     const int W2 = W + 2;
     const int cbase = cb * 64;
@@ -852,7 +877,9 @@ static int gconv_prepare(const int8_t *x, int n, int h, int w, int c, const int8
             long long per_cb = (2 * 256) / bd.ncb;
             if (per_cb > units) per_cb = units;
             if (per_cb < 1) per_cb = 1;
+            if (per_cb >= 64) per_cb -= per_cb % 8;  // for the XCD-aware order; small grids keep every workgroup
             bd.wgs_per_cb = (int)per_cb;
+            bd.swizzle = per_cb % 8 == 0;
             L.lds = (size_t)(tapk ? kTapkFragBytes + kTapkParBytes : kGconvFragBytes + kGconvParBytes) +
                     (size_t)bd.G * bd.RI * row_bytes;
             L.grid = (unsigned)(per_cb * bd.ncb);
@@ -999,7 +1026,8 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                 // The launch has as many workgroups as are resident at once (two per compute unit),
                 // shared out by the bytes the layers move: alone, a small layer spreads over the chip
                 // for the sake of latency; here that would queue thousands of workgroups that each
-                // live one latency chain long.
+                // live one latency chain long.  (Shares by an estimate of the rounds of MFMA work
+                // instead of the bytes were measured and are worse.)
                 double total = 0;
                 for (int k = 0; k < j - i; ++k) total += (double)(prepared[(size_t)order[k]].xbytes + prepared[(size_t)order[k]].ybytes);
                 int start = 0;
@@ -1012,9 +1040,11 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                     long long per_cb = (long long)(kGconvBatchSlots * share / L.bd.ncb + 0.5);
                     if (per_cb > L.bd.units) per_cb = L.bd.units;
                     if (per_cb < 1) per_cb = 1;
+                    if (per_cb >= 8) per_cb -= per_cb % 8;  // for the XCD-aware order (measured: 10 % on ResNeXt)
                     b.bd[k].wgs_per_cb = (int)per_cb;
-                    b.start[k] = start;
-                    start += (int)(per_cb * L.bd.ncb);
+                    b.bd[k].swizzle = per_cb % 8 == 0;
+                    b.start[k] = start;  // a multiple of 8: a member's workgroup index tells its XCD
+                    start += (int)((per_cb * L.bd.ncb + 7) / 8 * 8);
                     if (L.lds > lds) lds = L.lds;
                 }
                 b.start[j - i] = start;
