@@ -22,6 +22,7 @@
 #include "prom_device.h"
 #include "prom_launch.h"
 #include <type_traits>
+#include <algorithm>
 #include <vector>
 
 namespace prom {
@@ -233,8 +234,26 @@ __global__ __launch_bounds__(256) void dw_batch_kernel(const DwBatchArgs b)
     const DwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
     const int l = bid - b.start[i];
     const int xb = b.xblocks[i];
-    const int bx = l % xb, r = l / xb;
-    const int by = r % a.strips, bz = r / a.strips;
+    // Workgroups go round-robin over the 8 XCDs, each with an L2 of its own.  With x fastest, the
+    // workgroups that share input (column neighbours in a row strip, strips above and below) sit on
+    // different XCDs and every shared line comes from HBM more than once (measured: 1.45 times the
+    // input).  So 8 consecutive workgroups are the same place in 8 images: an XCD has whole images,
+    // their workgroups one after the other.  (start[] are multiples of 8.)
+    int bx, by, bz;
+    if ((a.N & 7) == 0) {
+        const int per_img = xb * a.strips;
+        const int k = l >> 3;
+        const int within = k % per_img;
+        bz = (k / per_img) * 8 + (l & 7);
+        bx = within % xb;
+        by = within / xb;
+    } else {
+        const int r = l / xb;
+        bx = l % xb;
+        by = r % a.strips;
+        bz = r / a.strips;
+    }
+    if (bz >= a.N) return;  // padding between the layers of the launch
     if (a.stride == 2)
         dw_body_v4<2, 4>(a, bx, by, bz);
     else if (a.strip_rows == 8)
@@ -421,13 +440,21 @@ extern "C" int prom_dw_conv_sequence(const prom_dw_layer_t *layers, int count, i
         }
         if (j - i >= 2) {
             b.count = j - i;
+            // the members with the least work first: a small layer is a latency chain per workgroup and
+            // would otherwise end the launch alone
+            int order[kDwMaxBatch];
+            for (int k = 0; k < j - i; ++k) order[k] = i + k;
+            std::stable_sort(order, order + (j - i), [&](int p, int q) {
+                return prepared[(size_t)p].xbytes + prepared[(size_t)p].ybytes <
+                       prepared[(size_t)q].xbytes + prepared[(size_t)q].ybytes;
+            });
             int start = 0;
-            for (int k = i; k < j; ++k) {
-                const DwLaunch &L = prepared[(size_t)k];
-                b.layer[k - i] = L.a;
-                b.xblocks[k - i] = (int)L.grid.x;
-                b.start[k - i] = start;
-                start += (int)(L.grid.x * L.grid.y * L.grid.z);
+            for (int k = 0; k < j - i; ++k) {
+                const DwLaunch &L = prepared[(size_t)order[k]];
+                b.layer[k] = L.a;
+                b.xblocks[k] = (int)L.grid.x;
+                b.start[k] = start;
+                start += (int)((L.grid.x * L.grid.y * L.grid.z + 7) / 8 * 8);
             }
             b.start[j - i] = start;
             hipLaunchKernelGGL(dw_batch_kernel, dim3((unsigned)start), dim3(256), 0, st, b);
