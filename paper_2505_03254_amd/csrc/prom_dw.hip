@@ -208,10 +208,22 @@ __device__ __forceinline__ void dw_body_v4(const DwArgs &a, const int bx, const 
         epilogue(std::false_type{});
 }
 
+// xb == 0: the grid is (columns x channels, row strips, images).  xb > 0 (that many workgroups per row
+// strip, images a multiple of 8): a 1-D grid in which 8 consecutive workgroups are the same place in
+// 8 images -- workgroups go round-robin over the 8 XCDs, so each XCD has whole images and the
+// workgroups that share input lines share its L2.
 template <int S, int ROWS = 4>
-__global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a)
+__global__ __launch_bounds__(256) void dw_kernel_v4(const DwArgs a, const int xb)
 {
-    dw_body_v4<S, ROWS>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    if (xb > 0) {
+        const int l = blockIdx.x;
+        const int per_img = xb * a.strips;
+        const int k = l >> 3;
+        const int within = k % per_img;
+        dw_body_v4<S, ROWS>(a, within % xb, within / xb, (k / per_img) * 8 + (l & 7));
+    } else {
+        dw_body_v4<S, ROWS>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    }
 }
 
 // Several independent depthwise layers in one launch: workgroups [start[i], start[i+1]) run layer i
@@ -366,12 +378,18 @@ static void dw_launch(const DwLaunch &L, hipStream_t st)
     const DwArgs &a = L.a;
     if (!L.fast)
         hipLaunchKernelGGL(dw_kernel_generic, L.grid, dim3(256), 0, st, a);
-    else if (a.stride == 1 && a.strip_rows == 8)
-        hipLaunchKernelGGL((dw_kernel_v4<1, 8>), L.grid, dim3(256), 0, st, a);
-    else if (a.stride == 1)
-        hipLaunchKernelGGL(dw_kernel_v4<1>, L.grid, dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL(dw_kernel_v4<2>, L.grid, dim3(256), 0, st, a);
+    else {
+        const long long blocks = (long long)L.grid.x * L.grid.y * L.grid.z;
+        const bool flat = (a.N & 7) == 0 && blocks <= (1LL << 30);
+        const dim3 grid = flat ? dim3((unsigned)blocks) : L.grid;
+        const int xb = flat ? (int)L.grid.x : 0;
+        if (a.stride == 1 && a.strip_rows == 8)
+            hipLaunchKernelGGL((dw_kernel_v4<1, 8>), grid, dim3(256), 0, st, a, xb);
+        else if (a.stride == 1)
+            hipLaunchKernelGGL(dw_kernel_v4<1>, grid, dim3(256), 0, st, a, xb);
+        else
+            hipLaunchKernelGGL(dw_kernel_v4<2>, grid, dim3(256), 0, st, a, xb);
+    }
 }
 
 // true if running `b` concurrently with `a` could change a result
