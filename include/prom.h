@@ -342,7 +342,9 @@ typedef struct {
  * output) share one kernel launch, up to 24 of them, and run concurrently; anything else is
  * launched layer by layer.  All layers are validated first; on an argument error nothing is
  * enqueued and the index of the offending layer is stored in *bad_layer when bad_layer is not
- * NULL.  PROM_EHIP if a launch fails (earlier launches stay enqueued). */
+ * NULL (a layer with group size 1 is handed to prom_dw_conv when its turn comes, and what that
+ * call checks beyond pointers, sizes and the window is checked then).  PROM_EHIP if a launch fails
+ * (earlier launches stay enqueued). */
 int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int count, int *bad_layer, void *stream);
 
 /* Bytes of the prepared form of prom_gconv_pack; 0 if the matrix-core kernel does not take this
