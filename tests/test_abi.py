@@ -113,6 +113,24 @@ def test_argument_errors_are_reported_before_any_launch(P):
     args2 = (X, 1, 8, 8, 16, 96, 24, 1, Wq, r, Wq + 4096, r, Wq + 8192, r)
     assert lib.prom_block(*args2, 1, ws, need, Y, None) == -1                     # residual needs cin == cout
     assert P.prom_block_workspace_size(1, 8, 8, 16, 96, 16, 3) == 0
+    # grouped 3x3 and its sequence: refused before anything is enqueued, with the offending layer's index
+    from paper_2505_03254_amd.binding import _GconvLayerC
+    assert lib.prom_gconv3x3(X, 1, 8, 8, 16, Wq, None, 4, 3, r, Y, None) == -1      # stride
+    assert lib.prom_gconv3x3(X, 1, 8, 8, 16, Wq, None, 5, 1, r, Y, None) == -1      # 16 % 5 != 0
+    assert lib.prom_gconv3x3(X, 1, 8, 8, 16, Wq, None, 4, 1, r, X + 64, None) == -3  # y overlaps x
+    assert lib.prom_gconv3x3(X, 1, 8, 8, 16, Wq, Wq + 8, 4, 1, r, Y, None) == -1    # prepared weights misaligned
+    arr = (_GconvLayerC * 2)()
+    for k in range(2):
+        l = arr[k]
+        l.x, l.n, l.h, l.w, l.c = X + k * 0x100000, 1, 8, 8, 16
+        l.w_g, l.w_frag, l.group_size, l.stride = Wq + k * 0x1000, None, 4, 1
+        l.rq, l.y = rq, Y + k * 0x100000
+    arr[1].group_size = 3
+    bad_layer = ctypes.c_int(-7)
+    assert lib.prom_gconv3x3_sequence(arr, 2, ctypes.byref(bad_layer), None) == -1 and bad_layer.value == 1
+    assert lib.prom_gconv3x3_sequence(arr, -1, None, None) == -1
+    assert lib.prom_gconv3x3_sequence(None, 2, None, None) == -1
+    assert lib.prom_gconv3x3_sequence(None, 0, ctypes.byref(bad_layer), None) == 0 and bad_layer.value == -1
 
 
 def test_host_side_queries_of_the_launch_forms(P):
