@@ -719,11 +719,26 @@ __device__ __forceinline__ int gconv_batch_member(const GconvBatchArgs &b)
     return m;
 }
 
+#ifdef PROM_TIMELINE
+// Developer build: member, entry and exit clock of the first 2048 workgroups of a shared launch.
+__device__ unsigned long long g_gcb_stamps[2048 * 3];
+#endif
+
 template <int PT>
 __global__ __launch_bounds__(kTapkThreads, 2) void gconv_tapk_batch_kernel(const GconvBatchArgs b)
 {
     const int m = gconv_batch_member(b);
+#ifdef PROM_TIMELINE
+    if (threadIdx.x == 0 && blockIdx.x < 2048) {
+        g_gcb_stamps[blockIdx.x * 3] = (unsigned long long)m;
+        g_gcb_stamps[blockIdx.x * 3 + 1] = wall_clock64();
+    }
+#endif
     gconv_tapk_body<PT>(b.a[m], b.bd[m], (int)blockIdx.x - b.start[m]);
+#ifdef PROM_TIMELINE
+    __builtin_amdgcn_s_waitcnt(0);
+    if (threadIdx.x == 0 && blockIdx.x < 2048) g_gcb_stamps[blockIdx.x * 3 + 2] = wall_clock64();
+#endif
 }
 
 __global__ __launch_bounds__(256, 2) void gconv_mfma_batch_kernel(const GconvBatchArgs b)
@@ -1016,35 +1031,80 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
         if (j - i >= 2) {
             rc = gconv_set_attributes();
             if (rc == PROM_OK) {
+                // The launch has as many workgroups as are resident at once (two per compute unit):
+                // alone, a small layer spreads over the chip for the sake of latency; here that would
+                // queue thousands of workgroups that each live one latency chain long.  They are shared
+                // out so that every layer's workgroups live about equally long, by an estimate of a
+                // workgroup's time per unit of work (a fixed part for staging, barriers and the fetch
+                // latency, plus the rounds in which its four wavefronts take the unit's groups of 32
+                // pixels; fitted to the per-workgroup lifetimes of such a launch): the layer whose
+                // workgroups would live longest gets the next ones.  Shares by the bytes alone leave the
+                // layers with small images far behind (a unit of three 7x7 images takes as long as a
+                // band of 112 pixels), shares by the rounds alone the large ones.
+                const int n = j - i;
+                double cost[kGconvMaxBatch];
+                int per_cb[kGconvMaxBatch], step[kGconvMaxBatch];
+                double cost_sum = 0;
+                for (int k = 0; k < n; ++k) {
+                    const GconvLaunch &L = prepared[(size_t)(i + k)];
+                    const int npix = (L.bd.G > 1 ? L.bd.G : 1) * L.bd.R * L.a.Wo;
+                    const int rounds = ((npix + 31) / 32 + 3) / 4;
+                    cost[k] = (double)L.bd.ncb * L.bd.units * (2.0 + 1.3 * rounds);
+                    cost_sum += cost[k];
+                }
+                int used = 0;
+                for (int k = 0; k < n; ++k) {
+                    const GconvBand &bd = prepared[(size_t)(i + k)].bd;
+                    const double ideal = kGconvBatchSlots * cost[k] / cost_sum / bd.ncb;
+                    // several channel blocks and enough workgroups: multiples of 8, for the XCD-aware order
+                    step[k] = (bd.ncb > 1 && ideal >= 8 && bd.units >= 8) ? 8 : 1;
+                    int w = (int)(ideal / step[k]) * step[k];
+                    if (w < step[k]) w = step[k];
+                    if (w > bd.units) w = bd.units / step[k] * step[k];
+                    per_cb[k] = w;
+                    used += w * bd.ncb;
+                }
+                for (;;) {  // the remaining workgroups, one step at a time, to the layer that would end last
+                    int best = -1;
+                    double best_life = 0;
+                    for (int k = 0; k < n; ++k) {
+                        const GconvBand &bd = prepared[(size_t)(i + k)].bd;
+                        if (per_cb[k] + step[k] > bd.units || used + step[k] * bd.ncb > kGconvBatchSlots) continue;
+                        const double life = cost[k] / ((double)per_cb[k] * bd.ncb);
+                        if (best < 0 || life > best_life) {
+                            best = k;
+                            best_life = life;
+                        }
+                    }
+                    if (best < 0) break;
+                    per_cb[best] += step[best];
+                    used += step[best] * prepared[(size_t)(i + best)].bd.ncb;
+                }
+                // Order: the layers without the XCD-aware order first, packed without gaps (padding
+                // blocks would leave some XCDs with more workgroups than they can hold at once), then,
+                // from a multiple of 8 on, the others; within each kind the least bytes first (a small
+                // layer is one latency chain per workgroup and would otherwise end the launch alone).
                 int order[kGconvMaxBatch];
-                for (int k = 0; k < j - i; ++k) order[k] = i + k;
-                std::stable_sort(order, order + (j - i), [&](int p, int q) {
-                    return prepared[(size_t)p].xbytes + prepared[(size_t)p].ybytes <
-                           prepared[(size_t)q].xbytes + prepared[(size_t)q].ybytes;
+                for (int k = 0; k < n; ++k) order[k] = k;
+                std::stable_sort(order, order + n, [&](int p, int q) {
+                    const bool sp = step[p] == 8, sq = step[q] == 8;
+                    if (sp != sq) return !sp;
+                    return prepared[(size_t)(i + p)].xbytes + prepared[(size_t)(i + p)].ybytes <
+                           prepared[(size_t)(i + q)].xbytes + prepared[(size_t)(i + q)].ybytes;
                 });
-                b.count = j - i;
-                // The launch has as many workgroups as are resident at once (two per compute unit),
-                // shared out by the bytes the layers move: alone, a small layer spreads over the chip
-                // for the sake of latency; here that would queue thousands of workgroups that each
-                // live one latency chain long.  (Shares by an estimate of the rounds of MFMA work
-                // instead of the bytes were measured and are worse.)
-                double total = 0;
-                for (int k = 0; k < j - i; ++k) total += (double)(prepared[(size_t)order[k]].xbytes + prepared[(size_t)order[k]].ybytes);
+                b.count = n;
                 int start = 0;
                 size_t lds = 0;
-                for (int k = 0; k < j - i; ++k) {
-                    const GconvLaunch &L = prepared[(size_t)order[k]];
+                for (int k = 0; k < n; ++k) {
+                    const int m = order[k];
+                    const GconvLaunch &L = prepared[(size_t)(i + m)];
                     b.a[k] = L.a;
                     b.bd[k] = L.bd;
-                    const double share = (double)(L.xbytes + L.ybytes) / total;
-                    long long per_cb = (long long)(kGconvBatchSlots * share / L.bd.ncb + 0.5);
-                    if (per_cb > L.bd.units) per_cb = L.bd.units;
-                    if (per_cb < 1) per_cb = 1;
-                    if (per_cb >= 8) per_cb -= per_cb % 8;  // for the XCD-aware order (measured: 10 % on ResNeXt)
-                    b.bd[k].wgs_per_cb = (int)per_cb;
-                    b.bd[k].swizzle = per_cb % 8 == 0;
-                    b.start[k] = start;  // a multiple of 8: a member's workgroup index tells its XCD
-                    start += (int)((per_cb * L.bd.ncb + 7) / 8 * 8);
+                    b.bd[k].wgs_per_cb = per_cb[m];
+                    b.bd[k].swizzle = step[m] == 8;
+                    if (step[m] == 8) start = (start + 7) / 8 * 8;  // a member's workgroup index tells its XCD
+                    b.start[k] = start;
+                    start += per_cb[m] * L.bd.ncb;
                     if (L.lds > lds) lds = L.lds;
                 }
                 b.start[j - i] = start;
@@ -1069,6 +1129,11 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
 }
 
 #ifdef PROM_TIMELINE
+extern "C" int prom_debug_gcb_stamps(unsigned long long *host)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return PROM_EHIP;
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(prom::g_gcb_stamps), sizeof(unsigned long long) * 2048 * 3) == hipSuccess ? PROM_OK : PROM_EHIP;
+}
 extern "C" int prom_debug_gc_stamps(unsigned long long *host)
 {
     if (hipDeviceSynchronize() != hipSuccess) return PROM_EHIP;
