@@ -206,3 +206,41 @@ def test_gconv_sequence_errors_and_empty(P):
     with pytest.raises(P.PromError) as err:
         P.prom_gconv3x3_sequence([tuple(e3)])
     assert err.value.code == -3
+
+
+@pytest.mark.parametrize("family", ["regnetx_400mf", "resnext50_32x4d"])
+def test_gconv_sequence_at_benchmark_size_equals_layer_by_layer(P, family):
+    """The shared launches of the benchmark's configuration (batch 128, every grouped 3x3 layer of the
+    network in one call: workgroup shares, XCD-aware order and padding as timed there) give, byte for
+    byte, what the layers give one by one (the single-layer path is checked against the oracle above,
+    one full-size layer on every output)."""
+    torch = torch_cuda()
+    from workloads import regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers
+    shapes = regnetx_400mf_grouped_layers() if family == "regnetx_400mf" else resnext50_32x4d_grouped_layers()
+    batch = 128
+    entries, singles = [], []
+    for i, g in enumerate(shapes):
+        G = make_gconv_layer(16000 + i, 1, 4, 4, g.c, g.gs, g.stride, shift_range=(8, 17) if i % 3 else (0, 31))
+        ho = (g.hw_in - 1) // g.stride + 1
+        x = torch.randint(-128, 128, (batch, g.hw_in, g.hw_in, g.c), dtype=torch.int8, device="cuda:0")
+        rq = P.Requant(dev(G.bias), dev(G.mult), dev(G.shift), -128, 127)
+        w = dev(G.weight)
+        frag = dev(P.prom_gconv_pack(G.weight))
+        y = torch.full((batch, ho, ho, g.c), 77, dtype=torch.int8, device="cuda:0")
+        entries.append((x, w, g.stride, rq, y, frag))
+        singles.append(P.prom_gconv3x3(x, w, g.stride, rq, w_frag=frag))
+    P.prom_gconv3x3_sequence(entries)
+    torch.cuda.synchronize()
+    for i, (e, want) in enumerate(zip(entries, singles)):
+        assert torch.equal(e[4], want), f"{family} layer {i} {shapes[i]}"
+    # one layer of each shape against the oracle on a sample of images
+    seen = set()
+    for i, g in enumerate(shapes):
+        key = (g.hw_in, g.c, g.gs, g.stride)
+        if key in seen or g.hw_in > 28:
+            continue
+        seen.add(key)
+        G = make_gconv_layer(16000 + i, 1, 4, 4, g.c, g.gs, g.stride, shift_range=(8, 17) if i % 3 else (0, 31))
+        xs = entries[i][0][:2].cpu().numpy()
+        want = oracle.gconv3x3(xs, G.weight, g.stride, G.bias, G.mult, G.shift, -128, 127)
+        assert_same(entries[i][4][:2].cpu().numpy(), want, f"{family} layer {i} against the oracle")
