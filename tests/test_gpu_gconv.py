@@ -244,3 +244,32 @@ def test_gconv_sequence_at_benchmark_size_equals_layer_by_layer(P, family):
         xs = entries[i][0][:2].cpu().numpy()
         want = oracle.gconv3x3(xs, G.weight, g.stride, G.bias, G.mult, G.shift, -128, 127)
         assert_same(entries[i][4][:2].cpu().numpy(), want, f"{family} layer {i} against the oracle")
+
+
+def test_gconv_matrix_core_kernels_on_random_shapes(P):
+    """Seeded random shapes for the two matrix-core kernels: odd sizes down to one pixel, channel counts
+    that leave a partial block of 64, several images per unit of work, both strides, all three epilogue
+    forms, prepared and unprepared weights; and the same layers again through one sequence call."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(20250511)
+    entries, wants = [], []
+    for case in range(48):
+        gs = int(rng.choice([4, 8, 16, 32, 64]))
+        c = gs * int(rng.integers(1, max(2, 200 // gs)))
+        n, h, w = int(rng.integers(1, 10)), int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        stride = int(rng.integers(1, 3))
+        prelu = bool(rng.integers(0, 2))
+        window = [(-128, 127), (0, 127), (-7, 19)][int(rng.integers(0, 3))]
+        sr = (8, 17) if rng.integers(0, 2) else (0, 31)
+        G = make_gconv_layer(17000 + case, n, h, w, c, gs, stride, signed_x=True, act_window=window, shift_range=sr)
+        mneg = prelu_mult_neg(17000 + case, G.mult) if prelu else None
+        use_frag = bool(rng.integers(0, 2))
+        want = _want(G, window, mneg)
+        got = _run(P, G, window, mneg, use_frag=use_frag)
+        assert_same(got, want, f"case {case}: n={n} h={h} w={w} c={c} gs={gs} s={stride} prelu={prelu} {window} frag={use_frag}")
+        entries.append(_seq_entry(P, G, window, mneg, use_frag))
+        wants.append(want)
+    P.prom_gconv3x3_sequence(entries)
+    torch.cuda.synchronize()
+    for case, (e, want) in enumerate(zip(entries, wants)):
+        assert_same(e[4].cpu().numpy(), want, f"sequence, case {case}")
