@@ -82,3 +82,27 @@ def test_sequence_reports_the_offending_layer_and_enqueues_nothing(P):
         P.prom_dw_conv_sequence([(x, w, 1, rq, x)])
     P.prom_dw_conv_sequence([])                                                             # empty: nothing to do
     torch.cuda.synchronize()
+
+
+def test_batches_that_are_multiples_of_eight_take_the_image_order(P):
+    """With a multiple of 8 images a layer's workgroups are laid out so that 8 consecutive ones are the
+    same place in 8 images (alone: a flat grid; in a shared launch: per member, with the members'
+    ranges padded to multiples of 8); mixed here with batches that keep the plain order."""
+    torch = torch_cuda()
+    shapes = [(8, 14, 14, 96, 1), (16, 7, 7, 160, 1), (3, 9, 13, 24, 1), (8, 28, 28, 32, 2), (24, 5, 6, 64, 1),
+              (8, 17, 11, 48, 2), (5, 8, 8, 16, 1), (16, 12, 12, 40, 1)]
+    layers, wants = [], []
+    for i, (n, h, w, c, s) in enumerate(shapes):
+        D = make_dw_layer(7500 + i, n, h, w, c, s, signed_x=True, act_window=(-128, 127))
+        ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+        y = torch.full((n, ho, wo, c), -77, dtype=torch.int8, device="cuda")
+        layers.append((dev(D.x), dev(D.weight), s, requant_dev(P, D), y))
+        wants.append(want_of(D, s))
+        # alone
+        got = P.prom_dw_conv(layers[-1][0], layers[-1][1], s, layers[-1][3])
+        torch.cuda.synchronize()
+        assert_same(got.cpu().numpy(), wants[-1], f"alone {shapes[i]}")
+    P.prom_dw_conv_sequence(layers)
+    torch.cuda.synchronize()
+    for shape, want, lay in zip(shapes, wants, layers):
+        assert_same(lay[4].cpu().numpy(), want, f"in one call {shape}")
