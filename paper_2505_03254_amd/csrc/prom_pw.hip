@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void pw_batch_kernel(const PwBatchArgs b)
     const int local = bid - b.start[i];
     const int nblk = b.start[i + 1] - b.start[i];
     const PwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
-    const int lid = logical_block_id(local, nblk);
+    const int lid = logical_block_id(local, nblk, i);
 #ifdef PROM_TIMELINE
     TimelineScope timeline_scope(bid, i);
 #endif

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256, 2) void pw_bigbatch_kernel(const PwBatchArgs b
     const int bid = blockIdx.x;
     int i = 0;
     while (i + 1 < b.count && bid >= b.start[i + 1]) ++i;
-    const int lid = logical_block_id(bid - b.start[i], b.start[i + 1] - b.start[i]);
+    const int lid = logical_block_id(bid - b.start[i], b.start[i + 1] - b.start[i], i);
     const PwArgs a = b.layer[i];  // a copy: a reference into the by-value argument can force all of it into scratch memory
     if constexpr (EPI != kEpiPlain) {
         if (a.mult_neg) {

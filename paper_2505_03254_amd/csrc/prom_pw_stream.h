@@ -195,6 +195,13 @@ __device__ __forceinline__ int logical_block_id(int bid, int nblk /* multiple of
     return (bid & 7) * (nblk >> 3) + (bid >> 3);
 }
 __device__ __forceinline__ int logical_block_id() { return logical_block_id(blockIdx.x, gridDim.x); }
+// The same for member `m` of a shared launch.  A member's grid is padded to a multiple of 8 and the
+// padding is its last logical ids, i.e. all in one XCD's eighth; the eighths are handed to the XCDs
+// rotated by the member's index, so that it is not the same XCD that comes short in every member.
+__device__ __forceinline__ int logical_block_id(int bid, int nblk, int m)
+{
+    return ((bid + m) & 7) * (nblk >> 3) + (bid >> 3);
+}
 
 // Depth of the activation prefetch ring (load groups in flight per wavefront).
 template <int PT> __host__ __device__ constexpr int ring_depth() { return PT == 1 ? 4 : 3; }
