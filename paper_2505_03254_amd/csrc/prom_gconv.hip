@@ -3,6 +3,11 @@
 // ResNeXt have this layer where MobileNetV2 has the depthwise convolution (paper Section 2); its
 // weights are 8-bit with one scale per output channel (Section 3.1, Eq. 4-5).
 //
+// Kernels, by group size: 4, 8, 16 -> gconv_tapk_kernel (matrix cores, the kernel taps in the k
+// dimension); 32, 64 -> gconv_mfma_kernel (matrix cores, one k step per tap); other multiples of 4
+// -> gconv_kernel_v4 (vector ALU); anything else -> gconv_kernel_generic; 1 is prom_dw_conv.  The
+// *_batch_kernel forms run several independent layers in one launch (prom_gconv3x3_sequence).
+//
 // gconv_kernel_v4: a thread owns 4 consecutive output channels (they lie in one group, gs being
 // a multiple of 4) of one output column and 4 consecutive output rows; lanes run over channels,
 // then columns.  For each of the 3 kernel columns it loads the gs input bytes of its group (in
