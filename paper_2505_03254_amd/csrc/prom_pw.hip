@@ -556,7 +556,13 @@ static bool batchable(const PwLaunch &L)
     const PwArgs &a = L.a;
     if (!L.fast || L.gemm || L.mode != 0 || a.K % 16 != 0 || a.Nc % 16 != 0) return false;
     if (batch_nt(a) * a.KS * 1024 > kLdsBudget) return false;
-    return (long long)a.M * (a.K + a.Nc) <= kBatchMaxBytes;
+    const long long bytes = (long long)a.M * (a.K + a.Nc);
+    if (bytes <= kBatchMaxBytes) return true;
+    // larger layers too, up to four times that, when the launch of the large layers has no body for
+    // their plan: alone in a sequence of independent layers they would stream at their own
+    // launch's pace (batch 256: eight layers of MobileNetV2, 2.5 TB/s one by one)
+    const bool has_big_body = L.big_body >= 0 && L.lds <= (size_t)kLdsBudget;
+    return !has_big_body && bytes <= 4 * kBatchMaxBytes;
 }
 
 struct Range { uintptr_t lo, hi; };
