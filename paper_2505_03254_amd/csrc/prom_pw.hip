@@ -561,8 +561,11 @@ static bool batchable(const PwLaunch &L)
     // larger layers too, up to four times that, when the launch of the large layers has no body for
     // their plan: alone in a sequence of independent layers they would stream at their own
     // launch's pace (batch 256: eight layers of MobileNetV2, 2.5 TB/s one by one)
+    // Only layers with a small weight matrix: the bodies of the shared launch re-read the
+    // activations once per chunk of output channels, which wide layers with many input channels
+    // (ResNeXt: 256 -> 512 at 28x28) pay for; those are faster alone.
     const bool has_big_body = L.big_body >= 0 && L.lds <= (size_t)kLdsBudget;
-    return !has_big_body && bytes <= 4 * kBatchMaxBytes;
+    return !has_big_body && bytes <= 4 * kBatchMaxBytes && (long long)a.K * a.Nc <= 64 * 1024;
 }
 
 struct Range { uintptr_t lo, hi; };
