@@ -504,27 +504,36 @@ def quick_sweep(P, torch, dev, batch, zero_fraction, steps=20):
     fraction: seeded weights and parameters, random activations (no parity check here: the parity
     tests cover these shapes), same timing as the main timed region."""
     from workloads import make_pw_layer, mobilenetv2_pointwise_layers
-    seq_layers, nbytes, ops = [], 0, 0
-    for i, s in enumerate(mobilenetv2_pointwise_layers()):
+    shapes = mobilenetv2_pointwise_layers()
+    nbytes = sum(layer_bytes(batch * s.hw * s.hw, s.cin, s.cout) for s in shapes)
+    ops = sum(2 * batch * s.hw * s.hw * s.cin * s.cout for s in shapes)
+    # a sweep whose tensors would fit the 256 MB last-level cache (batch 32: 220 MB) rotates over
+    # several sets of them, so that no step finds its input cached by the step before
+    nsets = max(1, -(-600_000_000 // nbytes))
+    params = []
+    for i, s in enumerate(shapes):
         L = make_pw_layer(SEED + 7000 + i, 1, 1, 1, s.cin, s.cout, p_zero=zero_fraction)
-        x = torch.randint(0, 128, (batch, s.hw, s.hw, s.cin), dtype=torch.int8, device=dev)
-        y = torch.empty((batch, s.hw, s.hw, s.cout), dtype=torch.int8, device=dev)
-        rq = P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
-                       torch.from_numpy(L.shift).to(dev), 0, 127)
-        seq_layers.append((x, torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev), s.cout, rq, None, y))
-        m = batch * s.hw * s.hw
-        nbytes += layer_bytes(m, s.cin, s.cout)
-        ops += 2 * m * s.cin * s.cout
-    seq = P.PwSequence(seq_layers)
-    for _ in range(60):  # (to the sustained rate, as the main timed region)
-        seq.run()
+        params.append((torch.from_numpy(P.prom_pack_ternary(L.weight)).to(dev),
+                       P.Requant(torch.from_numpy(L.bias).to(dev), torch.from_numpy(L.mult).to(dev),
+                                 torch.from_numpy(L.shift).to(dev), 0, 127)))
+    seqs = []
+    for _ in range(nsets):
+        seq_layers = []
+        for s, (wp, rq) in zip(shapes, params):
+            x = torch.randint(0, 128, (batch, s.hw, s.hw, s.cin), dtype=torch.int8, device=dev)
+            y = torch.empty((batch, s.hw, s.hw, s.cout), dtype=torch.int8, device=dev)
+            seq_layers.append((x, wp, s.cout, rq, None, y))
+        seqs.append(P.PwSequence(seq_layers))
+    for k in range(60 * nsets):  # (to the sustained rate, as the main timed region)
+        seqs[k % nsets].run()
     torch.cuda.synchronize()
+    steps *= nsets
     t0 = time.perf_counter()
-    for _ in range(steps):
-        seq.run()
+    for k in range(steps):
+        seqs[k % nsets].run()
     torch.cuda.synchronize()
     us = (time.perf_counter() - t0) * 1e6 / steps
-    return {"batch": batch, "weight_zero_fraction": zero_fraction, "us": round(us, 1),
+    return {"batch": batch, "weight_zero_fraction": zero_fraction, "tensor_sets_in_rotation": nsets, "us": round(us, 1),
             "gops": round(ops / (us * 1e-6) / 1e9, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1),
             "frac_hbm_roofline": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 
@@ -579,19 +588,29 @@ def family_leg(P, torch, dev, batch, shapes, log, tag):
             f"{rows[-1]['bound']:>4}-bound  {100 * rows[-1]['frac_roofline']:5.1f} % of its roofline")
         tensors[(hw, k, n, res)] = (xs[0], wp, n, rq, r, ys[0])
         del xs, ys, seqs
-    # the whole network's layers in one call (independent here: the library may share launches)
-    # (own outputs per layer: layers that write the same buffer are ordered, not concurrent)
-    seq_layers = []
-    for sh in shapes:
-        x, wp, n, rq, r, y = tensors[(sh.hw, sh.cin, sh.cout, sh.residual)]
-        seq_layers.append((x, wp, n, rq, r, torch.empty_like(y)))
-    seq = P.PwSequence(seq_layers)
-    settle(torch, lambda j: seq.run(), ms=40.0)
+    # the whole network's layers in one call (independent here: the library may share launches).
+    # Every layer has tensors of its own, as in the network (layers of one shape that read the same
+    # input would find it cached, and layers that write the same buffer are ordered, not
+    # concurrent); a network that would fit the last-level cache rotates over several sets.
+    total = sum(layer_bytes(batch * sh.hw * sh.hw, sh.cin, sh.cout, sh.residual) for sh in shapes)
+    nsets = max(1, -(-600_000_000 // total))
+    seqs = []
+    for _ in range(nsets):
+        seq_layers = []
+        for sh in shapes:
+            x, wp, n, rq, r, y = tensors[(sh.hw, sh.cin, sh.cout, sh.residual)]
+            seq_layers.append((torch.randint(0, 128, x.shape, dtype=torch.int8, device=dev), wp, n, rq,
+                               torch.randint(-64, 64, y.shape, dtype=torch.int8, device=dev) if r is not None else None,
+                               torch.empty_like(y)))
+        seqs.append(P.PwSequence(seq_layers))
+    del tensors
+    settle(torch, lambda j: seqs[j % nsets].run(), ms=40.0)
+    reps = 20 * nsets
     t0 = time.perf_counter()
-    for _ in range(20):
-        seq.run()
+    for j in range(reps):
+        seqs[j % nsets].run()
     torch.cuda.synchronize()
-    seq_us = (time.perf_counter() - t0) * 1e6 / 20
+    seq_us = (time.perf_counter() - t0) * 1e6 / reps
     sum_us = sum(r["us"] * r["count"] for r in rows)
     roof_us = sum(r.pop("roofline_us") * r["count"] for r in rows)
     log(f"[bench] {tag}: one launch per layer {sum_us:.1f} us ({100 * roof_us / sum_us:.1f} % of the per-layer "

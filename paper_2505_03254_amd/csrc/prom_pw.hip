@@ -550,6 +550,17 @@ namespace prom {
 // dominated by fixed costs.
 constexpr long long kBatchMaxBytes = 32LL << 20;
 constexpr long long kBatchBytesPerWg = 256LL << 10;  // bytes the first workgroups of a batch move (later ones less)
+constexpr long long kBatchRefWork = 300LL << 20;     // launches with at least this much work take pieces of that size
+constexpr long long kBigRefWork = 400LL << 20;       // the same for the launch of large layers
+
+// Factor on the piece size (bytes or time per workgroup) of a shared launch with `work` bytes.
+static double launch_scale(long long work, long long ref_work)
+{
+    // (proportional: with the square or the cube of the ratio the MobileNetV2 sweep at batch 32
+    // takes 97 and 116 us instead of 81, at batch 64 125 and 141 instead of 128)
+    const double s = (double)work / (double)ref_work;
+    return s >= 1.0 ? 1.0 : (s < 0.0625 ? 0.0625 : s);
+}
 
 static bool batchable(const PwLaunch &L)
 {
@@ -746,11 +757,15 @@ static int launch_batch(const PwLaunch *const *members, int count, hipStream_t s
     std::stable_sort(order, order + count, [&](int p, int q) {
         return plans[p].work * plans[p].a.n_chunks < plans[q].work * plans[q].a.n_chunks;
     });
+    // The piece sizes were chosen on a launch of some 400 MB (about 100 us); a launch with less work
+    // takes proportionally smaller pieces, or a few long workgroups would be all of it.
+    const double scale = launch_scale(total_work, kBatchRefWork);
+    const long long first_wg = (long long)(kBatchBytesPerWg * scale);
     for (int k = 0; k < count; ++k) {
         SmallPlan &sp = plans[order[k]];
-        const long long per_wg = done_work * 10 < total_work * 7   ? kBatchBytesPerWg
-                                 : done_work * 10 < total_work * 9 ? kBatchBytesPerWg / 2
-                                                                   : kBatchBytesPerWg / 4;
+        const long long per_wg = done_work * 10 < total_work * 7   ? first_wg
+                                 : done_work * 10 < total_work * 9 ? first_wg / 2
+                                                                   : first_wg / 4;
         done_work += sp.work * sp.a.n_chunks;
         const int nblk = size_small_member(sp, per_wg);
         b.layer[k] = sp.a;
@@ -794,6 +809,10 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         const int width = 16 * L.nt * (L.rows ? L.a.cw : 1);
         total_work += (long long)L.a.M * (L.a.K + width) * L.a.n_chunks;
     }
+    // (workgroup sizes below were measured on a launch of 500 MB; less work, smaller pieces)
+    const double scale = launch_scale(total_work, kBigRefWork);
+    const long long big_wg = (long long)(kBigBytesPerWg * scale);
+    const double wg_micros = kBigWgMicros * scale;
     for (int i = 0; i < count; ++i) {
         const PwLaunch &L = *members[i];
         PwArgs a = L.a;  // keeps its own plan (tiles, pixel tiles, chunks); only the grid changes
@@ -804,9 +823,9 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         const int body = pw_big_replan(L.big_body, a, &replanned);
         if (replanned) per_step = replanned;
         const long long wg_units = (a.units + per_step - 1) / per_step;
-        const long long per_wg = done_work * 10 < total_work * 8   ? kBigBytesPerWg
-                                 : done_work * 20 < total_work * 19 ? kBigBytesPerWg / 2
-                                                                    : kBigBytesPerWg / 4;
+        const long long per_wg = done_work * 10 < total_work * 8   ? big_wg
+                                 : done_work * 20 < total_work * 19 ? big_wg / 2
+                                                                    : big_wg / 4;
         done_work += work * a.n_chunks;
         long long wgs = (work + per_wg - 1) / per_wg;
         // Bodies differ in speed (3 to 18 ns per pixel and workgroup), and workgroups of equal
@@ -818,7 +837,7 @@ static int launch_big(const PwLaunch *const *members, int count, hipStream_t st)
         const double ns = a.KS <= 3 ? pw_big_body_ns_per_pixel(body) : 0.0;
         if (ns > 0) {
             const bool early = (done_work - work * a.n_chunks) * 10 < total_work * 7;
-            wgs = (long long)((double)a.M * ns / ((early ? kBigWgMicros : kBigWgMicros / 2) * 1000.0) + 0.999);
+            wgs = (long long)((double)a.M * ns / ((early ? wg_micros : wg_micros / 2) * 1000.0) + 0.999);
         }
         if (wgs < 1) wgs = 1;
         if (wgs > wg_units) wgs = wg_units;
