@@ -443,7 +443,13 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
     // streaming kernel): 14x14 1024 -> 512 33 against 37, 1024 -> 1024 56 against 63; 7x7
     // 1024 -> 2048 31 against 36, 2048 -> 1024 32 against 58.  With 512 and fewer input channels the
     // streaming kernel is the faster one (14x14 512 -> 1024 26 against 43 us, 28x28 512 -> 512 45
-    // against 76), so the library takes the tile kernel from 1024 input channels on.
+    // against 76), so the library takes the tile kernel from 1024 input channels on -- when its
+    // tiles fill the chip: a tile takes 6 us plus 0.65 us per k step however few there are, and with
+    // less than one tile per compute unit the streaming kernel, which spreads the pixels over more
+    // workgroups, is faster (batch 32: 14x14 1024 -> 512, 100 tiles, 13 against 19 us; 7x7
+    // 1024 -> 2048, 112 tiles, 13 against 20; 2048 -> 1024, 56 tiles, 19 against 26; 14x14
+    // 1024 -> 1024, 200 tiles, 22 against 20).  The two meet at about 180 tiles of 16 k steps and 80
+    // tiles of 32: tiles x k steps >= 2800.
     L.gemm = false;
     const int k_outer = plan ? plan->k_outer : 0;
     if (k_outer != 0 && k_outer != 1 && k_outer != -1) return PROM_EINVAL;
@@ -455,7 +461,9 @@ static int pw_prepare(const int8_t *x, int n, int h, int w, int cin, const void 
             return PROM_EINVAL;
     }
     const bool explicit_stream = plan && (plan->tiles_per_wave || plan->pixel_tiles || plan->row_waves);
-    if (gemm_ok && (k_outer == 1 || (k_outer == 0 && !explicit_stream && cin >= 1024 && cout >= 256))) {
+    const long long gemm_tiles = ((M + 255) / 256) * ((cout + 127) / 128);
+    const bool gemm_pays = cin >= 1024 && cout >= 256 && gemm_tiles * (cin / 64) >= 2800;
+    if (gemm_ok && (k_outer == 1 || (k_outer == 0 && !explicit_stream && gemm_pays))) {
         L.gemm = true;
         L.rows = false;
         a.cw = 0;

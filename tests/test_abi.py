@@ -160,8 +160,12 @@ def test_host_side_queries_of_the_launch_forms(P):
     assert P.prom_pw_plan_query(128, 7, 7, 1024, 128)["k_outer"] == 0
     assert P.prom_pw_plan_query(128, 14, 14, 960, 320)["k_outer"] == 0
     assert P.prom_pw_plan_query(128, 14, 14, 1032, 512)["k_outer"] == 0   # cin % 64
-    # wide layers never join a shared launch
-    assert P.prom_pw_batch_class(16, 7, 7, 1024, 512) == 0
+    # ... when its tiles fill the chip (tiles x k steps >= 2800)
+    assert P.prom_pw_plan_query(32, 7, 7, 2048, 1024)["k_outer"] == 0      # 56 tiles of 32 k steps
+    assert P.prom_pw_plan_query(32, 14, 14, 1024, 1024)["k_outer"] == 1    # 200 tiles of 16
+    assert P.prom_pw_plan_query(64, 7, 7, 2048, 1024)["k_outer"] == 1      # 104 tiles of 32
+    # layers that take the kernel for wide layers never join a shared launch
+    assert P.prom_pw_batch_class(128, 7, 7, 2048, 1024) == 0
 
 
 def test_binding_fails_loudly_without_library(P, monkeypatch):
