@@ -951,15 +951,30 @@ extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, i
     // layers run concurrently.  A layer that conflicts with a pending one forces both batches out
     // first; any other layer that fits no batch is launched at once and may overtake them.
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const PwLaunch *pending[2][kMaxBatch];
+    // (Small layers wait for up to two launches' worth: a network with more independent small
+    // layers than a launch holds is then not cut in sequence order, which would put its last, smallest
+    // layers -- one latency chain per workgroup -- in a launch of their own, but dealt out by size, so
+    // that each launch has large layers to stream behind its small ones.  RegNetX-400MF's 48 layers
+    // at batch 128: two launches of 24 instead of the first 32 and the last 16.)
+    constexpr int kMaxPending = 2 * kMaxBatch;
+    const PwLaunch *pending[2][kMaxPending];
     int npending[2] = {0, 0};
     int first_pending[2] = {0, 0};
     auto flush_one = [&](int c) -> int {
         int rc = PROM_OK;
-        if (npending[c] == 1)
+        if (npending[c] == 1) {
             rc = pw_launch(*pending[c][0], st);
-        else if (npending[c] > 1)
+        } else if (npending[c] > kMaxBatch) {
+            std::stable_sort(pending[c], pending[c] + npending[c], [](const PwLaunch *p, const PwLaunch *q) {
+                return (long long)p->a.M * (p->a.K + p->a.Nc) < (long long)q->a.M * (q->a.K + q->a.Nc);
+            });
+            const PwLaunch *half[2][kMaxBatch];
+            int nhalf[2] = {0, 0};
+            for (int k = 0; k < npending[c]; ++k) half[k & 1][nhalf[k & 1]++] = pending[c][k];
+            for (int h = 0; h < 2 && rc == PROM_OK; ++h) rc = launch_batch(half[h], nhalf[h], st);
+        } else if (npending[c] > 1) {
             rc = c == 0 ? launch_batch(pending[c], npending[c], st) : launch_big(pending[c], npending[c], st);
+        }
         npending[c] = 0;
         if (rc != PROM_OK && bad_layer) *bad_layer = first_pending[c];
         return rc;
@@ -981,7 +996,7 @@ extern "C" int prom_pw_conv_sequence(const prom_pw_layer_t *layers, int count, i
             if (rc != PROM_OK) return rc;
         }
         if (cls >= 0) {
-            if (npending[cls] == kMaxBatch) {
+            if (npending[cls] == (cls == 0 ? kMaxPending : kMaxBatch)) {
                 const int rc = flush_one(cls);
                 if (rc != PROM_OK) return rc;
             }

@@ -270,6 +270,33 @@ def test_sequence_batches_independent_layers_and_respects_dependencies(P):
         assert_same(ys2[i].cpu().numpy(), wnt, f"independent layer {i} with in-place residual")
 
 
+def test_sequence_of_more_independent_layers_than_two_launches_hold(P):
+    """75 independent small layers of mixed sizes in one call (a shared launch holds 32, the
+    library lets 64 wait and deals them out by size), then one layer that reads the first
+    layer's output: every output against the oracle."""
+    torch = torch_cuda()
+    shapes = [(16 * (1 + i % 6), 16 * (1 + (i * 5) % 7)) for i in range(75)]
+    Ls = [make_pw_layer(8300 + i, 1 + i % 3, 5 + i % 4, 7, ci, co, signed_x=True, act_window=(-128, 127),
+                        shift_range=(3, 8)) for i, (ci, co) in enumerate(shapes)]
+    ys = [torch.empty((L.x.shape[0], L.x.shape[1], L.x.shape[2], L.cout), dtype=torch.int8, device="cuda") for L in Ls]
+    layers = [(dev(L.x), dev(P.prom_pack_ternary(L.weight)), L.cout, requant_dev(P, L, (-128, 127)), None, y)
+              for L, y in zip(Ls, ys)]
+    last = make_pw_layer(8399, Ls[0].x.shape[0], Ls[0].x.shape[1], 7, Ls[0].cout, 48, signed_x=True,
+                         act_window=(-128, 127), shift_range=(3, 8))
+    y_last = torch.empty((*Ls[0].x.shape[:3], 48), dtype=torch.int8, device="cuda")
+    layers.append((ys[0], dev(P.prom_pack_ternary(last.weight)), 48, requant_dev(P, last, (-128, 127)), None, y_last))
+    P.PwSequence(layers).run()
+    torch.cuda.synchronize()
+    want0 = None
+    for i, (L, y) in enumerate(zip(Ls, ys)):
+        want = oracle.pw_conv(L.x, L.weight, L.bias, L.mult, L.shift, -128, 127)
+        if i == 0:
+            want0 = want
+        assert_same(y.cpu().numpy(), want, f"independent layer {i} {shapes[i]}")
+    assert_same(y_last.cpu().numpy(),
+                oracle.pw_conv(want0, last.weight, last.bias, last.mult, last.shift, -128, 127), "dependent last layer")
+
+
 def test_pixel_tile_plans_agree_on_a_full_size_layer(P):
     """Regression: with two or four pixel tiles per step the 16-byte output stores of one step
     follow each other closely, and the registers of a store were once reused before the store had
