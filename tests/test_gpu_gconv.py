@@ -208,16 +208,17 @@ def test_gconv_sequence_errors_and_empty(P):
     assert err.value.code == -3
 
 
-@pytest.mark.parametrize("family", ["regnetx_400mf", "resnext50_32x4d"])
-def test_gconv_sequence_at_benchmark_size_equals_layer_by_layer(P, family):
+@pytest.mark.parametrize("family,batch", [("regnetx_400mf", 128), ("resnext50_32x4d", 128),
+                                          ("regnetx_400mf", 256), ("regnetx_400mf", 48)])
+def test_gconv_sequence_at_benchmark_size_equals_layer_by_layer(P, family, batch):
     """The shared launches of the benchmark's configuration (batch 128, every grouped 3x3 layer of the
     network in one call: workgroup shares, XCD-aware order and padding as timed there) give, byte for
     byte, what the layers give one by one (the single-layer path is checked against the oracle above,
-    one full-size layer on every output)."""
+    one full-size layer on every output).  Also at batch 256, where layers hand workgroups on to the
+    layer that would end last, and at a batch that is no multiple of 64."""
     torch = torch_cuda()
     from workloads import regnetx_400mf_grouped_layers, resnext50_32x4d_grouped_layers
     shapes = regnetx_400mf_grouped_layers() if family == "regnetx_400mf" else resnext50_32x4d_grouped_layers()
-    batch = 128
     entries, singles = [], []
     for i, g in enumerate(shapes):
         G = make_gconv_layer(16000 + i, 1, 4, 4, g.c, g.gs, g.stride, shift_range=(8, 17) if i % 3 else (0, 31))
