@@ -53,14 +53,16 @@ def _sample_rows(m, rng):
     return np.unique(np.concatenate([fixed, rng.integers(0, m, size=700)]))
 
 
+@pytest.mark.parametrize("batch", [128, 32])
 @pytest.mark.parametrize("family", sorted(FAMILIES))
-def test_sequence_at_batch128_sampled_rows(P, family):
+def test_sequence_at_batch128_sampled_rows(P, family, batch):
     """The configuration the benchmark leg times: all unique shapes at batch 128 through one
-    prom_pw_conv_sequence call (independent layers: the library may share launches)."""
+    prom_pw_conv_sequence call (independent layers: the library may share launches).  Also at
+    batch 32, where the shared launches take smaller pieces and layers with a thousand and more
+    input channels leave the kernel for wide layers and may share a launch."""
     torch = torch_cuda()
     rng = np.random.default_rng(12)
     shapes = unique_shapes(FAMILIES[family][0]())
-    batch = 128
     inputs, layers = [], []
     for i, s in enumerate(shapes):
         window = (-128, 127) if s.residual else (0, 127)
