@@ -1050,6 +1050,32 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                 double cost[kGconvMaxBatch];
                 int per_cb[kGconvMaxBatch], step[kGconvMaxBatch];
                 double cost_sum = 0;
+                // Small images: a layer alone takes no more images per unit of work than leaves a
+                // workgroup for every compute unit; here a layer has a dozen workgroups whatever it
+                // does, and takes as many images per unit as cost least per image by the same
+                // estimate (7x7: seven instead of three, 14x14: two instead of one).
+                for (int k = 0; k < n; ++k) {
+                    GconvLaunch &L = prepared[(size_t)(i + k)];
+                    GconvBand &bd = L.bd;
+                    if (bd.bands != 1) continue;
+                    const int band_bytes = kind == GconvLaunch::TAPK ? kTapkPieces * kTapkThreads * 16 : kGconvPieces * 256 * 16;
+                    const int image_bytes = bd.RI * (L.a.W + 2) * 64;
+                    int gmax = band_bytes / image_bytes;
+                    if (gmax > 16) gmax = 16;
+                    if (gmax > L.a.N) gmax = L.a.N;
+                    auto per_image = [&](int g) {
+                        const int rounds = ((g * bd.R * L.a.Wo + 31) / 32 + 3) / 4;
+                        return (2.0 + 1.3 * rounds) / g;
+                    };
+                    int best = bd.G;
+                    for (int g = 1; g <= gmax; ++g)
+                        if (per_image(g) < 0.98 * per_image(best)) best = g;
+                    if (best != bd.G) {
+                        L.lds = L.lds - (size_t)bd.G * image_bytes + (size_t)best * image_bytes;
+                        bd.G = best;
+                        bd.units = (L.a.N + best - 1) / best;
+                    }
+                }
                 for (int k = 0; k < n; ++k) {
                     const GconvLaunch &L = prepared[(size_t)(i + k)];
                     const int npix = (L.bd.G > 1 ? L.bd.G : 1) * L.bd.R * L.a.Wo;
@@ -1057,10 +1083,13 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                     cost[k] = (double)L.bd.ncb * L.bd.units * (2.0 + 1.3 * rounds);
                     cost_sum += cost[k];
                 }
+                // (three per compute unit would fit LDS and registers of the tap-in-k kernel: 108-114
+                // against 91 us for RegNetX-400MF's 22 layers, 301-313 against 264 for ResNeXt-50's)
+                constexpr int slots = kGconvBatchSlots;
                 int used = 0;
                 for (int k = 0; k < n; ++k) {
                     const GconvBand &bd = prepared[(size_t)(i + k)].bd;
-                    const double ideal = kGconvBatchSlots * cost[k] / cost_sum / bd.ncb;
+                    const double ideal = slots * cost[k] / cost_sum / bd.ncb;
                     // several channel blocks and enough workgroups: multiples of 8, for the XCD-aware order
                     step[k] = (bd.ncb > 1 && ideal >= 8 && bd.units >= 8) ? 8 : 1;
                     int w = (int)(ideal / step[k]) * step[k];
@@ -1074,7 +1103,7 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                     double best_life = 0;
                     for (int k = 0; k < n; ++k) {
                         const GconvBand &bd = prepared[(size_t)(i + k)].bd;
-                        if (per_cb[k] + step[k] > bd.units || used + step[k] * bd.ncb > kGconvBatchSlots) continue;
+                        if (per_cb[k] + step[k] > bd.units || used + step[k] * bd.ncb > slots) continue;
                         const double life = cost[k] / ((double)per_cb[k] * bd.ncb);
                         if (best < 0 || life > best_life) {
                             best = k;
@@ -1091,7 +1120,7 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                 // that would end a quarter sooner even without them (RegNetX-400MF at batch 256: 174
                 // against 223 us; with any gain taken, batch 32 and 128 lose 3-6 %: the estimate is
                 // no finer than that).
-                for (int pass = 0; pass < 4 * kGconvBatchSlots; ++pass) {
+                for (int pass = 0; pass < 4 * slots; ++pass) {
                     int last = -1;
                     double last_life = 0;
                     for (int k = 0; k < n; ++k) {
@@ -1105,7 +1134,7 @@ extern "C" int prom_gconv3x3_sequence(const prom_gconv_layer_t *layers, int coun
                     if (per_cb[last] + step[last] > lb.units) break;
                     int trial[kGconvMaxBatch];
                     for (int k = 0; k < n; ++k) trial[k] = per_cb[k];
-                    int need = step[last] * lb.ncb - (kGconvBatchSlots - used);
+                    int need = step[last] * lb.ncb - (slots - used);
                     while (need > 0) {
                         int donor = -1;
                         double donor_life = 0;
